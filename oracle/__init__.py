@@ -1,0 +1,13 @@
+"""TEST INFRASTRUCTURE -- the CPU oracle (patch-by-patch scanning, fp64).
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package.  It shares no code with the HIP path and imports nothing from it.
+
+  patchscan.c   literal patch-by-patch forward / backward through the original
+                strided CNN (paper Sec. 1.1, Fig. 1(a), Sec. 4.3)
+  scan.py       ctypes binding + image padding (Sec. 3.3) + high-level helpers
+  loss.py       masked softmax cross-entropy and its error map (Sec. 4.3 mask)
+"""
+from .scan import (build, pad_image, pack_params, unpack_params, patch_forward,  # noqa: F401
+                   scan_forward, scan_backward, num_threads, geometry)
+from .loss import masked_softmax_xent  # noqa: F401

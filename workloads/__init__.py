@@ -1,0 +1,9 @@
+"""Seeded synthetic workloads shared by the CPU oracle's tests and the HIP path's tests.
+
+This package holds network descriptions (the ORIGINAL strided patch CNNs) and
+seeded random tensors only.  It contains none of the method's arithmetic: no
+convolution, pooling, dilation planning, padding or loss code lives here.
+"""
+from .nets import Layer, Net, conv, maxpool, avgpool, CONFIGS, config_net  # noqa: F401
+from .gen import (Workload, make_workload, make_params, pick_mask, sample_pixels,
+                  config_workload)  # noqa: F401

@@ -1,0 +1,200 @@
+/*
+ * libdsk -- whole-image forward / backward propagation of a patch-classification
+ * CNN with d-regularly sparse kernels, for AMD MI355X (gfx950).
+ *
+ * Every stride-s convolution, pooling and fully connected layer of the original
+ * patch CNN becomes a stride-1 layer whose k x k kernel has its neighbouring
+ * entries d pixels apart (paper Sec. 3.2); Algorithm 1 gives d per layer.  One
+ * pass over the padded image then yields, at every pixel, what the original CNN
+ * yields on the patch around that pixel, and one backward pass with a pixel mask
+ * on the last error map yields the summed gradients of the masked patches
+ * (Sec. 4).  The zeros of the sparse kernels are never stored or multiplied: a
+ * layer is described by its dense k x k kernel and the spacing d.
+ *
+ * Conventions (all entry points unless stated otherwise)
+ *   - Tensors are dense, row-major NCHW (W fastest).  H, W in a call are the
+ *     INPUT map's size; the output is Ho = H-(kh-1)*d by Wo = W-(kw-1)*d.
+ *   - Pointers are DEVICE pointers owned by the caller, base-aligned to 16 bytes.
+ *     The library never allocates, frees, copies to the host or synchronises; all
+ *     work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default).
+ *   - Outputs are overwritten.  Inputs and outputs must not alias unless stated.
+ *   - Weights w[K][C][kh][kw], bias b[K], their gradients, the loss and the last
+ *     error map are always fp32.  `in` / `out` / `t` give the type of the
+ *     activation tensors: DSK_F32, or DSK_BF16 (bfloat16 storage; products are
+ *     accumulated in fp32, weights are rounded to bf16 inside the kernel).
+ *   - Arguments are validated before anything is launched, so every error below
+ *     except DSK_ELAUNCH is returned without touching the GPU.  No exceptions
+ *     cross this boundary; apart from the diagnostic switch dsk_set_conv_algo the
+ *     library keeps no state and calls are re-entrant.
+ *   - Return value: DSK_OK (0) or a negative dsk_status.
+ */
+#ifndef DSK_H
+#define DSK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DSK_OK = 0,
+    DSK_EINVAL = -1,     /* null / misaligned pointer, N,C,K,k < 1, d < 1, bad enum value   */
+    DSK_ESHAPE = -2,     /* output would be empty, k*k > 255 (pool), tensor over 2^31-1 elements */
+    DSK_EDTYPE = -3,     /* dtype combination not supported by this entry point            */
+    DSK_EWORKSPACE = -4, /* workspace NULL or smaller than dsk_*_workspace_bytes says      */
+    DSK_ELAUNCH = -5     /* the HIP runtime reported an error at launch                    */
+} dsk_status;
+
+typedef enum { DSK_F32 = 0, DSK_BF16 = 1 } dsk_dtype;
+typedef enum { DSK_ACT_NONE = 0, DSK_ACT_RELU = 1, DSK_ACT_TANH = 2 } dsk_act;
+typedef enum { DSK_CONV = 0, DSK_MAXPOOL = 1, DSK_AVGPOOL = 2 } dsk_kind;
+
+/* ------------------------------------------------------------------------- */
+/* Host-side planner: Algorithm 1's bookkeeping.  HOST pointers, no GPU use.   */
+/* ------------------------------------------------------------------------- */
+
+/* One layer of the ORIGINAL strided patch CNN.  A fully connected layer is a
+ * conv whose kernel covers the whole remaining map (Sec. 3.4, last paragraph). */
+typedef struct {
+    int kind; /* dsk_kind */
+    int K;    /* conv: output channels; pools: ignored */
+    int k;    /* square kernel size */
+    int s;    /* stride in the original CNN */
+    int act;  /* conv: dsk_act applied to the output */
+} dsk_layer;
+
+/* The same layer in the whole-image network: stride 1, kernel spacing d. */
+typedef struct {
+    int kind, act;
+    int C, K;         /* input / output channels */
+    int k, d;         /* kernel size and spacing (Algorithm 1: d = product of earlier strides) */
+    int H, W;         /* input map size */
+    int Ho, Wo;       /* output map size = H-(k-1)*d, W-(k-1)*d */
+} dsk_layer_plan;
+
+/* Algorithm 1 for an image of H x W pixels with C0 channels.  Fills out[0..L-1].
+ *   *rf       receptive field 1 + sum (k-1)*d: the patch size for which the
+ *             original CNN ends in a 1 x 1 map when all its strides divide evenly
+ *   n         declared patch size of the original CNN, or 0 to use *rf.  n > *rf
+ *             (strides that do not divide evenly: the original CNN ignores the
+ *             trailing rows/columns of its patch) is allowed, n < *rf is DSK_ESHAPE
+ *   *pad_lo   zero rows/columns to add on the top/left  = floor(n/2)      (Sec. 3.3)
+ *   *pad_hi   ... on the bottom/right = *rf - 1 - *pad_lo, so that the padded
+ *             image is (H + *rf - 1) x (W + *rf - 1) and the last map is H x W
+ * Any of rf / pad_lo / pad_hi may be NULL.  Errors: DSK_EINVAL, DSK_ESHAPE. */
+int dsk_plan(const dsk_layer *layers, int L, int C0, int H, int W, int n,
+             dsk_layer_plan *out, int *rf, int *pad_lo, int *pad_hi);
+
+const char *dsk_status_string(int status);
+
+/* ------------------------------------------------------------------------- */
+/* Image padding (Sec. 3.3): once, at the input only.                          */
+/* ------------------------------------------------------------------------- */
+
+/* xpad[N][C][H+lo+hi][W+lo+hi] (type `out`) = zero-padded copy of the fp32 image
+ * x[N][C][H][W]: lo zero rows/columns on the top/left, hi on the bottom/right. */
+int dsk_pad_image(const float *x, void *xpad, int N, int C, int H, int W,
+                  int lo, int hi, dsk_dtype out, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Stride-1 convolution with a d-regularly sparse kernel (Sec. 3.1-3.2, Alg. 1) */
+/* ------------------------------------------------------------------------- */
+
+typedef enum { DSK_WS_CONV_FWD = 0, DSK_WS_CONV_BWD_DATA = 1, DSK_WS_CONV_BWD_WEIGHT = 2 } dsk_ws_which;
+
+/* Bytes of scratch device memory the matching conv call needs (0 is possible). */
+size_t dsk_conv_workspace_bytes(int which, int N, int C, int H, int W, int K,
+                                int kh, int kw, int d, dsk_dtype in);
+
+/* Forward, y_k = W_{k,d} *^1 x_k + b_k followed by the non-linearity:
+ *   y[n][f][u][v] = act( b[f] + sum_{c,a,b} w[f][c][a][b] * x[n][c][u+a*d][v+b*d] )
+ * x[N][C][H][W] (`in`), y[N][K][Ho][Wo] (`out`), b may be NULL (no bias). */
+int dsk_conv_fwd(const void *x, const float *w, const float *b, void *y,
+                 int N, int C, int H, int W, int K, int kh, int kw, int d,
+                 dsk_dtype in, dsk_dtype out, dsk_act act,
+                 void *ws, size_t ws_bytes, void *stream);
+
+/* Error map of the layer's input (Sec. 4.1): delta_k = pad(delta_{k+1}) *^1 rot180(W_{k,d}),
+ *   dx[n][c][p][q] = sum_{f,a,b} dy[n][f][p-a*d][q-b*d] * w[f][c][a][b]   (dy = 0 outside its map)
+ * dy[N][K][Ho][Wo] (`in`), dx[N][C][H][W] (`out`). */
+int dsk_conv_bwd_data(const void *dy, const float *w, void *dx,
+                      int N, int C, int H, int W, int K, int kh, int kw, int d,
+                      dsk_dtype in, dsk_dtype out,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* Gradients of the non-zero kernel entries and of the bias (Sec. 4.1):
+ *   dw[f][c][a][b] = sum_{n,u,v} dy[n][f][u][v] * x[n][c][u+a*d][v+b*d]
+ *   db[f]          = sum_{n,u,v} dy[n][f][u][v]                       (db may be NULL)
+ * x and dy have type `in`; dw, db are fp32.  The summation order is fixed: two
+ * calls on the same input give bit-identical results. */
+int dsk_conv_bwd_weight(const void *x, const void *dy, float *dw, float *db,
+                        int N, int C, int H, int W, int K, int kh, int kw, int d,
+                        dsk_dtype in, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Stride-1 pooling with a d-regularly sparse k x k kernel (Sec. 3.1-3.2, 4.2)  */
+/* ------------------------------------------------------------------------- */
+
+/* y[n][c][u][v] = max_{a,b} x[n][c][u+a*d][v+b*d]; argmax[n][c][u][v] = a*k+b of the
+ * winner ("the index within every patch", Sec. 4.2).  Taps are visited in the
+ * order a*k+b and replace the running maximum only when strictly greater, so the
+ * lowest index wins ties (and -0.0 == +0.0).  NaN inputs are unsupported.
+ * argmax may be NULL (inference).  Needs k*k <= 255. */
+int dsk_maxpool_fwd(const void *x, void *y, uint8_t *argmax,
+                    int N, int C, int H, int W, int k, int d, dsk_dtype t, void *stream);
+
+/* Errors accumulate at the recorded locations (Sec. 4.2):
+ *   dx[n][c][p][q] = sum_{a,b} [argmax[n][c][p-a*d][q-b*d] == a*k+b] * dy[n][c][p-a*d][q-b*d]
+ * Gather form, fixed summation order, no atomics. */
+int dsk_maxpool_bwd(const void *dy, const uint8_t *argmax, void *dx,
+                    int N, int C, int H, int W, int k, int d, dsk_dtype t, void *stream);
+
+/* y = mean of the k*k taps (divisor always k*k: no padding exists inside the net). */
+int dsk_avgpool_fwd(const void *x, void *y,
+                    int N, int C, int H, int W, int k, int d, dsk_dtype t, void *stream);
+
+/* dx[n][c][p][q] = (1/k^2) sum_{a,b} dy[n][c][p-a*d][q-b*d]: a mean filter (Sec. 4.2). */
+int dsk_avgpool_bwd(const void *dy, void *dx,
+                    int N, int C, int H, int W, int k, int d, dsk_dtype t, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Point-wise non-linearity, backward (Sec. 1: the non-linearity layer)        */
+/* ------------------------------------------------------------------------- */
+
+/* In place: dy[i] *= act'(.) expressed through the layer's OUTPUT y:
+ * ReLU: [y > 0];  tanh: 1 - y*y;  none: no-op.  y and dy have type t. */
+int dsk_act_bwd(const void *y, void *dy, size_t count, dsk_act act, dsk_dtype t, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Last layer: masked softmax cross-entropy (pixel mask of Sec. 4.3)           */
+/* ------------------------------------------------------------------------- */
+
+size_t dsk_softmax_xent_workspace_bytes(int N, int Cls, int H, int W);
+
+/* scores[N][Cls][H][W] fp32, labels[N][H][W] int32 in [0, Cls), mask[N][H][W] u8.
+ *   p       = softmax over classes at each pixel (row maximum subtracted)
+ *   count   = number of pixels with mask != 0 in the whole batch
+ *   loss[0] = -(1/count) * sum_{mask != 0} log p[label]        (0 if count == 0)
+ *   dscores = (mask != 0) * (p - onehot(label)) / count        (0 if count == 0)
+ *             [N][Cls][H][W], stored in type `dt` (the arithmetic is fp32 either way)
+ * Errors of unchosen pixels are exactly zero; cost does not depend on the mask.
+ * A label outside [0, Cls) at a chosen pixel is the caller's error (the pixel
+ * then contributes p as its error and nothing to the loss).  loss: 1 device float. */
+int dsk_masked_softmax_xent(const float *scores, const int32_t *labels, const uint8_t *mask,
+                            float *loss, void *dscores, dsk_dtype dt, int N, int Cls, int H, int W,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Kernel selection (diagnostics)                                              */
+/* ------------------------------------------------------------------------- */
+
+/* 0 = automatic (matrix-core kernels where they apply), 1 = force the plain
+ * one-thread-per-output kernels.  Process-wide; returns the previous value. */
+int dsk_set_conv_algo(int algo);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSK_H */

@@ -254,11 +254,12 @@ int orc_patch_forward(const orc_layer *L, int nL, int C0, int n, const double *p
 
 /* Forward scan.  xpad: [N][C0][Hp][Wp] (already padded); pix: [P][3] = (image,
  * i, j) in UNPADDED pixel coordinates; the patch of (i, j) is padded rows
- * i..i+n-1, columns j..j+n-1.  scores: [P][classes].  The net must reduce the
- * patch to 1 x 1.  Returns 0, or -1 on a malformed net / out-of-range pixel. */
+ * i..i+n-1, columns j..j+n-1.  scores: [P][classes].  last_amax (may be NULL):
+ * [P][classes] winning tap indices when the last layer is a max pool.  The net
+ * must reduce the patch to 1 x 1.  Returns 0, or -1 on a malformed net / out-of-range pixel. */
 int orc_scan_forward(const orc_layer *L, int nL, int C0, int n, const double *params,
                      const double *xpad, int N, int Hp, int Wp,
-                     const int *pix, long P, double *scores)
+                     const int *pix, long P, double *scores, int *last_amax)
 {
     orc_geom g;
     if (geom_build(L, nL, C0, n, &g) || g.m[nL] != 1) return -1;
@@ -270,18 +271,22 @@ int orc_scan_forward(const orc_layer *L, int nL, int C0, int n, const double *pa
 #pragma omp parallel
     {
         double *acts = (double *)malloc(sizeof(double) * (size_t)g.act_off[nL + 1]);
-        if (!acts) {
+        int *amax = last_amax ? (int *)malloc(sizeof(int) * (size_t)g.act_off[nL + 1]) : NULL;
+        if (!acts || (last_amax && !amax)) {
 #pragma omp atomic write
             fail = 1;
         }
 #pragma omp for schedule(dynamic, 1)
         for (long p = 0; p < P; ++p) {
-            if (!acts) continue;
+            if (!acts || (last_amax && !amax)) continue;
             crop_patch(xpad, C0, Hp, Wp, n, pix[3 * p], pix[3 * p + 1], pix[3 * p + 2], acts);
-            patch_forward(L, &g, params, acts, NULL);
+            patch_forward(L, &g, params, acts, amax);
             memcpy(scores + p * cls, acts + g.act_off[nL], sizeof(double) * (size_t)cls);
+            if (last_amax)
+                memcpy(last_amax + p * cls, amax + g.act_off[nL], sizeof(int) * (size_t)cls);
         }
         free(acts);
+        free(amax);
     }
     return fail ? -2 : 0;
 }

@@ -44,7 +44,7 @@ def _load():
         lib.orc_sizes.argtypes = [Lp, ci, ci, ci, lp, lp, ip, ip]
         lib.orc_geometry.argtypes = [Lp, ci, ci, ci, ip, ip, lp, lp]
         lib.orc_patch_forward.argtypes = [Lp, ci, ci, ci, dp, dp, dp, ip]
-        lib.orc_scan_forward.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp]
+        lib.orc_scan_forward.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp, ip]
         lib.orc_scan_backward.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp, dp, dp]
         lib.orc_num_threads.restype = ci
         _lib = lib
@@ -156,8 +156,9 @@ def patch_forward(net, params, patch):
     return maps, ams
 
 
-def scan_forward(net, params, xpad, pix):
-    """Scores [P, classes] of the patches at pix [P, 3] = (image, i, j)."""
+def scan_forward(net, params, xpad, pix, want_argmax=False):
+    """Scores [P, classes] of the patches at pix [P, 3] = (image, i, j).  With
+    want_argmax (last layer a max pool) also the winning tap indices [P, classes]."""
     lib = _load()
     g = geometry(net)
     if g["m_last"] != 1:
@@ -170,11 +171,13 @@ def scan_forward(net, params, xpad, pix):
     N, C0, Hp, Wp = xpad.shape
     assert C0 == net.C0
     out = np.zeros((pix.shape[0], g["classes"]), np.float64)
+    am = np.zeros((pix.shape[0], g["classes"]), np.int32) if want_argmax else None
     rc = lib.orc_scan_forward(arr, nL, net.C0, net.patch, _dptr(params), _dptr(xpad),
-                              N, Hp, Wp, _iptr(pix), pix.shape[0], _dptr(out))
+                              N, Hp, Wp, _iptr(pix), pix.shape[0], _dptr(out),
+                              _iptr(am) if want_argmax else None)
     if rc:
         raise ValueError("orc_scan_forward failed: %d" % rc)
-    return out
+    return (out, am) if want_argmax else out
 
 
 def scan_backward(net, params, xpad, pix, delta, want_dx=False):

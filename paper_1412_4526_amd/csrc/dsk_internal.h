@@ -1,0 +1,99 @@
+// Internal declarations shared by libdsk's translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dsk.h"
+
+namespace dsk {
+
+// bfloat16 storage type: the upper 16 bits of an IEEE fp32.
+struct bf16 {
+    uint16_t v;
+};
+
+__host__ __device__ inline float bf16_to_f32(bf16 h)
+{
+    union { uint32_t u; float f; } c;
+    c.u = (uint32_t)h.v << 16;
+    return c.f;
+}
+
+// round-to-nearest-even; NaN stays NaN (quiet)
+__host__ __device__ inline bf16 f32_to_bf16(float f)
+{
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    bf16 h;
+    if ((c.u & 0x7fffffffu) > 0x7f800000u) {
+        h.v = (uint16_t)((c.u >> 16) | 0x0040u);
+    } else {
+        c.u += 0x7fffu + ((c.u >> 16) & 1u);
+        h.v = (uint16_t)(c.u >> 16);
+    }
+    return h;
+}
+
+__device__ inline float ldf(const float *p, long i) { return p[i]; }
+__device__ inline float ldf(const bf16 *p, long i) { return bf16_to_f32(p[i]); }
+__device__ inline void stf(float *p, long i, float v) { p[i] = v; }
+__device__ inline void stf(bf16 *p, long i, float v) { p[i] = f32_to_bf16(v); }
+
+// value a kernel computing in type T sees for an fp32 weight
+template <typename T> __device__ inline float round_w(float w);
+template <> __device__ inline float round_w<float>(float w) { return w; }
+template <> __device__ inline float round_w<bf16>(float w) { return bf16_to_f32(f32_to_bf16(w)); }
+
+__device__ inline float act_apply(int act, float z)
+{
+    if (act == DSK_ACT_RELU) return z > 0.f ? z : 0.f;
+    if (act == DSK_ACT_TANH) return tanhf(z);
+    return z;
+}
+
+struct ConvShape {
+    int N, C, H, W, K, kh, kw, d, Ho, Wo;
+};
+
+// ---- plain one-thread-per-output kernels (dsk_direct.hip) ----
+int launch_conv_fwd_direct(const void *x, const float *w, const float *b, void *y, const ConvShape &s,
+                           dsk_dtype in, dsk_dtype out, int act, hipStream_t st);
+int launch_conv_bwd_data_direct(const void *dy, const float *w, void *dx, const ConvShape &s,
+                                dsk_dtype in, dsk_dtype out, hipStream_t st);
+int launch_conv_bwd_weight_direct(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
+                                  dsk_dtype in, hipStream_t st);
+
+// ---- matrix-core (MFMA) kernels (dsk_conv_mfma.hip) ----
+size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in);
+bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype out);
+int launch_conv_fwd_mfma(const void *x, const float *w, const float *b, void *y, const ConvShape &s,
+                         dsk_dtype in, dsk_dtype out, int act, void *ws, hipStream_t st);
+int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const ConvShape &s,
+                              dsk_dtype in, dsk_dtype out, void *ws, hipStream_t st);
+int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
+                                dsk_dtype in, void *ws, hipStream_t st);
+
+// ---- pooling, padding, activation, loss (dsk_pool.hip, dsk_misc.hip, dsk_loss.hip) ----
+int launch_maxpool_fwd(const void *x, void *y, uint8_t *am, int N, int C, int H, int W, int k, int d,
+                       dsk_dtype t, hipStream_t st);
+int launch_maxpool_bwd(const void *dy, const uint8_t *am, void *dx, int N, int C, int H, int W, int k, int d,
+                       dsk_dtype t, hipStream_t st);
+int launch_avgpool_fwd(const void *x, void *y, int N, int C, int H, int W, int k, int d, dsk_dtype t,
+                       hipStream_t st);
+int launch_avgpool_bwd(const void *dy, void *dx, int N, int C, int H, int W, int k, int d, dsk_dtype t,
+                       hipStream_t st);
+int launch_pad_image(const float *x, void *xpad, int N, int C, int H, int W, int lo, int hi, dsk_dtype out,
+                     hipStream_t st);
+int launch_act_bwd(const void *y, void *dy, size_t count, int act, dsk_dtype t, hipStream_t st);
+size_t softmax_xent_ws_bytes(long pixels);
+int launch_masked_softmax_xent(const float *scores, const int32_t *labels, const uint8_t *mask, float *loss,
+                               void *dscores, dsk_dtype dt, int N, int Cls, int H, int W, void *ws,
+                               hipStream_t st);
+
+inline int check_launch()
+{
+    return hipGetLastError() == hipSuccess ? DSK_OK : DSK_ELAUNCH;
+}
+
+} // namespace dsk

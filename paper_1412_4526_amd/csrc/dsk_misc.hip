@@ -1,0 +1,62 @@
+// Image padding (paper Sec. 3.3) and the backward of the point-wise
+// non-linearity layer.  Both are pure streaming kernels.
+#include "dsk_internal.h"
+
+namespace dsk {
+
+static constexpr int kThreads = 256;
+
+template <typename TO>
+__global__ void __launch_bounds__(kThreads)
+pad_image_kernel(const float *__restrict__ x, TO *__restrict__ xp, long planes, int H, int W, int lo, int Hp, int Wp)
+{
+    const long total = planes * Hp * Wp;
+    const long idx = (long)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= total) return;
+    const int q = (int)(idx % Wp);
+    const int p = (int)((idx / Wp) % Hp);
+    const long plane = idx / ((long)Wp * Hp);
+    const int i = p - lo, j = q - lo;
+    float v = 0.f;
+    if (i >= 0 && i < H && j >= 0 && j < W) v = x[(plane * H + i) * W + j];
+    stf(xp, idx, v);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+act_bwd_kernel(const T *__restrict__ y, T *__restrict__ dy, size_t count, int act)
+{
+    const size_t idx = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= count) return;
+    const float yv = ldf(y, (long)idx);
+    const float g = ldf(dy, (long)idx);
+    const float f = (act == DSK_ACT_RELU) ? (yv > 0.f ? 1.f : 0.f) : (1.f - yv * yv);
+    stf(dy, (long)idx, g * f);
+}
+
+int launch_pad_image(const float *x, void *xpad, int N, int C, int H, int W, int lo, int hi, dsk_dtype out,
+                     hipStream_t st)
+{
+    const int Hp = H + lo + hi, Wp = W + lo + hi;
+    const long planes = (long)N * C;
+    const long total = planes * Hp * Wp;
+    dim3 g((unsigned)((total + kThreads - 1) / kThreads)), t(kThreads);
+    if (out == DSK_F32)
+        pad_image_kernel<float><<<g, t, 0, st>>>(x, (float *)xpad, planes, H, W, lo, Hp, Wp);
+    else
+        pad_image_kernel<bf16><<<g, t, 0, st>>>(x, (bf16 *)xpad, planes, H, W, lo, Hp, Wp);
+    return check_launch();
+}
+
+int launch_act_bwd(const void *y, void *dy, size_t count, int act, dsk_dtype t, hipStream_t st)
+{
+    if (act == DSK_ACT_NONE || count == 0) return DSK_OK;
+    dim3 g((unsigned)((count + kThreads - 1) / kThreads)), th(kThreads);
+    if (t == DSK_F32)
+        act_bwd_kernel<float><<<g, th, 0, st>>>((const float *)y, (float *)dy, count, act);
+    else
+        act_bwd_kernel<bf16><<<g, th, 0, st>>>((const bf16 *)y, (bf16 *)dy, count, act);
+    return check_launch();
+}
+
+} // namespace dsk

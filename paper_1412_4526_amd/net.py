@@ -1,0 +1,126 @@
+"""Whole-image forward / backward of a patch CNN: chains the libdsk calls in the
+order Algorithm 1 (forward) and Sec. 4 (backward) of the paper prescribe.  This
+file only sequences library calls on preallocated device buffers; all arithmetic
+runs in the library's kernels.
+"""
+import torch
+
+from . import binding as B
+
+
+class WholeImageNet:
+    """The stride-1, d-regularly-sparse version of an original strided patch CNN,
+    bound to one image batch shape.
+
+    net: object with C0, patch, layers (each: kind, K, k, s, act) -- the ORIGINAL CNN.
+    dtype: "f32", or "bf16" (activations and error maps stored in bfloat16, fp32
+    accumulation; scores, loss, weights and their gradients stay fp32).
+    """
+
+    def __init__(self, net, N, H, W, dtype="f32", device="cuda:0", train=True):
+        self.net, self.N, self.H, self.W = net, N, H, W
+        self.device = torch.device(device)
+        self.act_dtype = torch.float32 if dtype == "f32" else torch.bfloat16
+        self.code = B.DSK_F32 if dtype == "f32" else B.DSK_BF16
+        self.train = train
+        self.plan, self.rf, self.pad_lo, self.pad_hi = B.dsk_plan(net.layers, net.C0, H, W, net.patch)
+        L = len(self.plan)
+        last = self.plan[-1]
+        if (last.Ho, last.Wo) != (H, W):
+            raise ValueError("plan does not end at the image size")
+        dev = self.device
+        Hp, Wp = H + self.pad_lo + self.pad_hi, W + self.pad_lo + self.pad_hi
+        self.xpad = torch.empty((N, net.C0, Hp, Wp), dtype=self.act_dtype, device=dev)
+        self.maps = [self.xpad]          # maps[l] = input of layer l; maps[L] = scores
+        self.argmax = [None] * L
+        ws_bytes = 0
+        for l, p in enumerate(self.plan):
+            out_dtype = torch.float32 if l == L - 1 else self.act_dtype
+            self.maps.append(torch.empty((N, p.K, p.Ho, p.Wo), dtype=out_dtype, device=dev))
+            if p.kind == B.DSK_MAXPOOL and train:
+                self.argmax[l] = torch.empty((N, p.K, p.Ho, p.Wo), dtype=torch.uint8, device=dev)
+            if p.kind == B.DSK_CONV:
+                shape = (N, p.C, p.H, p.W, p.K, p.k, p.k, p.d)
+                whiches = (B.DSK_WS_CONV_FWD, B.DSK_WS_CONV_BWD_DATA, B.DSK_WS_CONV_BWD_WEIGHT) if train \
+                    else (B.DSK_WS_CONV_FWD,)
+                for which in whiches:
+                    ws_bytes = max(ws_bytes, B.dsk_conv_workspace_bytes(which, *shape, self.code))
+        self.scores = self.maps[-1]
+        self.weights, self.biases = [], []
+        for p in self.plan:
+            if p.kind == B.DSK_CONV:
+                self.weights.append(torch.zeros((p.K, p.C, p.k, p.k), dtype=torch.float32, device=dev))
+                self.biases.append(torch.zeros((p.K,), dtype=torch.float32, device=dev))
+        if train:
+            ws_bytes = max(ws_bytes, B.dsk_softmax_xent_workspace_bytes(N, last.K, H, W))
+            self.loss = torch.zeros((1,), dtype=torch.float32, device=dev)
+            self.dw = [torch.empty_like(w) for w in self.weights]
+            self.db = [torch.empty_like(b) for b in self.biases]
+            # error maps: the one arriving at layer l's output and the one leaving at its input
+            # alternate between two flat buffers sized for the largest map
+            biggest = max(m.numel() for m in self.maps[1:])
+            self._g = [torch.empty(biggest, dtype=self.act_dtype, device=dev) for _ in range(2)]
+        self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    # ------------------------------------------------------------------ parameters
+    def load_params(self, weights, biases):
+        """weights / biases: sequences of arrays or tensors, one per conv layer."""
+        for dst, src in zip(self.weights, weights):
+            dst.copy_(torch.as_tensor(src, dtype=torch.float32).reshape(dst.shape))
+        for dst, src in zip(self.biases, biases):
+            dst.copy_(torch.as_tensor(src, dtype=torch.float32).reshape(dst.shape))
+
+    # ------------------------------------------------------------------ Algorithm 1
+    def forward(self, image):
+        """image: fp32 GPU tensor [N, C0, H, W] (unpadded).  Returns scores [N, Cls, H, W] fp32."""
+        B.dsk_pad_image(image, self.pad_lo, self.pad_hi, xpad=self.xpad)
+        ci = 0
+        for l, p in enumerate(self.plan):
+            x, y = self.maps[l], self.maps[l + 1]
+            if p.kind == B.DSK_CONV:
+                B.dsk_conv_fwd(x, self.weights[ci], self.biases[ci], p.d, p.act, y=y, ws=self.ws)
+                ci += 1
+            elif p.kind == B.DSK_MAXPOOL:
+                B.dsk_maxpool_fwd(x, p.k, p.d, y=y, argmax=self.argmax[l], want_argmax=self.train)
+            else:
+                B.dsk_avgpool_fwd(x, p.k, p.d, y=y)
+        return self.scores
+
+    # ------------------------------------------------------------------ Sec. 4
+    def _gbuf(self, which, like):
+        return self._g[which][:like.numel()].view(like.shape)
+
+    def loss_backward(self, labels, mask):
+        """labels int32 [N,H,W], mask uint8 [N,H,W] on the GPU; forward() must have run.
+        Returns (loss tensor [1], dw list, db list)."""
+        assert self.train
+        L = len(self.plan)
+        cur = 0
+        g = self._gbuf(cur, self.scores)
+        B.dsk_masked_softmax_xent(self.scores, labels, mask, loss=self.loss, dscores=g, ws=self.ws)
+        ci = len(self.weights) - 1
+        for l in range(L - 1, -1, -1):
+            p = self.plan[l]
+            x, y = self.maps[l], self.maps[l + 1]
+            gin = self._g[1 - cur][:x.numel()].view(x.shape) if l > 0 else None
+            if p.kind == B.DSK_CONV:
+                if p.act != B.DSK_ACT_NONE:
+                    B.dsk_act_bwd(y, g, p.act)
+                B.dsk_conv_bwd_weight(x, g, p.k, p.k, p.d, dw=self.dw[ci], db=self.db[ci], ws=self.ws)
+                if l > 0:        # nobody needs the error map of the image itself
+                    B.dsk_conv_bwd_data(g, self.weights[ci], p.d, p.H, p.W, dx=gin, ws=self.ws)
+                ci -= 1
+            elif p.kind == B.DSK_MAXPOOL:
+                B.dsk_maxpool_bwd(g, self.argmax[l], p.k, p.d, p.H, p.W, dx=gin)
+            else:
+                B.dsk_avgpool_bwd(g, p.k, p.d, p.H, p.W, dx=gin)
+            if l > 0:
+                g = gin
+                cur = 1 - cur
+        return self.loss, self.dw, self.db
+
+    # ------------------------------------------------------------------ bookkeeping for benchmarks
+    def conv_flops(self):
+        """Algorithmic FLOPs (non-zero taps only) of one forward pass over all conv layers."""
+        return sum(2.0 * self.N * p.C * p.K * p.k * p.k * p.Ho * p.Wo
+                   for p in self.plan if p.kind == B.DSK_CONV)

@@ -1,0 +1,241 @@
+"""Per-kernel parity of the HIP path (through the C-ABI) against the patch-scanning
+oracle, element by element on the same seeded inputs.  Shapes span several tiles
+of every kernel and have ragged tails; spacings d cover 1 and values that do not
+divide the tile sizes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1412_4526_amd as dsk
+from gpu_common import (assert_close, to_np, bf16_round, oracle_conv_fwd, oracle_conv_bwd,
+                        oracle_pool_fwd, oracle_pool_bwd)
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _t(a, dtype=torch.float32):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV).to(dtype).contiguous()
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# (N, C, H, W, K, k, d, act)
+CONV_CASES = [
+    (1, 3, 23, 29, 8, 5, 1, 1),        # first layer: C = 3
+    (2, 8, 40, 37, 16, 3, 2, 1),
+    (1, 16, 30, 45, 10, 2, 4, 0),      # fc as a 2x2 conv, K not a multiple of anything
+    (1, 5, 41, 33, 7, 1, 3, 2),        # 1x1, tanh
+    (1, 32, 75, 141, 64, 5, 2, 1),     # several tiles + ragged tail in both directions
+    (1, 40, 60, 92, 70, 4, 8, 1),      # C, K not multiples of 32; large spacing
+    (2, 64, 37, 70, 33, 1, 8, 0),      # 1x1 with K = 33
+    (1, 6, 64, 50, 48, 7, 1, 1),       # 7x7
+    (1, 130, 20, 90, 2, 3, 3, 0),      # K = 2, C > 128
+]
+
+
+@pytest.mark.parametrize("algo", [0, 1], ids=["auto", "direct"])
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "N%dC%dH%dW%dK%dk%dd%da%d" % c)
+def test_conv_fwd(case, algo):
+    N, C, H, W, K, k, d, act = case
+    _say("conv_fwd", case, "algo", algo)
+    rng = np.random.default_rng(hash(case) % 2**31)
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = (rng.standard_normal((K, C, k, k)) * np.sqrt(2.0 / (C * k * k))).astype(np.float32)
+    b = (rng.standard_normal(K) * 0.2).astype(np.float32)
+    ref = oracle_conv_fwd(x, w, b, d, act)
+    prev = dsk.dsk_set_conv_algo(algo)
+    try:
+        y = dsk.dsk_conv_fwd(_t(x), _t(w), _t(b), d, act)
+        y_nobias = dsk.dsk_conv_fwd(_t(x), _t(w), None, d, dsk.DSK_ACT_NONE)
+        torch.cuda.synchronize()
+    finally:
+        dsk.dsk_set_conv_algo(prev)
+    assert_close(y, ref, "conv_fwd")
+    if act == 0:
+        assert_close(y_nobias, ref - b[None, :, None, None], "conv_fwd without bias")
+
+
+@pytest.mark.parametrize("algo", [0, 1], ids=["auto", "direct"])
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "N%dC%dH%dW%dK%dk%dd%da%d" % c)
+def test_conv_bwd(case, algo):
+    N, C, H, W, K, k, d, act = case
+    _say("conv_bwd", case, "algo", algo)
+    rng = np.random.default_rng(hash(case) % 2**31 + 1)
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = (rng.standard_normal((K, C, k, k)) * np.sqrt(2.0 / (C * k * k))).astype(np.float32)
+    b = (rng.standard_normal(K) * 0.2).astype(np.float32)
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    dy = rng.standard_normal((N, K, Ho, Wo)).astype(np.float32)
+    dy[rng.random(dy.shape) < 0.5] = 0.0          # error maps are sparse after a mask
+    rdw, rdb, rdx = oracle_conv_bwd(x, w, b, d, act, dy)
+    prev = dsk.dsk_set_conv_algo(algo)
+    try:
+        xt, wt = _t(x), _t(w)
+        y = dsk.dsk_conv_fwd(xt, wt, _t(b), d, act)
+        g = _t(dy)
+        dsk.dsk_act_bwd(y, g, act)
+        dw, db = dsk.dsk_conv_bwd_weight(xt, g, k, k, d)
+        dw2, db2 = dsk.dsk_conv_bwd_weight(xt, g, k, k, d)
+        dx = dsk.dsk_conv_bwd_data(g, wt, d, H, W)
+        torch.cuda.synchronize()
+    finally:
+        dsk.dsk_set_conv_algo(prev)
+    assert_close(dw, rdw, "dw")
+    assert_close(db, rdb, "db")
+    assert_close(dx, rdx, "dx")
+    assert torch.equal(dw, dw2) and torch.equal(db, db2), "bwd_weight is not run-to-run deterministic"
+
+
+def test_conv_bf16_variant():
+    """bf16 activations/weights, fp32 accumulate: within 2e-2 of the fp32 oracle on the
+    unrounded inputs, and within fp32 tolerance of the oracle fed the rounded inputs."""
+    N, C, H, W, K, k, d, act = 1, 32, 50, 77, 48, 3, 2, 1
+    rng = np.random.default_rng(7)
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = (rng.standard_normal((K, C, k, k)) * np.sqrt(2.0 / (C * k * k))).astype(np.float32)
+    b = (rng.standard_normal(K) * 0.2).astype(np.float32)
+    for algo in (0, 1):
+        _say("conv bf16 algo", algo)
+        prev = dsk.dsk_set_conv_algo(algo)
+        try:
+            xb = _t(x, torch.bfloat16)
+            y = dsk.dsk_conv_fwd(xb, _t(w), _t(b), d, act, out_dtype=torch.float32)
+            yb = dsk.dsk_conv_fwd(xb, _t(w), _t(b), d, act)
+            Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+            dy = rng.standard_normal((N, K, Ho, Wo)).astype(np.float32)
+            gb = _t(dy, torch.bfloat16)
+            dw, db = dsk.dsk_conv_bwd_weight(xb, gb, k, k, d)
+            dx = dsk.dsk_conv_bwd_data(gb, _t(w), d, H, W, out_dtype=torch.float32)
+            torch.cuda.synchronize()
+        finally:
+            dsk.dsk_set_conv_algo(prev)
+        assert yb.dtype == torch.bfloat16
+        assert_close(y, oracle_conv_fwd(x, w, b, d, act), "bf16 conv vs fp32 oracle", bf16=True)
+        assert_close(yb, oracle_conv_fwd(x, w, b, d, act), "bf16-out conv vs fp32 oracle", bf16=True)
+        xr, wr = bf16_round(x), bf16_round(w)
+        assert_close(y, oracle_conv_fwd(xr, wr, b, d, act), "bf16 conv vs oracle on rounded inputs")
+        rdw, rdb, rdx = oracle_conv_bwd(xr, wr, b, d, 0, bf16_round(dy))
+        assert_close(dw, rdw, "bf16 dw vs oracle on rounded inputs")
+        assert_close(db, rdb, "bf16 db vs oracle on rounded inputs")
+        assert_close(dx, rdx, "bf16 dx vs oracle on rounded inputs")
+        fdw, fdb, fdx = oracle_conv_bwd(x, w, b, d, 0, dy)
+        assert_close(dw, fdw, "bf16 dw vs fp32 oracle", bf16=True)
+        assert_close(dx, fdx, "bf16 dx vs fp32 oracle", bf16=True)
+
+
+# (N, C, H, W, k, d)
+POOL_CASES = [
+    (1, 8, 51, 51, 2, 1), (2, 5, 46, 300, 2, 2), (1, 3, 70, 530, 2, 4), (1, 4, 90, 61, 2, 8),
+    (1, 6, 64, 77, 3, 2), (2, 3, 40, 280, 3, 4), (1, 2, 60, 44, 4, 3), (1, 3, 33, 20, 8, 1),
+    (1, 2, 9, 9, 2, 8),   # d larger than the output
+]
+
+
+@pytest.mark.parametrize("case", POOL_CASES, ids=lambda c: "N%dC%dH%dW%dk%dd%d" % c)
+@pytest.mark.parametrize("ties", [False, True], ids=["random", "ties"])
+def test_maxpool_fwd_bwd(case, ties):
+    N, C, H, W, k, d = case
+    _say("maxpool", case, "ties", ties)
+    rng = np.random.default_rng(hash(case) % 2**31)
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    if ties:
+        x = np.maximum(x, 0.0)                    # ReLU output: many exact zeros (some -0.0)
+        x[rng.random(x.shape) < 0.05] = -0.0
+    ry, ram = oracle_pool_fwd(x, k, d, True)
+    y, am = dsk.dsk_maxpool_fwd(_t(x), k, d)
+    y_only, none = dsk.dsk_maxpool_fwd(_t(x), k, d, want_argmax=False)
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    dy = rng.standard_normal((N, C, Ho, Wo)).astype(np.float32)
+    dx = dsk.dsk_maxpool_bwd(_t(dy), am, k, d, H, W)
+    torch.cuda.synchronize()
+    assert none is None
+    assert np.array_equal(to_np(y), ry), "max-pool values must be exact"
+    assert np.array_equal(to_np(y_only), ry)
+    assert np.array_equal(am.cpu().numpy().astype(np.int32), ram), "argmax must be bit-exact"
+    assert_close(dx, oracle_pool_bwd(x, k, d, True, dy), "maxpool dx")
+
+
+@pytest.mark.parametrize("case", POOL_CASES, ids=lambda c: "N%dC%dH%dW%dk%dd%d" % c)
+def test_avgpool_fwd_bwd(case):
+    N, C, H, W, k, d = case
+    _say("avgpool", case)
+    rng = np.random.default_rng(hash(case) % 2**31 + 5)
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    ry, _ = oracle_pool_fwd(x, k, d, False)
+    y = dsk.dsk_avgpool_fwd(_t(x), k, d)
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    dy = rng.standard_normal((N, C, Ho, Wo)).astype(np.float32)
+    dx = dsk.dsk_avgpool_bwd(_t(dy), k, d, H, W)
+    torch.cuda.synchronize()
+    assert_close(y, ry, "avgpool y")
+    assert_close(dx, oracle_pool_bwd(x, k, d, False, dy), "avgpool dx")
+
+
+def test_pool_bf16():
+    N, C, H, W, k, d = 1, 4, 40, 150, 2, 2
+    rng = np.random.default_rng(3)
+    x = bf16_round(rng.uniform(-1, 1, (N, C, H, W)))
+    ry, ram = oracle_pool_fwd(x, k, d, True)
+    y, am = dsk.dsk_maxpool_fwd(_t(x, torch.bfloat16), k, d)
+    torch.cuda.synchronize()
+    assert y.dtype == torch.bfloat16
+    assert np.array_equal(to_np(y), ry) and np.array_equal(am.cpu().numpy().astype(np.int32), ram)
+    ya = dsk.dsk_avgpool_fwd(_t(x, torch.bfloat16), k, d)
+    assert_close(ya, oracle_pool_fwd(x, k, d, False)[0], "bf16 avgpool", bf16=True)
+
+
+@pytest.mark.parametrize("shape", [(1, 10, 40, 40), (2, 33, 37, 61), (1, 2, 50, 9), (3, 1, 5, 7)],
+                         ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("frac", [0.0, 0.1, 1.0])
+def test_masked_softmax_xent(shape, frac):
+    N, Cls, H, W = shape
+    _say("softmax", shape, frac)
+    rng = np.random.default_rng(N * 1000 + Cls)
+    scores = (rng.standard_normal(shape) * 4).astype(np.float32)
+    labels = rng.integers(0, Cls, (N, H, W)).astype(np.int32)
+    mask = (rng.random((N, H, W)) < frac).astype(np.uint8) * rng.integers(1, 255, (N, H, W)).astype(np.uint8)
+    rloss, rdelta, count = oracle.masked_softmax_xent(scores, labels, mask)
+    loss, delta = dsk.dsk_masked_softmax_xent(_t(scores), _t(labels, torch.int32), _t(mask, torch.uint8))
+    torch.cuda.synchronize()
+    assert_close(loss, np.array([rloss]), "loss")
+    assert_close(delta, rdelta, "dscores")
+    # errors of unchosen pixels are exactly zero
+    assert not to_np(delta)[np.broadcast_to((mask == 0)[:, None], shape)].any()
+    lossb, deltab = dsk.dsk_masked_softmax_xent(_t(scores), _t(labels, torch.int32), _t(mask, torch.uint8),
+                                                dscores_dtype=torch.bfloat16)
+    assert_close(deltab, rdelta, "bf16 dscores", bf16=True)
+
+
+def test_pad_image_and_act_bwd():
+    rng = np.random.default_rng(0)
+    img = rng.uniform(-1, 1, (2, 3, 17, 23)).astype(np.float32)
+    for n in (1, 6, 15):
+        lo = n // 2
+        xp = dsk.dsk_pad_image(_t(img), lo, n - 1 - lo)
+        assert np.array_equal(to_np(xp), oracle.pad_image(img, n))
+    xpb = dsk.dsk_pad_image(_t(img), 3, 2, out_dtype=torch.bfloat16)
+    assert np.array_equal(to_np(xpb)[:, :, 3:20, 3:26], bf16_round(img).astype(np.float64))
+    y = rng.uniform(-1, 1, 1000).astype(np.float32)
+    y[::7] = 0.0
+    g = rng.standard_normal(1000).astype(np.float32)
+    for act, ref in ((1, g * (y > 0)), (2, g * (1 - y.astype(np.float64) ** 2)), (0, g)):
+        gt = _t(g.copy())
+        dsk.dsk_act_bwd(_t(y), gt, act)
+        assert_close(gt, ref, "act_bwd %d" % act)
+
+
+def test_launch_errors_are_reported_not_raised_as_faults():
+    """Shapes the kernels cannot take are refused with a status before any launch."""
+    x = torch.zeros((1, 2, 8, 8), device=DEV)
+    w = torch.zeros((3, 2, 3, 3), device=DEV)
+    with pytest.raises(dsk.DskError) as e:
+        dsk.dsk_conv_fwd(x, w, None, 4)
+    assert e.value.status == dsk.DSK_ESHAPE
+    with pytest.raises(dsk.DskError) as e:
+        dsk.dsk_maxpool_fwd(x, 2, 8)
+    assert e.value.status == dsk.DSK_ESHAPE

@@ -1,0 +1,188 @@
+"""End-to-end parity: whole-image forward + masked backward on the GPU against
+literal patch-by-patch scanning by the oracle.
+
+Small networks and benchmark configuration 0 are scanned in full (every pixel,
+every gradient).  The large benchmark configurations are checked on sampled
+pixels: forward scores and per-layer intermediates (a patch-CNN entry (u, v)
+after layer l sits at whole-image position (i + D_l*u, j + D_l*v), D_l = product
+of the original strides through layer l; Fig. 3 of the paper), gradients through
+a 256-pixel test mask, and -- at the configuration's real mask density --
+linearity of the gradients in the mask (Sec. 4.3)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1412_4526_amd as dsk
+from workloads import Net, conv, maxpool, avgpool, CONFIGS, make_workload, sample_pixels
+from workloads.nets import ACT_RELU, ACT_TANH, MAXPOOL, CONV
+from gpu_common import assert_close, to_np, all_pixels, bf16_round
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+SMALL_NETS = [
+    (CONFIGS[0].net, 1, 40, 40, 0.10),                      # benchmark configuration 0, in full
+    (Net("example15", 2, 15, (conv(3, 2, 1, ACT_TANH), maxpool(2, 2), conv(4, 2, 1, ACT_RELU),
+                              maxpool(3, 3), conv(5, 2))), 2, 9, 13, 0.3),
+    (Net("s2", 2, 23, (conv(4, 3, 2, ACT_TANH), maxpool(3, 2), conv(5, 2, 1, ACT_RELU),
+                       avgpool(2, 2), conv(3, 2))), 1, 21, 17, 0.5),
+    (Net("s3", 2, 16, (conv(3, 4, 3, ACT_TANH), maxpool(2, 1), avgpool(2, 2), conv(4, 2))), 2, 11, 10, 1.0),
+    (Net("uneven", 2, 8, (maxpool(3, 2), conv(3, 3))), 1, 12, 9, 0.4),   # patch larger than the receptive field
+]
+
+
+def _oracle_full(net, wl):
+    N, _, H, W = wl.image.shape
+    params = oracle.pack_params(wl.weights, wl.biases)
+    xpad = oracle.pad_image(wl.image, net.patch)
+    pix = all_pixels(N, H, W)
+    scores = oracle.scan_forward(net, params, xpad, pix).reshape(N, H, W, -1).transpose(0, 3, 1, 2)
+    loss, delta, count = oracle.masked_softmax_xent(scores, wl.labels, wl.mask)
+    keep = wl.mask.ravel() != 0
+    d = delta.transpose(0, 2, 3, 1).reshape(-1, scores.shape[1])[keep]
+    g, _ = oracle.scan_backward(net, params, xpad, pix[keep], d)
+    dws, dbs = oracle.unpack_params(net, g)
+    return scores, loss, dws, dbs
+
+
+@pytest.mark.parametrize("case", SMALL_NETS, ids=lambda c: c[0].name)
+@pytest.mark.parametrize("algo", [0, 1], ids=["auto", "direct"])
+def test_small_nets_in_full(case, algo):
+    net, N, H, W, frac = case
+    _say("small net", net.name, "algo", algo)
+    wl = make_workload(net, N, H, W, frac, seed=0, bias_std=0.1 if net.name != "tiny16" else 0.0)
+    rscores, rloss, rdws, rdbs = _oracle_full(net, wl)
+    prev = dsk.dsk_set_conv_algo(algo)
+    try:
+        m = dsk.WholeImageNet(net, N, H, W, "f32", DEV)
+        m.load_params(wl.weights, wl.biases)
+        scores = m.forward(torch.from_numpy(wl.image).to(DEV))
+        loss, dws, dbs = m.loss_backward(torch.from_numpy(wl.labels).to(DEV), torch.from_numpy(wl.mask).to(DEV))
+        torch.cuda.synchronize()
+    finally:
+        dsk.dsk_set_conv_algo(prev)
+    assert_close(scores, rscores, "scores")
+    assert_close(loss, np.array([rloss]), "loss")
+    for i in range(len(rdws)):
+        assert_close(dws[i], rdws[i], "dw%d" % i)
+        assert_close(dbs[i], rdbs[i], "db%d" % i)
+
+
+def test_empty_mask_gives_zero_loss_and_gradients():
+    net = CONFIGS[0].net
+    wl = make_workload(net, 1, 12, 12, 0.0, seed=3)
+    m = dsk.WholeImageNet(net, 1, 12, 12, "f32", DEV)
+    m.load_params(wl.weights, wl.biases)
+    m.forward(torch.from_numpy(wl.image).to(DEV))
+    loss, dws, dbs = m.loss_backward(torch.from_numpy(wl.labels).to(DEV), torch.from_numpy(wl.mask).to(DEV))
+    torch.cuda.synchronize()
+    assert loss.item() == 0.0
+    assert all(not t.any().item() for t in dws + dbs)
+
+
+def _check_intermediates(net, m, wl, params, xpad, pix, bf16):
+    """Layer-by-layer correspondence at a few pixels, and argmax agreement."""
+    D = np.cumprod([L.s for L in net.layers])
+    flips = total = 0
+    for (n, i, j) in pix:
+        pm, pam = oracle.patch_forward(net, params, xpad[n, :, i:i + net.patch, j:j + net.patch])
+        for l in range(1, len(net.layers) + 1):
+            sz = pm[l].shape[1]
+            sl = (n, slice(None), slice(i, i + D[l - 1] * sz, D[l - 1]), slice(j, j + D[l - 1] * sz, D[l - 1]))
+            got = to_np(m.maps[l][sl])
+            scale = np.abs(pm[l]).max()
+            tol = (2e-2 * scale + 1e-6) if bf16 else (1e-4 * scale + 1e-5)
+            err = np.abs(got - pm[l]).max()
+            assert err <= tol, "layer %d at pixel %s: err %.3g tol %.3g" % (l, (n, i, j), err, tol)
+            if net.layers[l - 1].kind == MAXPOOL and m.argmax[l - 1] is not None:
+                ga = m.argmax[l - 1][sl].cpu().numpy().astype(np.int32)
+                total += ga.size
+                flips += int((ga != pam[l]).sum())
+    return flips, total
+
+
+BIG = [1, 2, 3, 4]
+
+
+@pytest.mark.parametrize("ci", BIG, ids=lambda i: "config%d" % i)
+def test_benchmark_configs_sampled(ci):
+    cfg = CONFIGS[ci]
+    net = cfg.net
+    if os.environ.get("DSK_TEST_SMALL_BIG", "0") == "1":
+        N, H, W = 1, 96, 80
+    else:
+        N, H, W = cfg.N, cfg.H, cfg.W
+    bf16 = cfg.dtype == "bf16"
+    dtypes = ["f32", "bf16"] if ci == 2 else [cfg.dtype]
+    n_fwd, n_bwd = (256, 256) if net.patch <= 67 else (96, 64)
+    _say("config", ci, net.name, N, H, W, dtypes)
+    wl = make_workload(net, N, H, W, cfg.mask_frac, cfg.seed, positive_frac=cfg.positive_frac)
+    params = oracle.pack_params(wl.weights, wl.biases)
+    xpad = oracle.pad_image(wl.image, net.patch)
+    pix = sample_pixels(N, H, W, n_fwd, seed=1)
+    rs = oracle.scan_forward(net, params, xpad, pix)
+    _say("  oracle forward done")
+    tpix = sample_pixels(N, H, W, n_bwd, seed=2)
+    tmask = np.zeros((N, H, W), np.uint8)
+    tmask[tpix[:, 0], tpix[:, 1], tpix[:, 2]] = 1
+    order = np.lexsort((tpix[:, 2], tpix[:, 1], tpix[:, 0]))
+    tpix = tpix[order]
+    image = torch.from_numpy(wl.image).to(DEV)
+    labels = torch.from_numpy(wl.labels).to(DEV)
+    for dt in dtypes:
+        b16 = dt == "bf16"
+        m = dsk.WholeImageNet(net, N, H, W, dt, DEV)
+        m.load_params(wl.weights, wl.biases)
+        scores = m.forward(image)
+        torch.cuda.synchronize()
+        _say("  gpu forward done", dt)
+        got = to_np(scores[pix[:, 0], :, pix[:, 1], pix[:, 2]])
+        assert_close(got, rs, "config %d %s scores at %d sampled pixels" % (ci, dt, len(pix)), bf16=b16)
+        flips, total = _check_intermediates(net, m, wl, params, xpad, pix[:6], b16)
+        _say("  intermediates ok; argmax flips %d of %d" % (flips, total))
+        if not b16:
+            assert flips <= total * 1e-3
+
+        # gradients through the 256-pixel test mask: the oracle uses the GPU's own error map
+        # only through its definition -- it recomputes scores, softmax and errors itself
+        rst = oracle.scan_forward(net, params, xpad, tpix)
+        smap = np.zeros((N, net.classes, H, W))
+        smap[tpix[:, 0], :, tpix[:, 1], tpix[:, 2]] = rst
+        rloss, rdelta, _ = oracle.masked_softmax_xent(smap, wl.labels, tmask)
+        rd = rdelta[tpix[:, 0], :, tpix[:, 1], tpix[:, 2]]
+        rg, _ = oracle.scan_backward(net, params, xpad, tpix, rd)
+        rdws, rdbs = oracle.unpack_params(net, rg)
+        _say("  oracle backward done")
+        loss, dws, dbs = m.loss_backward(labels, torch.from_numpy(tmask).to(DEV))
+        torch.cuda.synchronize()
+        assert_close(loss, np.array([rloss]), "loss", bf16=b16)
+        for i in range(len(rdws)):
+            assert_close(dws[i], rdws[i], "config %d %s dw%d" % (ci, dt, i), bf16=b16)
+            assert_close(dbs[i], rdbs[i], "config %d %s db%d" % (ci, dt, i), bf16=b16)
+        gT = [t.clone() for t in dws + dbs]
+
+        # real mask density: gradients are linear in the mask (Sec. 4.3):
+        # |M| g(M) = |T| g(T) + |M\T| g(M\T) for the test mask T inside M
+        M = np.maximum(wl.mask, tmask)
+        R = M * (1 - tmask)
+        nM, nT, nR = int(M.sum()), int(tmask.sum()), int(R.sum())
+        lossM, dws, dbs = m.loss_backward(labels, torch.from_numpy(M).to(DEV))
+        gM = [t.clone() for t in dws + dbs]
+        lossM = lossM.item()
+        lossR, dws, dbs = m.loss_backward(labels, torch.from_numpy(R).to(DEV))
+        gR = [t.clone() for t in dws + dbs]
+        torch.cuda.synchronize()
+        for a, t, r in zip(gM, gT, gR):
+            want = (to_np(t) * nT + to_np(r) * nR) / nM
+            assert_close(a, want, "mask linearity", bf16=b16)
+        assert abs(lossM * nM - (loss.item() * nT + lossR.item() * nR)) <= (2e-2 if b16 else 1e-4) * abs(lossM * nM) + 1e-5
+        del m
+        torch.cuda.empty_cache()

@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark: labelled pixels/s of whole-image forward + backward on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch that is already
+resident in HBM: pad -> every sparse-kernel conv / pool layer -> masked softmax
+cross-entropy -> error maps and all weight / bias gradients.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--dtype f32|bf16]
+                  [--forward-only] [--no-cpu-baseline] [--algo 0|1]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA = 157.3      # TFLOP/s, MI355X dense fp32 matrix
+PEAK_BF16_MFMA = 2500.0     # TFLOP/s, MI355X dense bf16 matrix
+PEAK_HBM = 8000.0           # GB/s
+
+
+def layer_costs(net, elem):
+    """Algorithmic work per library call: FLOPs of the non-zero taps for convs,
+    minimum bytes (each input element read once, each output written once) for the rest."""
+    import paper_1412_4526_amd as dsk
+    N, out = net.N, {}
+    L = len(net.plan)
+    for l, p in enumerate(net.plan):
+        nin, nout = N * p.C * p.H * p.W, N * p.K * p.Ho * p.Wo
+        oel = 4 if l == L - 1 else elem
+        if p.kind == dsk.DSK_CONV:
+            fl = 2.0 * N * p.C * p.K * p.k * p.k * p.Ho * p.Wo
+            wb = p.K * p.C * p.k * p.k * 4
+            out[("conv_fwd", l)] = dict(flops=fl, bytes=nin * elem + nout * oel + wb)
+            out[("conv_bwd_data", l)] = dict(flops=fl, bytes=nout * oel + nin * elem + wb)
+            out[("conv_bwd_weight", l)] = dict(flops=fl, bytes=nin * elem + nout * oel + wb)
+            out[("act_bwd", l)] = dict(flops=0.0, bytes=3 * nout * oel)
+        elif p.kind == dsk.DSK_MAXPOOL:
+            out[("maxpool_fwd", l)] = dict(flops=0.0, bytes=nin * elem + nout * (elem + 1))
+            out[("maxpool_bwd", l)] = dict(flops=0.0, bytes=nout * (elem + 1) + nin * elem)
+        else:
+            out[("avgpool_fwd", l)] = dict(flops=0.0, bytes=nin * elem + nout * elem)
+            out[("avgpool_bwd", l)] = dict(flops=0.0, bytes=nout * elem + nin * elem)
+    last = net.plan[-1]
+    px = N * last.Ho * last.Wo
+    out[("softmax_xent", L)] = dict(flops=0.0, bytes=px * (last.K * 4 + 4 + 1 + last.K * elem))
+    out[("pad", -1)] = dict(flops=0.0, bytes=N * net.net.C0 * (net.H * net.W * 4 + net.maps[0].shape[2] * net.maps[0].shape[3] * elem))
+    return out
+
+
+def cpu_baseline(cfg, wl, forward_only, budget_s=20.0):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of
+    the same workload: patches are independent and equal-cost, so px/s = patches/s."""
+    import numpy as np
+    import oracle
+    from workloads import sample_pixels
+    net = cfg.net
+    params = oracle.pack_params(wl.weights, wl.biases)
+    xpad = oracle.pad_image(wl.image, net.patch)
+    threads = oracle.num_threads()
+    N, _, H, W = wl.image.shape
+    probe = sample_pixels(N, H, W, threads, seed=11)
+
+    def run(pix):
+        t0 = time.perf_counter()
+        s = oracle.scan_forward(net, params, xpad, pix)
+        if not forward_only:
+            d = np.full((len(pix), net.classes), 1.0 / len(pix))
+            oracle.scan_backward(net, params, xpad, pix, d)
+        return time.perf_counter() - t0
+
+    t_probe = run(probe)
+    count = int(max(threads, min(N * H * W, threads * max(1.0, budget_s / max(t_probe, 1e-3)))))
+    count -= count % threads
+    pix = sample_pixels(N, H, W, count, seed=12)
+    t = run(pix)
+    return {"value": len(pix) / t, "unit": "labelled pixels/s", "cores": threads, "kind": "oracle",
+            "sample": "%d patches of %dx%d (of %d pixels), %s, patch-by-patch fp64, %.1f s"
+                      % (len(pix), net.patch, net.patch, N * H * W,
+                         "forward only" if forward_only else "forward + backward", t)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--dtype", default=None)
+    ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--algo", type=int, default=0)
+    ap.add_argument("--layers", action="store_true", help="print the per-call table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_1412_4526_amd as dsk
+    from workloads import CONFIGS, make_workload
+
+    cfg = CONFIGS[args.config]
+    dtype = args.dtype or cfg.dtype
+    elem = 4 if dtype == "f32" else 2
+    wl = make_workload(cfg.net, cfg.N, cfg.H, cfg.W, cfg.mask_frac, cfg.seed, positive_frac=cfg.positive_frac)
+    dev = "cuda:0"
+    dsk.dsk_set_conv_algo(args.algo)
+    net = dsk.WholeImageNet(cfg.net, cfg.N, cfg.H, cfg.W, dtype, dev, train=not args.forward_only)
+    net.load_params(wl.weights, wl.biases)
+    image = torch.from_numpy(wl.image).to(dev)
+    labels = torch.from_numpy(wl.labels).to(dev)
+    mask = torch.from_numpy(wl.mask).to(dev)
+
+    def step():
+        net.forward(image)
+        if not args.forward_only:
+            net.loss_backward(labels, mask)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    net.timeline = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    timeline, net.timeline = net.timeline, None
+
+    pixels = cfg.N * cfg.H * cfg.W
+    # per-call device time from the events recorded inside the timed region
+    per = {}
+    for tag, layer, e0, e1 in timeline:
+        per.setdefault((tag, layer), []).append(e0.elapsed_time(e1))
+    costs = layer_costs(net, elem)
+    rows = []
+    for key, ms in per.items():
+        avg = sum(ms) / len(ms)
+        c = costs[key]
+        p = net.plan[key[1]] if 0 <= key[1] < len(net.plan) else None
+        row = {"call": key[0], "layer": key[1], "ms": round(avg, 4)}
+        if p is not None:
+            row["shape"] = "C%d K%d k%d d%d %dx%d" % (p.C, p.K, p.k, p.d, p.H, p.W)
+        if c["flops"] > 0:
+            row["tflops"] = round(c["flops"] / avg / 1e9, 2)
+            row["intensity"] = round(c["flops"] / c["bytes"], 1)
+        row["gbs"] = round(c["bytes"] / avg / 1e6, 1)
+        rows.append(row)
+    if args.layers:
+        for r in sorted(rows, key=lambda r: -r["ms"]):
+            sys.stderr.write(json.dumps(r) + "\n")
+
+    # roofline of the dominant call
+    dom = max(rows, key=lambda r: r["ms"])
+    c = costs[(dom["call"], dom["layer"])]
+    peak_mfma = PEAK_FP32_MFMA if dtype == "f32" else PEAK_BF16_MFMA
+    ridge = peak_mfma * 1e3 / PEAK_HBM          # flop per byte where the two roofs meet
+    if c["flops"] > 0 and c["flops"] / c["bytes"] >= ridge:
+        roof = {"bound": "mfma", "achieved": dom["tflops"], "peak": peak_mfma, "unit": "TFLOP/s",
+                "frac": round(dom["tflops"] / peak_mfma, 4)}
+    else:
+        roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM, "unit": "GB/s",
+                "frac": round(dom["gbs"] / PEAK_HBM, 4)}
+    roof["traffic"] = None
+    roof["kernel"] = "%s layer %d (%s)" % (dom["call"], dom["layer"], dom.get("shape", ""))
+    roof["ms"] = dom["ms"]
+
+    worst_conv = min((r["tflops"] / peak_mfma for r in rows
+                      if "tflops" in r and r["intensity"] >= ridge), default=None)
+    worst_pool = min((r["gbs"] / PEAK_HBM for r in rows if "pool" in r["call"]), default=None)
+
+    out = {
+        "metric": "labelled pixels/s whole-image %s" % ("fwd" if args.forward_only else "fwd+bwd"),
+        "value": pixels * args.steps / dt, "unit": "labelled pixels/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype,
+        "data": "synthetic",
+        "config": {"workload": "configs[%d]: %s patch %d, %dx%dx%dx%d image, mask %.0f%%"
+                               % (args.config, cfg.net.name, cfg.net.patch, cfg.N, cfg.net.C0, cfg.H, cfg.W,
+                                  cfg.mask_frac * 100),
+                   "conv_algo": "auto" if args.algo == 0 else "direct"},
+        "roofline": roof,
+        "worst_conv_frac_of_mfma_peak": None if worst_conv is None else round(worst_conv, 4),
+        "worst_pool_frac_of_hbm_peak": None if worst_pool is None else round(worst_pool, 4),
+        "layers": sorted(rows, key=lambda r: (r["layer"], r["call"])),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, args.forward_only)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -9,5 +9,6 @@ this package.  It shares no code with the HIP path and imports nothing from it.
   loss.py       masked softmax cross-entropy and its error map (Sec. 4.3 mask)
 """
 from .scan import (build, pad_image, pack_params, unpack_params, patch_forward,  # noqa: F401
+                   STORE_EXACT, STORE_BF16,
                    scan_forward, scan_backward, num_threads, geometry)
 from .loss import masked_softmax_xent  # noqa: F401

@@ -119,13 +119,47 @@ static double act_grad_from_output(int act, double y)
     return 1.0;
 }
 
+/* Storage precision of the maps.  ORC_STORE_EXACT keeps every value in fp64.
+ * ORC_STORE_BF16 models a path that STORES activations in bfloat16: the patch and
+ * every layer output except the last are rounded to bfloat16 (nearest even) after
+ * being computed in fp64, so that the decisions taken on stored values (ReLU
+ * gates, max-pool winners) are taken in the storage precision. */
+enum { ORC_STORE_EXACT = 0, ORC_STORE_BF16 = 1 };
+
+static double round_bf16(double v)
+{
+    union { float f; unsigned u; } c;
+    c.f = (float)v;
+    if ((c.u & 0x7fffffffu) > 0x7f800000u) return v; /* NaN */
+    c.u += 0x7fffu + ((c.u >> 16) & 1u);
+    c.u &= 0xffff0000u;
+    return (double)c.f;
+}
+
+static void round_map(double *p, long count, int storage)
+{
+    if (storage == ORC_STORE_BF16)
+        for (long t = 0; t < count; ++t) p[t] = round_bf16(p[t]);
+}
+
 /* Forward of the original CNN on one patch.  acts[act_off[0]...] must already
  * hold the patch (C0 x n x n).  Fills every later map; amax gets, at the same
  * offsets as the map it belongs to, the winning tap index of each max-pool
- * output (other entries untouched). */
+ * output (other entries untouched).
+ *
+ * margin (may be NULL) receives how far the patch is from the nearest point
+ * where its gradient is discontinuous, relative to the size of the values
+ * involved: the minimum over ReLU units of |pre-activation| / max|pre-activation
+ * of that layer|, and over max-pool windows of (winner - best different-valued
+ * other tap) / max|input of that layer|.  Exact zeros and exact ties (zero
+ * padding, ReLU outputs) are decided the same way in any precision and do not
+ * count.  Tests use it to keep away from inputs
+ * on which two correct finite-precision evaluations may decide differently. */
 static void patch_forward(const orc_layer *L, const orc_geom *g, const double *params,
-                          double *acts, int *amax)
+                          double *acts, int *amax, int storage, double *margin)
 {
+    double worst = 1.0;
+    round_map(acts + g->act_off[0], g->act_off[1] - g->act_off[0], storage);
     for (int l = 0; l < g->nL; ++l) {
         const int Ci = g->C[l], mi = g->m[l], Co = g->C[l + 1], mo = g->m[l + 1];
         const int k = L[l].k, s = L[l].s;
@@ -134,6 +168,7 @@ static void patch_forward(const orc_layer *L, const orc_geom *g, const double *p
         if (L[l].kind == ORC_CONV) {
             const double *w = params + g->par_off[l];
             const double *b = w + (long)Co * Ci * k * k;
+            double zmax = 0.0, zmin = INFINITY;
             for (int f = 0; f < Co; ++f)
                 for (int u = 0; u < mo; ++u)
                     for (int v = 0; v < mo; ++v) {
@@ -144,9 +179,15 @@ static void patch_forward(const orc_layer *L, const orc_geom *g, const double *p
                                     acc += w[(((long)f * Ci + c) * k + a) * k + bb] *
                                            x[((long)c * mi + (u * s + a)) * mi + (v * s + bb)];
                         y[((long)f * mo + u) * mo + v] = act_apply(L[l].act, acc);
+                        if (fabs(acc) > zmax) zmax = fabs(acc);
+                        if (acc != 0.0 && fabs(acc) < zmin) zmin = fabs(acc);
                     }
+            if (L[l].act == ORC_ACT_RELU && zmax > 0.0 && zmin / zmax < worst) worst = zmin / zmax;
         } else if (L[l].kind == ORC_MAXPOOL) {
             int *am = amax ? amax + g->act_off[l + 1] : NULL;
+            double xmax = 0.0, gapmin = INFINITY;
+            for (long t = 0; t < (long)Ci * mi * mi; ++t)
+                if (fabs(x[t]) > xmax) xmax = fabs(x[t]);
             for (int c = 0; c < Ci; ++c)
                 for (int u = 0; u < mo; ++u)
                     for (int v = 0; v < mo; ++v) {
@@ -159,7 +200,14 @@ static void patch_forward(const orc_layer *L, const orc_geom *g, const double *p
                             }
                         y[((long)c * mo + u) * mo + v] = best;
                         if (am) am[((long)c * mo + u) * mo + v] = bi;
+                        if (margin)
+                            for (int a = 0; a < k; ++a)
+                                for (int bb = 0; bb < k; ++bb) {
+                                    double t = x[((long)c * mi + (u * s + a)) * mi + (v * s + bb)];
+                                    if (t != best && best - t < gapmin) gapmin = best - t;
+                                }
                     }
+            if (xmax > 0.0 && gapmin / xmax < worst) worst = gapmin / xmax;
         } else { /* ORC_AVGPOOL */
             for (int c = 0; c < Ci; ++c)
                 for (int u = 0; u < mo; ++u)
@@ -171,7 +219,9 @@ static void patch_forward(const orc_layer *L, const orc_geom *g, const double *p
                         y[((long)c * mo + u) * mo + v] = acc / (double)(k * k);
                     }
         }
+        if (l + 1 < g->nL) round_map(y, (long)Co * mo * mo, storage);
     }
+    if (margin) *margin = worst;
 }
 
 /* Textbook backward of the original CNN on one patch.  grads holds, at the
@@ -242,13 +292,13 @@ static void crop_patch(const double *xpad, int C0, int Hp, int Wp, int n,
 /* One patch, all intermediates (for layer-by-layer checks).  patch: C0*n*n.
  * acts: orc_sizes().act_total doubles; amax: same count of ints (may be NULL). */
 int orc_patch_forward(const orc_layer *L, int nL, int C0, int n, const double *params,
-                      const double *patch, double *acts, int *amax)
+                      const double *patch, double *acts, int *amax, int storage)
 {
     orc_geom g;
     if (geom_build(L, nL, C0, n, &g)) return -1;
     memcpy(acts, patch, sizeof(double) * (size_t)C0 * n * n);
     if (amax) for (long t = 0; t < g.act_off[nL + 1]; ++t) amax[t] = -1;
-    patch_forward(L, &g, params, acts, amax);
+    patch_forward(L, &g, params, acts, amax, storage, NULL);
     return 0;
 }
 
@@ -256,10 +306,12 @@ int orc_patch_forward(const orc_layer *L, int nL, int C0, int n, const double *p
  * i, j) in UNPADDED pixel coordinates; the patch of (i, j) is padded rows
  * i..i+n-1, columns j..j+n-1.  scores: [P][classes].  last_amax (may be NULL):
  * [P][classes] winning tap indices when the last layer is a max pool.  The net
- * must reduce the patch to 1 x 1.  Returns 0, or -1 on a malformed net / out-of-range pixel. */
+ * must reduce the patch to 1 x 1.  storage: ORC_STORE_*; margins (may be NULL):
+ * [P] distance of each patch from a gradient discontinuity (see patch_forward).  Returns 0, or -1 on a malformed net / out-of-range pixel. */
 int orc_scan_forward(const orc_layer *L, int nL, int C0, int n, const double *params,
                      const double *xpad, int N, int Hp, int Wp,
-                     const int *pix, long P, double *scores, int *last_amax)
+                     const int *pix, long P, double *scores, int *last_amax,
+                     int storage, double *margins)
 {
     orc_geom g;
     if (geom_build(L, nL, C0, n, &g) || g.m[nL] != 1) return -1;
@@ -280,7 +332,7 @@ int orc_scan_forward(const orc_layer *L, int nL, int C0, int n, const double *pa
         for (long p = 0; p < P; ++p) {
             if (!acts || (last_amax && !amax)) continue;
             crop_patch(xpad, C0, Hp, Wp, n, pix[3 * p], pix[3 * p + 1], pix[3 * p + 2], acts);
-            patch_forward(L, &g, params, acts, amax);
+            patch_forward(L, &g, params, acts, amax, storage, margins ? margins + p : NULL);
             memcpy(scores + p * cls, acts + g.act_off[nL], sizeof(double) * (size_t)cls);
             if (last_amax)
                 memcpy(last_amax + p * cls, amax + g.act_off[nL], sizeof(int) * (size_t)cls);
@@ -299,7 +351,7 @@ int orc_scan_forward(const orc_layer *L, int nL, int C0, int n, const double *pa
 int orc_scan_backward(const orc_layer *L, int nL, int C0, int n, const double *params,
                       const double *xpad, int N, int Hp, int Wp,
                       const int *pix, long P, const double *delta,
-                      double *dparams, double *dxpad)
+                      double *dparams, double *dxpad, int storage)
 {
     orc_geom g;
     if (geom_build(L, nL, C0, n, &g) || g.m[nL] != 1) return -1;
@@ -336,7 +388,7 @@ int orc_scan_backward(const orc_layer *L, int nL, int C0, int n, const double *p
             if (!acts || !grads || !amax) continue;
             const int img = pix[3 * p], i = pix[3 * p + 1], j = pix[3 * p + 2];
             crop_patch(xpad, C0, Hp, Wp, n, img, i, j, acts);
-            patch_forward(L, &g, params, acts, amax);
+            patch_forward(L, &g, params, acts, amax, storage, NULL);
             memset(grads, 0, sizeof(double) * (size_t)na);
             memcpy(grads + g.act_off[nL], delta + p * cls, sizeof(double) * (size_t)cls);
             patch_backward(L, &g, params, acts, amax, grads, mine);

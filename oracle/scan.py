@@ -43,9 +43,9 @@ def _load():
         ci, cl = ctypes.c_int, ctypes.c_long
         lib.orc_sizes.argtypes = [Lp, ci, ci, ci, lp, lp, ip, ip]
         lib.orc_geometry.argtypes = [Lp, ci, ci, ci, ip, ip, lp, lp]
-        lib.orc_patch_forward.argtypes = [Lp, ci, ci, ci, dp, dp, dp, ip]
-        lib.orc_scan_forward.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp, ip]
-        lib.orc_scan_backward.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp, dp, dp]
+        lib.orc_patch_forward.argtypes = [Lp, ci, ci, ci, dp, dp, dp, ip, ci]
+        lib.orc_scan_forward.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp, ip, ci, dp]
+        lib.orc_scan_backward.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp, dp, dp, ci]
         lib.orc_num_threads.restype = ci
         _lib = lib
     return _lib
@@ -131,7 +131,10 @@ def unpack_params(net, flat):
     return ws, bs
 
 
-def patch_forward(net, params, patch):
+STORE_EXACT, STORE_BF16 = 0, 1
+
+
+def patch_forward(net, params, patch, storage=STORE_EXACT):
     """Original CNN on one patch [C0, n, n].  Returns (maps, argmax): lists over
     l = 0..L of fp64 [C_l, m_l, m_l] maps (map 0 is the patch) and int32 arrays of
     the same shapes holding the winning tap index a*k+b of max-pool outputs
@@ -146,7 +149,7 @@ def patch_forward(net, params, patch):
     acts = np.zeros(g["act_total"], np.float64)
     amax = np.zeros(g["act_total"], np.int32)
     if lib.orc_patch_forward(arr, nL, net.C0, net.patch, _dptr(params), _dptr(patch),
-                             _dptr(acts), _iptr(amax)):
+                             _dptr(acts), _iptr(amax), storage):
         raise ValueError("malformed net")
     maps, ams = [], []
     for l in range(nL + 1):
@@ -156,9 +159,12 @@ def patch_forward(net, params, patch):
     return maps, ams
 
 
-def scan_forward(net, params, xpad, pix, want_argmax=False):
+def scan_forward(net, params, xpad, pix, want_argmax=False, storage=STORE_EXACT, want_margin=False):
     """Scores [P, classes] of the patches at pix [P, 3] = (image, i, j).  With
-    want_argmax (last layer a max pool) also the winning tap indices [P, classes]."""
+    want_argmax (last layer a max pool) also the winning tap indices [P, classes]; with
+    want_margin also each patch's relative distance [P] from the nearest ReLU gate / max-pool
+    near-tie, where the gradient is discontinuous.  storage=STORE_BF16 rounds the patch and
+    every layer output but the last to bfloat16."""
     lib = _load()
     g = geometry(net)
     if g["m_last"] != 1:
@@ -172,15 +178,18 @@ def scan_forward(net, params, xpad, pix, want_argmax=False):
     assert C0 == net.C0
     out = np.zeros((pix.shape[0], g["classes"]), np.float64)
     am = np.zeros((pix.shape[0], g["classes"]), np.int32) if want_argmax else None
+    mg = np.ones(pix.shape[0], np.float64) if want_margin else None
     rc = lib.orc_scan_forward(arr, nL, net.C0, net.patch, _dptr(params), _dptr(xpad),
                               N, Hp, Wp, _iptr(pix), pix.shape[0], _dptr(out),
-                              _iptr(am) if want_argmax else None)
+                              _iptr(am) if want_argmax else None, storage,
+                              _dptr(mg) if want_margin else None)
     if rc:
         raise ValueError("orc_scan_forward failed: %d" % rc)
-    return (out, am) if want_argmax else out
+    res = (out,) + ((am,) if want_argmax else ()) + ((mg,) if want_margin else ())
+    return res if len(res) > 1 else out
 
 
-def scan_backward(net, params, xpad, pix, delta, want_dx=False):
+def scan_backward(net, params, xpad, pix, delta, want_dx=False, storage=STORE_EXACT):
     """Sum over the listed patches of the parameter gradients for output errors
     delta [P, classes].  Returns (dparams flat, dxpad or None)."""
     lib = _load()
@@ -198,7 +207,7 @@ def scan_backward(net, params, xpad, pix, delta, want_dx=False):
     dx = np.zeros_like(xpad) if want_dx else None
     rc = lib.orc_scan_backward(arr, nL, net.C0, net.patch, _dptr(params), _dptr(xpad),
                                N, Hp, Wp, _iptr(pix), pix.shape[0], _dptr(delta), _dptr(dpar),
-                               _dptr(dx) if want_dx else None)
+                               _dptr(dx) if want_dx else None, storage)
     if rc:
         raise ValueError("orc_scan_backward failed: %d" % rc)
     return dpar[:g["n_params"]], dx

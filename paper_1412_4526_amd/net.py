@@ -61,6 +61,19 @@ class WholeImageNet:
             biggest = max(m.numel() for m in self.maps[1:])
             self._g = [torch.empty(biggest, dtype=self.act_dtype, device=dev) for _ in range(2)]
         self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+        self.timeline = None     # set to a list to collect (tag, layer, start_event, end_event) per call
+
+    def _timed(self, tag, layer, fn, *a, **kw):
+        """Run one library call; when a timeline is attached, bracket it with events on
+        the current stream (the stream the library launches on)."""
+        if self.timeline is None:
+            return fn(*a, **kw)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        out = fn(*a, **kw)
+        e1.record()
+        self.timeline.append((tag, layer, e0, e1))
+        return out
 
     # ------------------------------------------------------------------ parameters
     def load_params(self, weights, biases):
@@ -73,17 +86,19 @@ class WholeImageNet:
     # ------------------------------------------------------------------ Algorithm 1
     def forward(self, image):
         """image: fp32 GPU tensor [N, C0, H, W] (unpadded).  Returns scores [N, Cls, H, W] fp32."""
-        B.dsk_pad_image(image, self.pad_lo, self.pad_hi, xpad=self.xpad)
+        self._timed("pad", -1, B.dsk_pad_image, image, self.pad_lo, self.pad_hi, xpad=self.xpad)
         ci = 0
         for l, p in enumerate(self.plan):
             x, y = self.maps[l], self.maps[l + 1]
             if p.kind == B.DSK_CONV:
-                B.dsk_conv_fwd(x, self.weights[ci], self.biases[ci], p.d, p.act, y=y, ws=self.ws)
+                self._timed("conv_fwd", l, B.dsk_conv_fwd, x, self.weights[ci], self.biases[ci], p.d, p.act,
+                            y=y, ws=self.ws)
                 ci += 1
             elif p.kind == B.DSK_MAXPOOL:
-                B.dsk_maxpool_fwd(x, p.k, p.d, y=y, argmax=self.argmax[l], want_argmax=self.train)
+                self._timed("maxpool_fwd", l, B.dsk_maxpool_fwd, x, p.k, p.d, y=y, argmax=self.argmax[l],
+                            want_argmax=self.train)
             else:
-                B.dsk_avgpool_fwd(x, p.k, p.d, y=y)
+                self._timed("avgpool_fwd", l, B.dsk_avgpool_fwd, x, p.k, p.d, y=y)
         return self.scores
 
     # ------------------------------------------------------------------ Sec. 4
@@ -97,7 +112,8 @@ class WholeImageNet:
         L = len(self.plan)
         cur = 0
         g = self._gbuf(cur, self.scores)
-        B.dsk_masked_softmax_xent(self.scores, labels, mask, loss=self.loss, dscores=g, ws=self.ws)
+        self._timed("softmax_xent", L, B.dsk_masked_softmax_xent, self.scores, labels, mask, loss=self.loss,
+                    dscores=g, ws=self.ws)
         ci = len(self.weights) - 1
         for l in range(L - 1, -1, -1):
             p = self.plan[l]
@@ -105,15 +121,17 @@ class WholeImageNet:
             gin = self._g[1 - cur][:x.numel()].view(x.shape) if l > 0 else None
             if p.kind == B.DSK_CONV:
                 if p.act != B.DSK_ACT_NONE:
-                    B.dsk_act_bwd(y, g, p.act)
-                B.dsk_conv_bwd_weight(x, g, p.k, p.k, p.d, dw=self.dw[ci], db=self.db[ci], ws=self.ws)
+                    self._timed("act_bwd", l, B.dsk_act_bwd, y, g, p.act)
+                self._timed("conv_bwd_weight", l, B.dsk_conv_bwd_weight, x, g, p.k, p.k, p.d, dw=self.dw[ci],
+                            db=self.db[ci], ws=self.ws)
                 if l > 0:        # nobody needs the error map of the image itself
-                    B.dsk_conv_bwd_data(g, self.weights[ci], p.d, p.H, p.W, dx=gin, ws=self.ws)
+                    self._timed("conv_bwd_data", l, B.dsk_conv_bwd_data, g, self.weights[ci], p.d, p.H, p.W,
+                                dx=gin, ws=self.ws)
                 ci -= 1
             elif p.kind == B.DSK_MAXPOOL:
-                B.dsk_maxpool_bwd(g, self.argmax[l], p.k, p.d, p.H, p.W, dx=gin)
+                self._timed("maxpool_bwd", l, B.dsk_maxpool_bwd, g, self.argmax[l], p.k, p.d, p.H, p.W, dx=gin)
             else:
-                B.dsk_avgpool_bwd(g, p.k, p.d, p.H, p.W, dx=gin)
+                self._timed("avgpool_bwd", l, B.dsk_avgpool_bwd, g, p.k, p.d, p.H, p.W, dx=gin)
             if l > 0:
                 g = gin
                 cur = 1 - cur

@@ -1,16 +1,538 @@
-// Matrix-core kernels for the sparse-kernel convolution operators (placeholder:
-// nothing is routed here yet).
+// Matrix-core (MFMA) kernels for the sparse-kernel convolution operators on gfx950:
+// forward and backward-data (paper Sec. 3.1-3.2, Sec. 4.1: delta_k = pad(delta_{k+1})
+// *^1 rot180(W_{k,d})) share one implicit-GEMM kernel; backward-weight (Sec. 4.1:
+// grad W_{k,d} = x_k *^1 rot(delta_{k+1,d})) has its own.
+//
+// No column matrix is ever materialised (the paper gathers the non-zero taps into
+// one; here the gather happens on the way from LDS to the matrix cores).
+//
+// Tiling idea, common to both kernels: a workgroup's output ROWS all lie in one
+// residue class modulo the spacing d (rows u0, u0+d, u0+2d, ...), while its COLUMNS
+// are contiguous.  The kh taps of such rows hit input rows of the same class, so a
+// tile of TH rows needs only TH+kh-1 input rows whatever d is, and every global
+// load is a contiguous row segment.  The column halo is (kw-1)*d.
+//
+// fp32 path: v_mfma_f32_32x32x2_f32.  Lane l supplies A[i = l%32][k = l/32] and
+// B[k = l/32][j = l%32]; register r of the 16 results holds D[8*(r/4) + 4*(l/32) + r%4][l%32].
 #include "dsk_internal.h"
 
 namespace dsk {
 
-size_t conv_ws_bytes(int, const ConvShape &, dsk_dtype) { return 0; }
-bool conv_mfma_supported(int, const ConvShape &, dsk_dtype, dsk_dtype) { return false; }
-int launch_conv_fwd_mfma(const void *, const float *, const float *, void *, const ConvShape &, dsk_dtype,
-                         dsk_dtype, int, void *, hipStream_t) { return DSK_EDTYPE; }
-int launch_conv_bwd_data_mfma(const void *, const float *, void *, const ConvShape &, dsk_dtype, dsk_dtype,
-                              void *, hipStream_t) { return DSK_EDTYPE; }
-int launch_conv_bwd_weight_mfma(const void *, const void *, float *, float *, const ConvShape &, dsk_dtype,
-                                void *, hipStream_t) { return DSK_EDTYPE; }
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+static constexpr int kThreads = 256;
+static constexpr int kXcds = 8;
+static constexpr size_t kMaxLds = 64 * 1024;      // forward / backward-data: two workgroups per CU
+static constexpr size_t kMaxLdsBw = 76 * 1024;    // backward-weight: still two per CU (160 KB)
+
+// Dynamic LDS beyond the default limit has to be enabled per kernel.
+template <typename F>
+static void allow_lds(F kernel, size_t bytes)
+{
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)bytes);
+}
+
+// ============================================================================
+// forward / backward-data: out[n][f][u][v] = epi( sum_{c,a,b} wt[c][a][b][f] *
+//                                   in[n][c][u + a*d - off][v + b*d - off] ), in = 0 outside
+// ============================================================================
+static constexpr int TH = 8;    // output rows per workgroup (one residue class mod d)
+static constexpr int TW = 64;   // output columns per workgroup
+
+struct GcParams {
+    const void *in;
+    void *out;
+    const float *wt;     // [n_fgrp][Cpad][taps][TF], zero padded
+    const float *bias;   // may be null
+    int N, Cin, Hin, Win, Fout, Hout, Wout;
+    int kh, kw, d, off_h, off_w, act;
+    int Cpad, Cc;        // padded channel count, channels per LDS chunk (even)
+    int rows, cols;      // LDS tile: TH+kh-1 by TW+(kw-1)*d
+    int chan_stride;     // rows*cols
+    int xs_floats;       // Cc*chan_stride rounded up to a multiple of 4
+    int n_rowtile, n_coltile, n_fgrp;
+    long total, per_xcd;
+};
+
+// Weight layout transform.  flip = 0: wt[g][c][t][fl] = w[g*TF+fl][c][t]            (forward)
+//                           flip = 1: wt[g][k][t][cl] = w[k][g*TF+cl][taps-1-t]     (backward-data)
+__global__ void __launch_bounds__(kThreads)
+gc_weight_prep_kernel(const float *__restrict__ w, float *__restrict__ wt, int K, int C, int taps,
+                      int Cpad, int TF, int n_fgrp, int flip)
+{
+    const long total = (long)n_fgrp * Cpad * taps * TF;
+    const long idx = (long)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= total) return;
+    const int fl = (int)(idx % TF);
+    const int t = (int)((idx / TF) % taps);
+    const int c = (int)((idx / ((long)TF * taps)) % Cpad);
+    const int g = (int)(idx / ((long)TF * taps * Cpad));
+    const int f = g * TF + fl;
+    float v = 0.f;
+    if (!flip) {
+        if (f < K && c < C) v = w[((long)f * C + c) * taps + t];
+    } else {
+        // channel index of the GEMM is the filter k of w, output index is the channel c of w
+        if (f < C && c < K) v = w[((long)c * C + f) * taps + (taps - 1 - t)];
+    }
+    wt[idx] = v;
+}
+
+template <typename TI, typename TO, int WM>
+__global__ void __launch_bounds__(kThreads, 2)
+gemm_conv_kernel(GcParams p)
+{
+    extern __shared__ __align__(16) float smem[];
+    constexpr int TF = WM * 32;
+    float *xs = smem;                   // [Cc][rows][cols]
+    float *wsm = smem + p.xs_floats;    // [Cc][taps][TF]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lo = lane & 31, hi = lane >> 5;
+
+    // consecutive physical workgroups go to different XCDs; give each XCD one contiguous
+    // run of logical tiles so that neighbours (shared halo, same input tile) share an L2
+    long j = (long)(blockIdx.x % kXcds) * p.per_xcd + blockIdx.x / kXcds;
+    if (j >= p.total) return;
+    const int fg = (int)(j % p.n_fgrp); j /= p.n_fgrp;
+    const int ct = (int)(j % p.n_coltile); j /= p.n_coltile;
+    const int rt = (int)(j % p.n_rowtile);
+    const int n = (int)(j / p.n_rowtile);
+    const int u0 = (rt / p.d) * p.d * TH + (rt % p.d);
+    const int v0 = ct * TW;
+    if (u0 >= p.Hout) return;
+
+    const TI *in = (const TI *)p.in;
+    const int taps = p.kh * p.kw;
+
+    f32x16 acc[WM][4];
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+        for (int wn = 0; wn < 4; ++wn)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
+
+    for (int c0 = 0; c0 < p.Cpad; c0 += p.Cc) {
+        __syncthreads();
+        // ---- stage the input tile: one (channel, row) segment per wave iteration
+        for (int seg = wave; seg < p.Cc * p.rows; seg += kThreads / 64) {
+            const int c = seg / p.rows, r = seg - c * p.rows;
+            const int gc = c0 + c;
+            const int irow = u0 + r * p.d - p.off_h;
+            const bool row_ok = gc < p.Cin && irow >= 0 && irow < p.Hin;
+            const TI *src = in + (((long)n * p.Cin + (row_ok ? gc : 0)) * p.Hin + (row_ok ? irow : 0)) * p.Win;
+            float *dst = xs + c * p.chan_stride + r * p.cols;
+            for (int col = lane; col < p.cols; col += 64) {
+                const int icol = v0 + col - p.off_w;
+                float v = 0.f;
+                if (row_ok && icol >= 0 && icol < p.Win) v = ldf(src, icol);
+                dst[col] = v;
+            }
+        }
+        // ---- stage the weights of this chunk: one contiguous run
+        {
+            const float4 *wsrc = (const float4 *)(p.wt + ((long)fg * p.Cpad + c0) * taps * TF);
+            float4 *wdst = (float4 *)wsm;
+            const int n4 = p.Cc * taps * TF / 4;
+            for (int i = tid; i < n4; i += kThreads) wdst[i] = wsrc[i];
+        }
+        __syncthreads();
+        // ---- matrix cores: k index = (channel pair, tap); lanes 32..63 take the odd channel
+        for (int cp = 0; cp < p.Cc; cp += 2) {
+            const float *xb = xs + (cp + hi) * p.chan_stride + (2 * wave) * p.cols + lo;
+            const float *wb = wsm + (cp + hi) * taps * TF + lo;
+            for (int a = 0; a < p.kh; ++a) {
+                for (int b = 0; b < p.kw; ++b) {
+                    float A[WM], B[4];
+#pragma unroll
+                    for (int wm = 0; wm < WM; ++wm) A[wm] = wb[(a * p.kw + b) * TF + wm * 32];
+#pragma unroll
+                    for (int wn = 0; wn < 4; ++wn)
+                        B[wn] = xb[((wn >> 1) + a) * p.cols + (wn & 1) * 32 + b * p.d];
+#pragma unroll
+                    for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                        for (int wn = 0; wn < 4; ++wn)
+                            acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- epilogue: bias, non-linearity, store; 32 consecutive pixels per filter per store
+    TO *out = (TO *)p.out;
+#pragma unroll
+    for (int wn = 0; wn < 4; ++wn) {
+        const int row = u0 + (2 * wave + (wn >> 1)) * p.d;
+        const int col = v0 + (wn & 1) * 32 + lo;
+        if (row >= p.Hout || col >= p.Wout) continue;
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int f = fg * TF + wm * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
+                if (f < p.Fout) {
+                    float v = acc[wm][wn][i];
+                    if (p.bias) v += p.bias[f];
+                    v = act_apply(p.act, v);
+                    stf(out, (((long)n * p.Fout + f) * p.Hout + row) * p.Wout + col, v);
+                }
+            }
+        }
+    }
+}
+
+struct GcPlan {
+    bool ok;
+    int TF, WM, Cc, Cpad, rows, cols, chan_stride, xs_floats, n_fgrp;
+    size_t lds_bytes, wt_bytes;
+};
+
+// Cin / Fout: channel and output counts of the GEMM (swapped for backward-data)
+static GcPlan gc_plan(int Cin, int Fout, int kh, int kw, int d)
+{
+    GcPlan g{};
+    g.WM = Fout > 32 ? 2 : 1;
+    g.TF = g.WM * 32;
+    g.n_fgrp = (Fout + g.TF - 1) / g.TF;
+    g.rows = TH + kh - 1;
+    const long cols = (long)TW + (long)(kw - 1) * d;
+    const long taps = (long)kh * kw;
+    if (cols > 4096 || taps > 1024) return g;
+    g.cols = (int)cols;
+    g.chan_stride = g.rows * g.cols;
+    int best = 0, best_pad = 0;
+    for (int cc = 8; cc >= 2; cc -= 2) {
+        const size_t bytes = 4 * ((size_t)((cc * g.chan_stride + 3) & ~3) + (size_t)cc * taps * g.TF);
+        if (bytes > kMaxLds) continue;
+        const int pad = (Cin + cc - 1) / cc * cc;
+        if (best == 0 || pad < best_pad) { best = cc; best_pad = pad; }
+    }
+    if (best == 0) return g;
+    g.Cc = best;
+    g.Cpad = best_pad;
+    g.xs_floats = (g.Cc * g.chan_stride + 3) & ~3;
+    g.lds_bytes = 4 * ((size_t)g.xs_floats + (size_t)g.Cc * taps * g.TF);
+    g.wt_bytes = 4 * (size_t)g.n_fgrp * g.Cpad * taps * g.TF;
+    g.ok = true;
+    return g;
+}
+
+template <typename TI, typename TO>
+static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
+{
+    const unsigned grid = (unsigned)(p.per_xcd * kXcds);
+    if (g.WM == 2)
+        gemm_conv_kernel<TI, TO, 2><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    else
+        gemm_conv_kernel<TI, TO, 1><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+}
+
+static int gc_run(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Hin, int Win,
+                  int Fout, int Hout, int Wout, int kh, int kw, int d, int off, int act, int flip,
+                  int K, int C, dsk_dtype tin, dsk_dtype tout, void *ws, hipStream_t st)
+{
+    const GcPlan g = gc_plan(Cin, Fout, kh, kw, d);
+    if (!g.ok) return DSK_ESHAPE;
+    const int taps = kh * kw;
+    float *wt = (float *)ws;
+    {
+        const long total = (long)g.n_fgrp * g.Cpad * taps * g.TF;
+        gc_weight_prep_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+            w, wt, K, C, taps, g.Cpad, g.TF, g.n_fgrp, flip);
+    }
+    GcParams p{};
+    p.in = in; p.out = out; p.wt = wt; p.bias = bias;
+    p.N = N; p.Cin = Cin; p.Hin = Hin; p.Win = Win; p.Fout = Fout; p.Hout = Hout; p.Wout = Wout;
+    p.kh = kh; p.kw = kw; p.d = d; p.off_h = off ? (kh - 1) * d : 0; p.off_w = off ? (kw - 1) * d : 0;
+    p.act = act;
+    p.Cpad = g.Cpad; p.Cc = g.Cc; p.rows = g.rows; p.cols = g.cols; p.chan_stride = g.chan_stride;
+    p.xs_floats = g.xs_floats;
+    p.n_rowtile = (Hout + d * TH - 1) / (d * TH) * d;
+    p.n_coltile = (Wout + TW - 1) / TW;
+    p.n_fgrp = g.n_fgrp;
+    p.total = (long)N * p.n_rowtile * p.n_coltile * p.n_fgrp;
+    p.per_xcd = (p.total + kXcds - 1) / kXcds;
+    if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;
+    if (tin == DSK_F32 && tout == DSK_F32) gc_launch<float, float>(p, g, st);
+    else if (tin == DSK_F32 && tout == DSK_BF16) gc_launch<float, bf16>(p, g, st);
+    else return DSK_EDTYPE;
+    return check_launch();
+}
+
+// ============================================================================
+// backward-weight: dw[f][c][a][b] = sum_{n,u,v} dy[n][f][u][v] * x[n][c][u+a*d][v+b*d]
+// One workgroup owns a 32-filter x 32-channel block of dw for ALL taps and walks over
+// a share of the pixel tiles (split-K); the four waves divide the taps.  Partial
+// blocks go to the workspace and are summed in a fixed order by a second kernel.
+// ============================================================================
+static constexpr int PH = 4;    // pixel-tile rows (one residue class mod d)
+static constexpr int PW = 32;   // pixel-tile columns
+static constexpr int DY_STRIDE = PH * PW + 1;   // odd: lanes = filters read conflict-free
+
+struct BwParams {
+    const void *x, *dy;
+    float *part;         // [S][Kp][Cp][taps]
+    int N, C, H, W, K, Ho, Wo, kh, kw, d;
+    int Kp, Cp;          // padded to 32
+    int xrows, xcols, xstride;   // x tile: PH+kh-1 by PW+(kw-1)*d, channel stride odd
+    int n_rowtile, n_coltile;    // pixel tiles per image
+    long n_ptile;        // N * n_rowtile * n_coltile
+    int S;               // split count
+    int n_fblk, n_cblk;
+};
+
+template <typename TI, int TPW>
+__global__ void __launch_bounds__(kThreads, (TPW <= 7 ? 2 : 1))
+conv_bwd_weight_mfma_kernel(BwParams p)
+{
+    extern __shared__ __align__(16) float smem[];
+    float *dys = smem;                       // [32 filters][DY_STRIDE]
+    float *xs = smem + 32 * DY_STRIDE;       // [32 channels][xstride]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lo = lane & 31, hi = lane >> 5;
+    const int taps = p.kh * p.kw;
+
+    int b = blockIdx.x;
+    const int s = b % p.S; b /= p.S;
+    const int cb = b % p.n_cblk;
+    const int fb = b / p.n_cblk;
+
+    const TI *x = (const TI *)p.x;
+    const TI *dy = (const TI *)p.dy;
+
+    f32x16 acc[TPW];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+    for (long pt = s; pt < p.n_ptile; pt += p.S) {
+        const int ct = (int)(pt % p.n_coltile);
+        const int rt = (int)((pt / p.n_coltile) % p.n_rowtile);
+        const int n = (int)(pt / ((long)p.n_coltile * p.n_rowtile));
+        const int u0 = (rt / p.d) * p.d * PH + (rt % p.d);
+        const int v0 = ct * PW;
+        if (u0 >= p.Ho) continue;            // uniform over the workgroup
+        __syncthreads();
+        // ---- dy tile: 32 filters x PH rows x 32 columns; half a wave per (filter, row) segment
+        for (int seg = wave * 2 + hi; seg < 32 * PH; seg += 8) {
+            const int f = seg / PH, r = seg - f * PH;
+            const int gf = fb * 32 + f;
+            const int row = u0 + r * p.d, col = v0 + lo;
+            float v = 0.f;
+            if (gf < p.K && row < p.Ho && col < p.Wo)
+                v = ldf(dy, (((long)n * p.K + gf) * p.Ho + row) * p.Wo + col);
+            dys[f * DY_STRIDE + r * PW + lo] = v;
+        }
+        // ---- x tile: 32 channels x xrows x xcols
+        for (int seg = wave; seg < 32 * p.xrows; seg += 4) {
+            const int c = seg / p.xrows, r = seg - c * p.xrows;
+            const int gc = cb * 32 + c;
+            const int row = u0 + r * p.d;
+            const bool row_ok = gc < p.C && row < p.H;
+            const TI *src = x + (((long)n * p.C + (row_ok ? gc : 0)) * p.H + (row_ok ? row : 0)) * p.W;
+            float *dst = xs + c * p.xstride + r * p.xcols;
+            for (int col = lane; col < p.xcols; col += 64) {
+                const int icol = v0 + col;
+                float v = 0.f;
+                if (row_ok && icol < p.W) v = ldf(src, icol);
+                dst[col] = v;
+            }
+        }
+        __syncthreads();
+        // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
+        const float *ab = dys + lo * DY_STRIDE + hi;
+        const float *bb = xs + lo * p.xstride + hi;
+        for (int r = 0; r < PH; ++r) {
+            for (int q = 0; q < PW / 2; ++q) {
+                const float A = ab[r * PW + 2 * q];
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) {
+                    const int tap = wave + 4 * t;
+                    if (tap < taps) {          // uniform over the wave
+                        const int a = tap / p.kw, bcol = tap - a * p.kw;
+                        const float B = bb[(r + a) * p.xcols + 2 * q + bcol * p.d];
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(A, B, acc[t], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- partial block out: part[s][f][c][tap]; lane = channel, registers = filters
+    float *part = p.part + (long)s * p.Kp * p.Cp * taps;
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+        const int tap = wave + 4 * t;
+        if (tap >= taps) continue;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int f = fb * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
+            const int c = cb * 32 + lo;
+            part[((long)f * p.Cp + c) * taps + tap] = acc[t][i];
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kThreads)
+bw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int taps, int Kp, int Cp, int S)
+{
+    const long total = (long)K * C * taps;
+    const long idx = (long)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= total) return;
+    const int t = (int)(idx % taps);
+    const int c = (int)((idx / taps) % C);
+    const int f = (int)(idx / ((long)taps * C));
+    const long o = ((long)f * Cp + c) * taps + t;
+    const long stride = (long)Kp * Cp * taps;
+    float acc = 0.f;
+    for (int s = 0; s < S; ++s) acc += part[s * stride + o];
+    dw[idx] = acc;
+}
+
+// db[f] = sum over n, u, v of dy: one workgroup per filter, fixed-order tree
+template <typename TI>
+__global__ void __launch_bounds__(kThreads)
+bias_grad_kernel(const TI *__restrict__ dy, float *__restrict__ db, int N, int K, long plane)
+{
+    __shared__ float sm[kThreads];
+    const int f = blockIdx.x;
+    float acc = 0.f;
+    for (int n = 0; n < N; ++n) {
+        const TI *src = dy + ((long)n * K + f) * plane;
+        for (long t = threadIdx.x; t < plane; t += kThreads) acc += ldf(src, t);
+    }
+    sm[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = kThreads / 2; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) sm[threadIdx.x] += sm[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) db[f] = sm[0];
+}
+
+struct BwPlan {
+    bool ok;
+    int Kp, Cp, xrows, xcols, xstride, n_rowtile, n_coltile, S, n_fblk, n_cblk, tpw;
+    long n_ptile;
+    size_t lds_bytes, part_bytes;
+};
+
+static BwPlan bw_plan(const ConvShape &s)
+{
+    BwPlan b{};
+    const long taps = (long)s.kh * s.kw;
+    if (taps > 52) return b;
+    b.tpw = taps <= 16 ? 4 : (taps <= 28 ? 7 : 13);
+    b.Kp = (s.K + 31) / 32 * 32;
+    b.Cp = (s.C + 31) / 32 * 32;
+    b.n_fblk = b.Kp / 32;
+    b.n_cblk = b.Cp / 32;
+    b.xrows = PH + s.kh - 1;
+    const long xcols = (long)PW + (long)(s.kw - 1) * s.d;
+    if (xcols > 2048) return b;
+    b.xcols = (int)xcols;
+    b.xstride = (b.xrows * b.xcols) | 1;
+    b.lds_bytes = 4 * ((size_t)32 * DY_STRIDE + (size_t)32 * b.xstride);
+    if (b.lds_bytes > kMaxLdsBw) return b;
+    b.n_rowtile = (s.Ho + s.d * PH - 1) / (s.d * PH) * s.d;
+    b.n_coltile = (s.Wo + PW - 1) / PW;
+    b.n_ptile = (long)s.N * b.n_rowtile * b.n_coltile;
+    const long blocks = (long)b.n_fblk * b.n_cblk;
+    long S = 2048 / blocks;
+    if (S > 256) S = 256;
+    if (S > b.n_ptile / 4) S = b.n_ptile / 4;
+    if (S < 1) S = 1;
+    b.S = (int)S;
+    b.part_bytes = 4 * (size_t)b.S * b.Kp * b.Cp * taps;
+    b.ok = true;
+    return b;
+}
+
+// ============================================================================
+// dispatch
+// ============================================================================
+size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
+{
+    if (in != DSK_F32) return 0;
+    if (which == DSK_WS_CONV_FWD) {
+        const GcPlan g = gc_plan(s.C, s.K, s.kh, s.kw, s.d);
+        return g.ok ? g.wt_bytes : 0;
+    }
+    if (which == DSK_WS_CONV_BWD_DATA) {
+        const GcPlan g = gc_plan(s.K, s.C, s.kh, s.kw, s.d);
+        return g.ok ? g.wt_bytes : 0;
+    }
+    if (which == DSK_WS_CONV_BWD_WEIGHT) {
+        const BwPlan b = bw_plan(s);
+        return b.ok ? b.part_bytes : 0;
+    }
+    return 0;
+}
+
+bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype out)
+{
+    if (in != DSK_F32) return false;
+    (void)out;
+    if (which == DSK_WS_CONV_FWD) return gc_plan(s.C, s.K, s.kh, s.kw, s.d).ok;
+    if (which == DSK_WS_CONV_BWD_DATA) return gc_plan(s.K, s.C, s.kh, s.kw, s.d).ok;
+    if (which == DSK_WS_CONV_BWD_WEIGHT) return bw_plan(s).ok;
+    return false;
+}
+
+int launch_conv_fwd_mfma(const void *x, const float *w, const float *b, void *y, const ConvShape &s,
+                         dsk_dtype in, dsk_dtype out, int act, void *ws, hipStream_t st)
+{
+    return gc_run(x, y, w, b, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d, 0, act, 0,
+                  s.K, s.C, in, out, ws, st);
+}
+
+int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const ConvShape &s,
+                              dsk_dtype in, dsk_dtype out, void *ws, hipStream_t st)
+{
+    return gc_run(dy, dx, w, nullptr, s.N, s.K, s.Ho, s.Wo, s.C, s.H, s.W, s.kh, s.kw, s.d, 1, DSK_ACT_NONE, 1,
+                  s.K, s.C, in, out, ws, st);
+}
+
+int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
+                                dsk_dtype in, void *ws, hipStream_t st)
+{
+    if (in != DSK_F32) return DSK_EDTYPE;
+    const BwPlan b = bw_plan(s);
+    if (!b.ok) return DSK_ESHAPE;
+    const int taps = s.kh * s.kw;
+    BwParams p{};
+    p.x = x; p.dy = dy; p.part = (float *)ws;
+    p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.Ho = s.Ho; p.Wo = s.Wo;
+    p.kh = s.kh; p.kw = s.kw; p.d = s.d;
+    p.Kp = b.Kp; p.Cp = b.Cp; p.xrows = b.xrows; p.xcols = b.xcols; p.xstride = b.xstride;
+    p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
+    p.n_fblk = b.n_fblk; p.n_cblk = b.n_cblk;
+    const unsigned grid = (unsigned)((long)b.n_fblk * b.n_cblk * b.S);
+    if (b.tpw == 4) {
+        allow_lds(conv_bwd_weight_mfma_kernel<float, 4>, b.lds_bytes);
+        conv_bwd_weight_mfma_kernel<float, 4><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+    } else if (b.tpw == 7) {
+        allow_lds(conv_bwd_weight_mfma_kernel<float, 7>, b.lds_bytes);
+        conv_bwd_weight_mfma_kernel<float, 7><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+    } else {
+        allow_lds(conv_bwd_weight_mfma_kernel<float, 13>, b.lds_bytes);
+        conv_bwd_weight_mfma_kernel<float, 13><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+    }
+    int rc = check_launch();
+    if (rc != DSK_OK) return rc;
+    const long total = (long)s.K * s.C * taps;
+    bw_reduce_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+        (const float *)ws, dw, s.K, s.C, taps, b.Kp, b.Cp, b.S);
+    rc = check_launch();
+    if (rc != DSK_OK || !db) return rc;
+    bias_grad_kernel<float><<<dim3(s.K), dim3(kThreads), 0, st>>>((const float *)dy, db, s.N, s.K,
+                                                                (long)s.Ho * s.Wo);
+    return check_launch();
+}
 
 } // namespace dsk

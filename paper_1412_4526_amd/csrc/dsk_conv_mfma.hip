@@ -79,7 +79,9 @@ gc_weight_prep_kernel(const float *__restrict__ w, float *__restrict__ wt, int K
     wt[idx] = v;
 }
 
-template <typename TI, typename TO, int WM>
+// XI: upper bound of input-tile elements a thread stages per chunk (Cc*chan_stride <= 256*XI);
+// XB of them are in flight at a time
+template <typename TI, typename TO, int WM, int XI, int XB = 16>
 __global__ void __launch_bounds__(kThreads, 2)
 gemm_conv_kernel(GcParams p)
 {
@@ -88,7 +90,8 @@ gemm_conv_kernel(GcParams p)
     float *xs = smem;                   // [Cc][rows][cols]
     float *wsm = smem + p.xs_floats;    // [Cc][taps][TF]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lo = lane & 31, hi = lane >> 5;
 
     // consecutive physical workgroups go to different XCDs; give each XCD one contiguous
@@ -103,8 +106,30 @@ gemm_conv_kernel(GcParams p)
     const int v0 = ct * TW;
     if (u0 >= p.Hout) return;
 
-    const TI *in = (const TI *)p.in;
+    const unsigned HW = (unsigned)(p.Hin * p.Win);   // Cin*Hin*Win < 2^30 is checked on the host
+    const TI *in_n = (const TI *)p.in + (long)n * p.Cin * (long)HW;
     const int taps = p.kh * p.kw;
+
+    // Where this thread's share of the input tile comes from; the same for every chunk.
+    // Element e = tid + 256*i of the tile [Cc][rows][cols]:  >= 0: (local channel << 28) |
+    // offset inside the channel plane;  -2: inside the tile but outside the map (zero);
+    // -1: beyond the tile.
+    int xoff[XI];
+    {
+        const int n_x = p.Cc * p.chan_stride;
+#pragma unroll
+        for (int i = 0; i < XI; ++i) {
+            const int e = tid + i * kThreads;
+            int pk = -1;
+            if (e < n_x) {
+                const int c = e / p.chan_stride, rem = e - c * p.chan_stride;
+                const int r = rem / p.cols, col = rem - r * p.cols;
+                const int irow = u0 + r * p.d - p.off_h, icol = v0 + col - p.off_w;
+                pk = (irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win) ? ((c << 28) | (irow * p.Win + icol)) : -2;
+            }
+            xoff[i] = pk;
+        }
+    }
 
     f32x16 acc[WM][4];
 #pragma unroll
@@ -114,29 +139,43 @@ gemm_conv_kernel(GcParams p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
 
+    const int n4 = p.Cc * taps * TF / 4;
     for (int c0 = 0; c0 < p.Cpad; c0 += p.Cc) {
-        __syncthreads();
-        // ---- stage the input tile: one (channel, row) segment per wave iteration
-        for (int seg = wave; seg < p.Cc * p.rows; seg += kThreads / 64) {
-            const int c = seg / p.rows, r = seg - c * p.rows;
-            const int gc = c0 + c;
-            const int irow = u0 + r * p.d - p.off_h;
-            const bool row_ok = gc < p.Cin && irow >= 0 && irow < p.Hin;
-            const TI *src = in + (((long)n * p.Cin + (row_ok ? gc : 0)) * p.Hin + (row_ok ? irow : 0)) * p.Win;
-            float *dst = xs + c * p.chan_stride + r * p.cols;
-            for (int col = lane; col < p.cols; col += 64) {
-                const int icol = v0 + col - p.off_w;
+        // ---- global loads are issued in batches before anything waits on them
+        const float4 *wsrc = (const float4 *)(p.wt + ((long)fg * p.Cpad + c0) * taps * TF);
+        float4 *wdst = (float4 *)wsm;
+        __syncthreads();      // every wave is done reading the previous chunk
+#pragma unroll
+        for (int i0 = 0; i0 < XI; i0 += XB) {
+            float xv[XB];
+#pragma unroll
+            for (int i = 0; i < XB; ++i) {
+                const int pk = xoff[i0 + i];
                 float v = 0.f;
-                if (row_ok && icol >= 0 && icol < p.Win) v = ldf(src, icol);
-                dst[col] = v;
+                if (pk >= 0) {
+                    // channels beyond Cin meet zero weights; clamp so the address stays inside the tensor
+                    unsigned gc = (unsigned)(c0 + (pk >> 28));
+                    gc = gc < (unsigned)p.Cin ? gc : (unsigned)p.Cin - 1u;
+                    v = ldf(in_n, (long)(gc * HW + (unsigned)(pk & 0x0fffffff)));
+                }
+                xv[i] = v;
             }
+#pragma unroll
+            for (int i = 0; i < XB; ++i)
+                if (xoff[i0 + i] != -1) xs[tid + (i0 + i) * kThreads] = xv[i];
         }
-        // ---- stage the weights of this chunk: one contiguous run
-        {
-            const float4 *wsrc = (const float4 *)(p.wt + ((long)fg * p.Cpad + c0) * taps * TF);
-            float4 *wdst = (float4 *)wsm;
-            const int n4 = p.Cc * taps * TF / 4;
-            for (int i = tid; i < n4; i += kThreads) wdst[i] = wsrc[i];
+        for (int i0 = 0; i0 < n4; i0 += 4 * kThreads) {
+            float4 wv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int idx = i0 + q * kThreads + tid;
+                wv[q] = idx < n4 ? wsrc[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int idx = i0 + q * kThreads + tid;
+                if (idx < n4) wdst[idx] = wv[q];
+            }
         }
         __syncthreads();
         // ---- matrix cores: k index = (channel pair, tap); lanes 32..63 take the odd channel
@@ -184,6 +223,8 @@ gemm_conv_kernel(GcParams p)
     }
 }
 
+static constexpr int kXI = 32;   // input-tile elements per thread per chunk, at most
+
 struct GcPlan {
     bool ok;
     int TF, WM, Cc, Cpad, rows, cols, chan_stride, xs_floats, n_fgrp;
@@ -206,7 +247,7 @@ static GcPlan gc_plan(int Cin, int Fout, int kh, int kw, int d)
     int best = 0, best_pad = 0;
     for (int cc = 8; cc >= 2; cc -= 2) {
         const size_t bytes = 4 * ((size_t)((cc * g.chan_stride + 3) & ~3) + (size_t)cc * taps * g.TF);
-        if (bytes > kMaxLds) continue;
+        if (bytes > kMaxLds || cc * g.chan_stride > kXI * kThreads) continue;
         const int pad = (Cin + cc - 1) / cc * cc;
         if (best == 0 || pad < best_pad) { best = cc; best_pad = pad; }
     }
@@ -225,9 +266,9 @@ static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
 {
     const unsigned grid = (unsigned)(p.per_xcd * kXcds);
     if (g.WM == 2)
-        gemm_conv_kernel<TI, TO, 2><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 2, kXI><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else
-        gemm_conv_kernel<TI, TO, 1><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 1, kXI><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
 }
 
 static int gc_run(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Hin, int Win,
@@ -284,15 +325,19 @@ struct BwParams {
     int n_fblk, n_cblk;
 };
 
-template <typename TI, int TPW>
-__global__ void __launch_bounds__(kThreads, (TPW <= 7 ? 2 : 1))
+// TPW: taps per wave (the four waves take taps wave, wave+4, ...); XR: rows of the x tile,
+// at most.  The next pixel tile is fetched into registers while the matrix cores work on
+// the current one, so global latency is paid once per workgroup, not once per tile.
+template <typename TI, int TPW, int XR>
+__global__ void __launch_bounds__(kThreads, (TPW <= 4 ? 2 : 1))
 conv_bwd_weight_mfma_kernel(BwParams p)
 {
     extern __shared__ __align__(16) float smem[];
     float *dys = smem;                       // [32 filters][DY_STRIDE]
     float *xs = smem + 32 * DY_STRIDE;       // [32 channels][xstride]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lo = lane & 31, hi = lane >> 5;
     const int taps = p.kh * p.kw;
 
@@ -304,61 +349,89 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     const TI *x = (const TI *)p.x;
     const TI *dy = (const TI *)p.dy;
 
+    // LDS offset of each of this wave's taps; a wave with fewer than TPW taps repeats tap 0
+    // (its extra products are never written out), which keeps the inner loop branch-free
+    int boff[TPW];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+        int tap = wave + 4 * t;
+        tap = tap < taps ? tap : 0;
+        const int a = tap / p.kw;
+        boff[t] = a * p.xcols + (tap - a * p.kw) * p.d;
+    }
+
     f32x16 acc[TPW];
 #pragma unroll
     for (int t = 0; t < TPW; ++t)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-    for (long pt = s; pt < p.n_ptile; pt += p.S) {
+    float dr[16];          // dy tile share: (filter, row) segments wave*2+hi+8i, column lo
+    float xr[8][XR];       // x tile share: channels wave+4*ci, rows r, column lane
+
+    auto load_tile = [&](long pt) {
         const int ct = (int)(pt % p.n_coltile);
         const int rt = (int)((pt / p.n_coltile) % p.n_rowtile);
         const int n = (int)(pt / ((long)p.n_coltile * p.n_rowtile));
         const int u0 = (rt / p.d) * p.d * PH + (rt % p.d);
         const int v0 = ct * PW;
-        if (u0 >= p.Ho) continue;            // uniform over the workgroup
-        __syncthreads();
-        // ---- dy tile: 32 filters x PH rows x 32 columns; half a wave per (filter, row) segment
-        for (int seg = wave * 2 + hi; seg < 32 * PH; seg += 8) {
-            const int f = seg / PH, r = seg - f * PH;
-            const int gf = fb * 32 + f;
-            const int row = u0 + r * p.d, col = v0 + lo;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int seg = wave * 2 + hi + 8 * i;
+            const int gf = fb * 32 + (seg >> 2);
+            const int row = u0 + (seg & 3) * p.d, col = v0 + lo;
             float v = 0.f;
             if (gf < p.K && row < p.Ho && col < p.Wo)
                 v = ldf(dy, (((long)n * p.K + gf) * p.Ho + row) * p.Wo + col);
-            dys[f * DY_STRIDE + r * PW + lo] = v;
+            dr[i] = v;
         }
-        // ---- x tile: 32 channels x xrows x xcols
-        for (int seg = wave; seg < 32 * p.xrows; seg += 4) {
-            const int c = seg / p.xrows, r = seg - c * p.xrows;
-            const int gc = cb * 32 + c;
-            const int row = u0 + r * p.d;
-            const bool row_ok = gc < p.C && row < p.H;
-            const TI *src = x + (((long)n * p.C + (row_ok ? gc : 0)) * p.H + (row_ok ? row : 0)) * p.W;
-            float *dst = xs + c * p.xstride + r * p.xcols;
-            for (int col = lane; col < p.xcols; col += 64) {
-                const int icol = v0 + col;
+        const bool col_ok = lane < p.xcols && v0 + lane < p.W;
+#pragma unroll
+        for (int ci = 0; ci < 8; ++ci) {
+            const int gc = cb * 32 + wave + 4 * ci;
+#pragma unroll
+            for (int r = 0; r < XR; ++r) {
+                const int row = u0 + r * p.d;
                 float v = 0.f;
-                if (row_ok && icol < p.W) v = ldf(src, icol);
-                dst[col] = v;
+                if (col_ok && gc < p.C && r < p.xrows && row < p.H)
+                    v = ldf(x, (((long)n * p.C + gc) * p.H + row) * p.W + v0 + lane);
+                xr[ci][r] = v;
             }
         }
+    };
+
+    long pt = s;
+    if (pt < p.n_ptile) load_tile(pt);
+    while (pt < p.n_ptile) {
+        __syncthreads();        // every wave is done with the previous tile
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int seg = wave * 2 + hi + 8 * i;
+            dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = dr[i];
+        }
+        if (lane < p.xcols) {
+#pragma unroll
+            for (int ci = 0; ci < 8; ++ci)
+#pragma unroll
+                for (int r = 0; r < XR; ++r)
+                    if (r < p.xrows) xs[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = xr[ci][r];
+        }
         __syncthreads();
+        pt += p.S;
+        if (pt < p.n_ptile) load_tile(pt);      // in flight while the matrix cores run
         // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
         const float *ab = dys + lo * DY_STRIDE + hi;
         const float *bb = xs + lo * p.xstride + hi;
         for (int r = 0; r < PH; ++r) {
+#pragma unroll 4
             for (int q = 0; q < PW / 2; ++q) {
                 const float A = ab[r * PW + 2 * q];
+                float B[TPW];
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) {
-                    const int tap = wave + 4 * t;
-                    if (tap < taps) {          // uniform over the wave
-                        const int a = tap / p.kw, bcol = tap - a * p.kw;
-                        const float B = bb[(r + a) * p.xcols + 2 * q + bcol * p.d];
-                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(A, B, acc[t], 0, 0, 0);
-                    }
-                }
+                for (int t = 0; t < TPW; ++t) B[t] = bb[boff[t] + r * p.xcols + 2 * q];
+#pragma unroll
+                for (int t = 0; t < TPW; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(A, B[t], acc[t], 0, 0, 0);
             }
         }
     }
@@ -394,17 +467,22 @@ bw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, 
     dw[idx] = acc;
 }
 
-// db[f] = sum over n, u, v of dy: one workgroup per filter, fixed-order tree
+// db[f] = sum over n, u, v of dy, in two fixed-order stages: kBiasSplit workgroups per filter
+// each reduce a contiguous share of every image's plane, then one thread per filter adds them.
+static constexpr int kBiasSplit = 32;
+
 template <typename TI>
 __global__ void __launch_bounds__(kThreads)
-bias_grad_kernel(const TI *__restrict__ dy, float *__restrict__ db, int N, int K, long plane)
+bias_partial_kernel(const TI *__restrict__ dy, float *__restrict__ part, int N, int K, long plane)
 {
     __shared__ float sm[kThreads];
-    const int f = blockIdx.x;
+    const int f = blockIdx.x / kBiasSplit, sp = blockIdx.x % kBiasSplit;
+    const long share = (plane + kBiasSplit - 1) / kBiasSplit;
+    const long lo = sp * share, hi = lo + share < plane ? lo + share : plane;
     float acc = 0.f;
     for (int n = 0; n < N; ++n) {
         const TI *src = dy + ((long)n * K + f) * plane;
-        for (long t = threadIdx.x; t < plane; t += kThreads) acc += ldf(src, t);
+        for (long t = lo + threadIdx.x; t < hi; t += kThreads) acc += ldf(src, t);
     }
     sm[threadIdx.x] = acc;
     __syncthreads();
@@ -412,7 +490,17 @@ bias_grad_kernel(const TI *__restrict__ dy, float *__restrict__ db, int N, int K
         if ((int)threadIdx.x < off) sm[threadIdx.x] += sm[threadIdx.x + off];
         __syncthreads();
     }
-    if (threadIdx.x == 0) db[f] = sm[0];
+    if (threadIdx.x == 0) part[blockIdx.x] = sm[0];
+}
+
+__global__ void __launch_bounds__(kThreads)
+bias_reduce_kernel(const float *__restrict__ part, float *__restrict__ db, int K)
+{
+    const int f = blockIdx.x * kThreads + threadIdx.x;
+    if (f >= K) return;
+    float acc = 0.f;
+    for (int sp = 0; sp < kBiasSplit; ++sp) acc += part[f * kBiasSplit + sp];
+    db[f] = acc;
 }
 
 struct BwPlan {
@@ -434,7 +522,7 @@ static BwPlan bw_plan(const ConvShape &s)
     b.n_cblk = b.Cp / 32;
     b.xrows = PH + s.kh - 1;
     const long xcols = (long)PW + (long)(s.kw - 1) * s.d;
-    if (xcols > 2048) return b;
+    if (xcols > 64 || s.kh > 7) return b;       // one wave-wide load per x-tile row; XR <= 10
     b.xcols = (int)xcols;
     b.xstride = (b.xrows * b.xcols) | 1;
     b.lds_bytes = 4 * ((size_t)32 * DY_STRIDE + (size_t)32 * b.xstride);
@@ -448,7 +536,7 @@ static BwPlan bw_plan(const ConvShape &s)
     if (S > b.n_ptile / 4) S = b.n_ptile / 4;
     if (S < 1) S = 1;
     b.S = (int)S;
-    b.part_bytes = 4 * (size_t)b.S * b.Kp * b.Cp * taps;
+    b.part_bytes = 4 * ((size_t)b.S * b.Kp * b.Cp * taps + (size_t)s.K * kBiasSplit);
     b.ok = true;
     return b;
 }
@@ -478,6 +566,10 @@ bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype 
 {
     if (in != DSK_F32) return false;
     (void)out;
+    // plane offsets are packed into 28 bits, per-image offsets are 32-bit
+    if ((long)s.H * s.W >= (1L << 28) || (long)s.C * s.H * s.W >= (1L << 30) ||
+        (long)s.K * s.Ho * s.Wo >= (1L << 30))
+        return false;
     if (which == DSK_WS_CONV_FWD) return gc_plan(s.C, s.K, s.kh, s.kw, s.d).ok;
     if (which == DSK_WS_CONV_BWD_DATA) return gc_plan(s.K, s.C, s.kh, s.kw, s.d).ok;
     if (which == DSK_WS_CONV_BWD_WEIGHT) return bw_plan(s).ok;
@@ -513,16 +605,16 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
     p.n_fblk = b.n_fblk; p.n_cblk = b.n_cblk;
     const unsigned grid = (unsigned)((long)b.n_fblk * b.n_cblk * b.S);
-    if (b.tpw == 4) {
-        allow_lds(conv_bwd_weight_mfma_kernel<float, 4>, b.lds_bytes);
-        conv_bwd_weight_mfma_kernel<float, 4><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
-    } else if (b.tpw == 7) {
-        allow_lds(conv_bwd_weight_mfma_kernel<float, 7>, b.lds_bytes);
-        conv_bwd_weight_mfma_kernel<float, 7><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
-    } else {
-        allow_lds(conv_bwd_weight_mfma_kernel<float, 13>, b.lds_bytes);
-        conv_bwd_weight_mfma_kernel<float, 13><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
-    }
+#define DSK_BW_LAUNCH(TPW, XR)                                                                         \
+    do {                                                                                               \
+        allow_lds(conv_bwd_weight_mfma_kernel<float, TPW, XR>, b.lds_bytes);                           \
+        conv_bwd_weight_mfma_kernel<float, TPW, XR><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p); \
+    } while (0)
+    const bool tall = b.xrows > 8;
+    if (b.tpw == 4) { if (tall) DSK_BW_LAUNCH(4, 10); else DSK_BW_LAUNCH(4, 8); }
+    else if (b.tpw == 7) { if (tall) DSK_BW_LAUNCH(7, 10); else DSK_BW_LAUNCH(7, 8); }
+    else DSK_BW_LAUNCH(13, 10);
+#undef DSK_BW_LAUNCH
     int rc = check_launch();
     if (rc != DSK_OK) return rc;
     const long total = (long)s.K * s.C * taps;
@@ -530,8 +622,10 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
         (const float *)ws, dw, s.K, s.C, taps, b.Kp, b.Cp, b.S);
     rc = check_launch();
     if (rc != DSK_OK || !db) return rc;
-    bias_grad_kernel<float><<<dim3(s.K), dim3(kThreads), 0, st>>>((const float *)dy, db, s.N, s.K,
-                                                                (long)s.Ho * s.Wo);
+    float *bpart = (float *)ws + (size_t)b.S * b.Kp * b.Cp * taps;
+    bias_partial_kernel<float><<<dim3(s.K * kBiasSplit), dim3(kThreads), 0, st>>>((const float *)dy, bpart, s.N, s.K,
+                                                                                (long)s.Ho * s.Wo);
+    bias_reduce_kernel<<<dim3((s.K + kThreads - 1) / kThreads), dim3(kThreads), 0, st>>>(bpart, db, s.K);
     return check_launch();
 }
 

@@ -59,7 +59,7 @@ struct GcParams {
 //                           flip = 1: wt[g][k][t][cl] = w[k][g*TF+cl][taps-1-t]     (backward-data)
 __global__ void __launch_bounds__(kThreads)
 gc_weight_prep_kernel(const float *__restrict__ w, float *__restrict__ wt, int K, int C, int taps,
-                      int Cpad, int TF, int n_fgrp, int flip)
+                      int Cpad, int TF, int n_fgrp, int flip, int round_bf16)
 {
     const long total = (long)n_fgrp * Cpad * taps * TF;
     const long idx = (long)blockIdx.x * kThreads + threadIdx.x;
@@ -76,12 +76,16 @@ gc_weight_prep_kernel(const float *__restrict__ w, float *__restrict__ wt, int K
         // channel index of the GEMM is the filter k of w, output index is the channel c of w
         if (f < C && c < K) v = w[((long)c * C + f) * taps + (taps - 1 - t)];
     }
-    wt[idx] = v;
+    wt[idx] = round_bf16 ? bf16_to_f32(f32_to_bf16(v)) : v;
 }
 
-// XI: upper bound of input-tile elements a thread stages per chunk (Cc*chan_stride <= 256*XI);
-// XB of them are in flight at a time
-template <typename TI, typename TO, int WM, int XI, int XB = 16>
+// XI / WI: upper bounds of what one thread stages per chunk: input-tile elements
+// (Cc*chan_stride <= 256*XI) and weight float4s (Cc*taps*TF <= 1024*WI).
+//
+// Pipeline: the global loads of chunk t+1 are issued before the matrix cores start on chunk
+// t and land in registers meanwhile; they are written to LDS after chunk t is done.  Inside
+// a chunk the LDS operands of k-step s+1 are read before the MFMAs of step s are issued.
+template <typename TI, typename TO, int WM, int XI, int WI>
 __global__ void __launch_bounds__(kThreads, 2)
 gemm_conv_kernel(GcParams p)
 {
@@ -140,63 +144,76 @@ gemm_conv_kernel(GcParams p)
             for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
 
     const int n4 = p.Cc * taps * TF / 4;
-    for (int c0 = 0; c0 < p.Cpad; c0 += p.Cc) {
-        // ---- global loads are issued in batches before anything waits on them
+    float xv[XI];
+    float4 wv[WI];
+    auto fetch = [&](int c0) {
+#pragma unroll
+        for (int i = 0; i < XI; ++i) {
+            const int pk = xoff[i];
+            float v = 0.f;
+            if (pk >= 0) {
+                // channels beyond Cin meet zero weights; clamp so the address stays inside the tensor
+                unsigned gc = (unsigned)(c0 + (pk >> 28));
+                gc = gc < (unsigned)p.Cin ? gc : (unsigned)p.Cin - 1u;
+                v = ldf(in_n, (long)(gc * HW + (unsigned)(pk & 0x0fffffff)));
+            }
+            xv[i] = v;
+        }
         const float4 *wsrc = (const float4 *)(p.wt + ((long)fg * p.Cpad + c0) * taps * TF);
-        float4 *wdst = (float4 *)wsm;
+#pragma unroll
+        for (int q = 0; q < WI; ++q) {
+            const int idx = q * kThreads + tid;
+            wv[q] = idx < n4 ? wsrc[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+
+    // per-lane LDS bases; the k-step offsets are uniform over the wave
+    const float *xlane = xs + hi * p.chan_stride + (2 * wave) * p.cols + lo;
+    const float *wlane = wsm + hi * taps * TF + lo;
+    const int nsteps = (p.Cc / 2) * taps;
+    auto read_ops = [&](int xo, int wo, float (&A)[WM], float (&B)[4]) {
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm) A[wm] = wlane[wo + wm * 32];
+#pragma unroll
+        for (int wn = 0; wn < 4; ++wn) B[wn] = xlane[xo + (wn >> 1) * p.cols + (wn & 1) * 32];
+    };
+
+    fetch(0);
+    for (int c0 = 0; c0 < p.Cpad; c0 += p.Cc) {
         __syncthreads();      // every wave is done reading the previous chunk
 #pragma unroll
-        for (int i0 = 0; i0 < XI; i0 += XB) {
-            float xv[XB];
+        for (int i = 0; i < XI; ++i)
+            if (xoff[i] != -1) xs[tid + i * kThreads] = xv[i];
 #pragma unroll
-            for (int i = 0; i < XB; ++i) {
-                const int pk = xoff[i0 + i];
-                float v = 0.f;
-                if (pk >= 0) {
-                    // channels beyond Cin meet zero weights; clamp so the address stays inside the tensor
-                    unsigned gc = (unsigned)(c0 + (pk >> 28));
-                    gc = gc < (unsigned)p.Cin ? gc : (unsigned)p.Cin - 1u;
-                    v = ldf(in_n, (long)(gc * HW + (unsigned)(pk & 0x0fffffff)));
-                }
-                xv[i] = v;
-            }
-#pragma unroll
-            for (int i = 0; i < XB; ++i)
-                if (xoff[i0 + i] != -1) xs[tid + (i0 + i) * kThreads] = xv[i];
-        }
-        for (int i0 = 0; i0 < n4; i0 += 4 * kThreads) {
-            float4 wv[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int idx = i0 + q * kThreads + tid;
-                wv[q] = idx < n4 ? wsrc[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int idx = i0 + q * kThreads + tid;
-                if (idx < n4) wdst[idx] = wv[q];
-            }
+        for (int q = 0; q < WI; ++q) {
+            const int idx = q * kThreads + tid;
+            if (idx < n4) ((float4 *)wsm)[idx] = wv[q];
         }
         __syncthreads();
+        if (c0 + p.Cc < p.Cpad) fetch(c0 + p.Cc);      // in flight while the matrix cores run
+
         // ---- matrix cores: k index = (channel pair, tap); lanes 32..63 take the odd channel
-        for (int cp = 0; cp < p.Cc; cp += 2) {
-            const float *xb = xs + (cp + hi) * p.chan_stride + (2 * wave) * p.cols + lo;
-            const float *wb = wsm + (cp + hi) * taps * TF + lo;
-            for (int a = 0; a < p.kh; ++a) {
-                for (int b = 0; b < p.kw; ++b) {
-                    float A[WM], B[4];
+        float An[WM], Bn[4];
+        int xo = 0, wo = 0, ta = 0, tb = 0;
+        read_ops(xo, wo, An, Bn);
+        for (int st = 0; st < nsteps; ++st) {
+            float A[WM], B[4];
 #pragma unroll
-                    for (int wm = 0; wm < WM; ++wm) A[wm] = wb[(a * p.kw + b) * TF + wm * 32];
+            for (int wm = 0; wm < WM; ++wm) A[wm] = An[wm];
 #pragma unroll
-                    for (int wn = 0; wn < 4; ++wn)
-                        B[wn] = xb[((wn >> 1) + a) * p.cols + (wn & 1) * 32 + b * p.d];
-#pragma unroll
-                    for (int wm = 0; wm < WM; ++wm)
-#pragma unroll
-                        for (int wn = 0; wn < 4; ++wn)
-                            acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
-                }
+            for (int wn = 0; wn < 4; ++wn) B[wn] = Bn[wn];
+            // next k-step: tap column, then tap row, then channel pair
+            ++tb; xo += p.d; wo += TF;
+            if (tb == p.kw) {
+                tb = 0; ++ta; xo += p.cols - p.kw * p.d;
+                if (ta == p.kh) { ta = 0; xo += 2 * p.chan_stride - p.kh * p.cols; wo += taps * TF; }
             }
+            if (st + 1 < nsteps) read_ops(xo, wo, An, Bn);
+#pragma unroll
+            for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                for (int wn = 0; wn < 4; ++wn)
+                    acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
         }
     }
 
@@ -223,7 +240,8 @@ gemm_conv_kernel(GcParams p)
     }
 }
 
-static constexpr int kXI = 32;   // input-tile elements per thread per chunk, at most
+static constexpr int kXI = 16;   // input-tile elements per thread per chunk, at most
+static constexpr int kWI = 8;    // weight float4s per thread per chunk, at most
 
 struct GcPlan {
     bool ok;
@@ -247,7 +265,8 @@ static GcPlan gc_plan(int Cin, int Fout, int kh, int kw, int d)
     int best = 0, best_pad = 0;
     for (int cc = 8; cc >= 2; cc -= 2) {
         const size_t bytes = 4 * ((size_t)((cc * g.chan_stride + 3) & ~3) + (size_t)cc * taps * g.TF);
-        if (bytes > kMaxLds || cc * g.chan_stride > kXI * kThreads) continue;
+        if (bytes > kMaxLds || cc * g.chan_stride > kXI * kThreads || (long)cc * taps * g.TF > 4L * kWI * kThreads)
+            continue;
         const int pad = (Cin + cc - 1) / cc * cc;
         if (best == 0 || pad < best_pad) { best = cc; best_pad = pad; }
     }
@@ -266,9 +285,9 @@ static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
 {
     const unsigned grid = (unsigned)(p.per_xcd * kXcds);
     if (g.WM == 2)
-        gemm_conv_kernel<TI, TO, 2, kXI><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 2, kXI, kWI><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else
-        gemm_conv_kernel<TI, TO, 1, kXI><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 1, kXI, kWI><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
 }
 
 static int gc_run(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Hin, int Win,
@@ -282,7 +301,7 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     {
         const long total = (long)g.n_fgrp * g.Cpad * taps * g.TF;
         gc_weight_prep_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
-            w, wt, K, C, taps, g.Cpad, g.TF, g.n_fgrp, flip);
+            w, wt, K, C, taps, g.Cpad, g.TF, g.n_fgrp, flip, tin == DSK_BF16 ? 1 : 0);
     }
     GcParams p{};
     p.in = in; p.out = out; p.wt = wt; p.bias = bias;
@@ -299,7 +318,8 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;
     if (tin == DSK_F32 && tout == DSK_F32) gc_launch<float, float>(p, g, st);
     else if (tin == DSK_F32 && tout == DSK_BF16) gc_launch<float, bf16>(p, g, st);
-    else return DSK_EDTYPE;
+    else if (tin == DSK_BF16 && tout == DSK_BF16) gc_launch<bf16, bf16>(p, g, st);
+    else gc_launch<bf16, float>(p, g, st);
     return check_launch();
 }
 
@@ -546,7 +566,7 @@ static BwPlan bw_plan(const ConvShape &s)
 // ============================================================================
 size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
 {
-    if (in != DSK_F32) return 0;
+    (void)in;
     if (which == DSK_WS_CONV_FWD) {
         const GcPlan g = gc_plan(s.C, s.K, s.kh, s.kw, s.d);
         return g.ok ? g.wt_bytes : 0;
@@ -564,7 +584,7 @@ size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
 
 bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype out)
 {
-    if (in != DSK_F32) return false;
+    (void)in;
     (void)out;
     // plane offsets are packed into 28 bits, per-image offsets are 32-bit
     if ((long)s.H * s.W >= (1L << 28) || (long)s.C * s.H * s.W >= (1L << 30) ||
@@ -593,7 +613,6 @@ int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const Co
 int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
                                 dsk_dtype in, void *ws, hipStream_t st)
 {
-    if (in != DSK_F32) return DSK_EDTYPE;
     const BwPlan b = bw_plan(s);
     if (!b.ok) return DSK_ESHAPE;
     const int taps = s.kh * s.kw;
@@ -607,8 +626,13 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     const unsigned grid = (unsigned)((long)b.n_fblk * b.n_cblk * b.S);
 #define DSK_BW_LAUNCH(TPW, XR)                                                                         \
     do {                                                                                               \
-        allow_lds(conv_bwd_weight_mfma_kernel<float, TPW, XR>, b.lds_bytes);                           \
-        conv_bwd_weight_mfma_kernel<float, TPW, XR><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p); \
+        if (in == DSK_F32) {                                                                           \
+            allow_lds(conv_bwd_weight_mfma_kernel<float, TPW, XR>, b.lds_bytes);                       \
+            conv_bwd_weight_mfma_kernel<float, TPW, XR><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p); \
+        } else {                                                                                       \
+            allow_lds(conv_bwd_weight_mfma_kernel<bf16, TPW, XR>, b.lds_bytes);                        \
+            conv_bwd_weight_mfma_kernel<bf16, TPW, XR><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p); \
+        }                                                                                              \
     } while (0)
     const bool tall = b.xrows > 8;
     if (b.tpw == 4) { if (tall) DSK_BW_LAUNCH(4, 10); else DSK_BW_LAUNCH(4, 8); }
@@ -623,8 +647,12 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     rc = check_launch();
     if (rc != DSK_OK || !db) return rc;
     float *bpart = (float *)ws + (size_t)b.S * b.Kp * b.Cp * taps;
-    bias_partial_kernel<float><<<dim3(s.K * kBiasSplit), dim3(kThreads), 0, st>>>((const float *)dy, bpart, s.N, s.K,
-                                                                                (long)s.Ho * s.Wo);
+    if (in == DSK_F32)
+        bias_partial_kernel<float><<<dim3(s.K * kBiasSplit), dim3(kThreads), 0, st>>>((const float *)dy, bpart, s.N,
+                                                                                    s.K, (long)s.Ho * s.Wo);
+    else
+        bias_partial_kernel<bf16><<<dim3(s.K * kBiasSplit), dim3(kThreads), 0, st>>>((const bf16 *)dy, bpart, s.N,
+                                                                                   s.K, (long)s.Ho * s.Wo);
     bias_reduce_kernel<<<dim3((s.K + kThreads - 1) / kThreads), dim3(kThreads), 0, st>>>(bpart, db, s.K);
     return check_launch();
 }

@@ -122,10 +122,18 @@ MARGIN = 1e-6
 def _test_mask(net, params, xpad, N, H, W, count, storage):
     """Pixels for the gradient check, chosen by the oracle alone: seeded candidates whose
     patches stay MARGIN away from every gradient discontinuity.  Returns (pix sorted, scores)."""
-    cand = sample_pixels(N, H, W, 4 * count, seed=2)
-    sc, mg = oracle.scan_forward(net, params, xpad, cand, storage=storage, want_margin=True)
-    keep = np.flatnonzero(mg >= MARGIN)[:count]
-    assert len(keep) >= count // 2, "too few unambiguous patches: %d" % len(keep)
+    if storage == oracle.STORE_BF16:
+        # bf16 storage: a value that straddles a bf16 rounding boundary already perturbs later
+        # layers by 2^-8 relative, far above any margin one could ask for; the 2e-2 bar of the
+        # bf16 path absorbs the occasional flipped gate, so every candidate is kept
+        cand = sample_pixels(N, H, W, count, seed=2)
+        sc = oracle.scan_forward(net, params, xpad, cand, storage=storage)
+        keep = np.arange(len(cand))
+    else:
+        cand = sample_pixels(N, H, W, 4 * count, seed=2)
+        sc, mg = oracle.scan_forward(net, params, xpad, cand, storage=storage, want_margin=True)
+        keep = np.flatnonzero(mg >= MARGIN)[:count]
+        assert len(keep) >= count // 2, "too few unambiguous patches: %d" % len(keep)
     pix, sc = cand[keep], sc[keep]
     order = np.lexsort((pix[:, 2], pix[:, 1], pix[:, 0]))
     return pix[order], sc[order]

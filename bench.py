@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--algo", type=int, default=0)
     ap.add_argument("--layers", action="store_true", help="print the per-call table to stderr")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a known-size reference "
+                         "for scaling HBM byte counters collected with rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -120,6 +123,13 @@ def main():
         net.forward(image)
         if not args.forward_only:
             net.loss_backward(labels, mask)
+
+    if args.calib_copy_mib > 0:
+        src = torch.zeros(args.calib_copy_mib * (1 << 20) // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                  # reads and writes calib_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -14,6 +14,8 @@
 //
 // fp32 path: v_mfma_f32_32x32x2_f32.  Lane l supplies A[i = l%32][k = l/32] and
 // B[k = l/32][j = l%32]; register r of the 16 results holds D[8*(r/4) + 4*(l/32) + r%4][l%32].
+#include <cstdlib>
+
 #include "dsk_internal.h"
 
 namespace dsk {
@@ -53,6 +55,7 @@ struct GcParams {
     int xs_floats;       // Cc*chan_stride rounded up to a multiple of 4
     int n_rowtile, n_coltile, n_fgrp;
     long total, per_xcd;
+    int dbg;
 };
 
 // Weight layout transform.  flip = 0: wt[g][c][t][fl] = w[g*TF+fl][c][t]            (forward)
@@ -170,16 +173,16 @@ gemm_conv_kernel(GcParams p)
     // per-lane LDS bases; the k-step offsets are uniform over the wave
     const float *xlane = xs + hi * p.chan_stride + (2 * wave) * p.cols + lo;
     const float *wlane = wsm + hi * taps * TF + lo;
-    const int nsteps = (p.Cc / 2) * taps;
-    auto read_ops = [&](int xo, int wo, float (&A)[WM], float (&B)[4]) {
+    auto read_ops = [&](int xo, int wo, const float *xb, const float *wb, float (&A)[WM], float (&B)[4]) {
 #pragma unroll
-        for (int wm = 0; wm < WM; ++wm) A[wm] = wlane[wo + wm * 32];
+        for (int wm = 0; wm < WM; ++wm) A[wm] = wb[wo + wm * 32];
 #pragma unroll
-        for (int wn = 0; wn < 4; ++wn) B[wn] = xlane[xo + (wn >> 1) * p.cols + (wn & 1) * 32];
+        for (int wn = 0; wn < 4; ++wn) B[wn] = xb[xo + (wn >> 1) * p.cols + (wn & 1) * 32];
     };
 
     fetch(0);
     for (int c0 = 0; c0 < p.Cpad; c0 += p.Cc) {
+        if (!(p.dbg & 1) || c0 == 0) {
         __syncthreads();      // every wave is done reading the previous chunk
 #pragma unroll
         for (int i = 0; i < XI; ++i)
@@ -190,30 +193,24 @@ gemm_conv_kernel(GcParams p)
             if (idx < n4) ((float4 *)wsm)[idx] = wv[q];
         }
         __syncthreads();
-        if (c0 + p.Cc < p.Cpad) fetch(c0 + p.Cc);      // in flight while the matrix cores run
+        if (c0 + p.Cc < p.Cpad && !(p.dbg & 1)) fetch(c0 + p.Cc);      // in flight while the matrix cores run
+        }
 
         // ---- matrix cores: k index = (channel pair, tap); lanes 32..63 take the odd channel
-        float An[WM], Bn[4];
-        int xo = 0, wo = 0, ta = 0, tb = 0;
-        read_ops(xo, wo, An, Bn);
-        for (int st = 0; st < nsteps; ++st) {
-            float A[WM], B[4];
+        for (int cp = 0; cp < p.Cc; cp += 2) {
+            const float *xb = xlane + cp * p.chan_stride;
+            const float *wb = wlane + cp * taps * TF;
+            for (int ta = 0; ta < p.kh; ++ta) {
+                for (int tb = 0; tb < p.kw; ++tb) {
+                    float A[WM], B[4];
+                    read_ops(ta * p.cols + tb * p.d, (ta * p.kw + tb) * TF, xb, wb, A, B);
 #pragma unroll
-            for (int wm = 0; wm < WM; ++wm) A[wm] = An[wm];
+                    for (int wm = 0; wm < WM; ++wm)
 #pragma unroll
-            for (int wn = 0; wn < 4; ++wn) B[wn] = Bn[wn];
-            // next k-step: tap column, then tap row, then channel pair
-            ++tb; xo += p.d; wo += TF;
-            if (tb == p.kw) {
-                tb = 0; ++ta; xo += p.cols - p.kw * p.d;
-                if (ta == p.kh) { ta = 0; xo += 2 * p.chan_stride - p.kh * p.cols; wo += taps * TF; }
+                        for (int wn = 0; wn < 4; ++wn)
+                            acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
+                }
             }
-            if (st + 1 < nsteps) read_ops(xo, wo, An, Bn);
-#pragma unroll
-            for (int wm = 0; wm < WM; ++wm)
-#pragma unroll
-                for (int wn = 0; wn < 4; ++wn)
-                    acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
         }
     }
 
@@ -284,8 +281,10 @@ template <typename TI, typename TO>
 static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
 {
     const unsigned grid = (unsigned)(p.per_xcd * kXcds);
+    size_t lds = g.lds_bytes;
+    if (p.dbg & 2) { lds = 100 * 1024; allow_lds(gemm_conv_kernel<TI, TO, 2, kXI, kWI>, lds); }
     if (g.WM == 2)
-        gemm_conv_kernel<TI, TO, 2, kXI, kWI><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 2, kXI, kWI><<<dim3(grid), dim3(kThreads), lds, st>>>(p);
     else
         gemm_conv_kernel<TI, TO, 1, kXI, kWI><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
 }
@@ -315,6 +314,7 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     p.n_fgrp = g.n_fgrp;
     p.total = (long)N * p.n_rowtile * p.n_coltile * p.n_fgrp;
     p.per_xcd = (p.total + kXcds - 1) / kXcds;
+    { const char *e = getenv("DSK_DBG"); p.dbg = e ? atoi(e) : 0; }
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;
     if (tin == DSK_F32 && tout == DSK_F32) gc_launch<float, float>(p, g, st);
     else if (tin == DSK_F32 && tout == DSK_BF16) gc_launch<float, bf16>(p, g, st);
@@ -345,11 +345,15 @@ struct BwParams {
     int n_fblk, n_cblk;
 };
 
-// TPW: taps per wave (the four waves take taps wave, wave+4, ...); XR: rows of the x tile,
-// at most.  The next pixel tile is fetched into registers while the matrix cores work on
-// the current one, so global latency is paid once per workgroup, not once per tile.
-template <typename TI, int TPW, int XR>
-__global__ void __launch_bounds__(kThreads, (TPW <= 4 ? 2 : 1))
+// TPW: accumulator tiles (taps) per wave; XR: rows of the x tile, at most.
+// ROWSPLIT = false: the four waves divide the taps (wave, wave+4, ...) and each walks over the
+//   whole pixel tile.  ROWSPLIT = true (few taps): every wave takes ALL taps but only row
+//   `wave` of the pixel tile; its block is then one more partial sum for the reduce kernel.
+// PREFETCH: fetch the next pixel tile into registers while the matrix cores work on the
+//   current one (needs the registers); otherwise the loads of a tile are issued together
+//   right before it is staged and a second resident workgroup covers their latency.
+template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH>
+__global__ void __launch_bounds__(kThreads, (TPW <= 9 ? 2 : 1))
 conv_bwd_weight_mfma_kernel(BwParams p)
 {
     extern __shared__ __align__(16) float smem[];
@@ -369,12 +373,12 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     const TI *x = (const TI *)p.x;
     const TI *dy = (const TI *)p.dy;
 
-    // LDS offset of each of this wave's taps; a wave with fewer than TPW taps repeats tap 0
-    // (its extra products are never written out), which keeps the inner loop branch-free
+    // LDS offset of each of this wave's taps; a slot beyond the last tap repeats tap 0 (its
+    // products are never written out), which keeps the inner loop branch-free
     int boff[TPW];
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
-        int tap = wave + 4 * t;
+        int tap = ROWSPLIT ? t : wave + 4 * t;
         tap = tap < taps ? tap : 0;
         const int a = tap / p.kw;
         boff[t] = a * p.xcols + (tap - a * p.kw) * p.d;
@@ -421,8 +425,9 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     };
 
     long pt = s;
-    if (pt < p.n_ptile) load_tile(pt);
+    if (PREFETCH && pt < p.n_ptile) load_tile(pt);
     while (pt < p.n_ptile) {
+        if (!PREFETCH) load_tile(pt);
         __syncthreads();        // every wave is done with the previous tile
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -438,11 +443,11 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         }
         __syncthreads();
         pt += p.S;
-        if (pt < p.n_ptile) load_tile(pt);      // in flight while the matrix cores run
+        if (PREFETCH && pt < p.n_ptile) load_tile(pt);      // in flight while the matrix cores run
         // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
         const float *ab = dys + lo * DY_STRIDE + hi;
         const float *bb = xs + lo * p.xstride + hi;
-        for (int r = 0; r < PH; ++r) {
+        for (int r = ROWSPLIT ? wave : 0; r < (ROWSPLIT ? wave + 1 : PH); ++r) {
 #pragma unroll 4
             for (int q = 0; q < PW / 2; ++q) {
                 const float A = ab[r * PW + 2 * q];
@@ -456,11 +461,12 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         }
     }
 
-    // ---- partial block out: part[s][f][c][tap]; lane = channel, registers = filters
-    float *part = p.part + (long)s * p.Kp * p.Cp * taps;
+    // ---- partial block out: part[split][f][c][tap]; lane = channel, registers = filters
+    const long split = ROWSPLIT ? (long)s * 4 + wave : s;
+    float *part = p.part + split * p.Kp * p.Cp * taps;
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
-        const int tap = wave + 4 * t;
+        const int tap = ROWSPLIT ? t : wave + 4 * t;
         if (tap >= taps) continue;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -526,6 +532,8 @@ bias_reduce_kernel(const float *__restrict__ part, float *__restrict__ db, int K
 struct BwPlan {
     bool ok;
     int Kp, Cp, xrows, xcols, xstride, n_rowtile, n_coltile, S, n_fblk, n_cblk, tpw;
+    bool rowsplit;
+    int n_part;          // partial blocks the reduce kernel adds up
     long n_ptile;
     size_t lds_bytes, part_bytes;
 };
@@ -535,14 +543,16 @@ static BwPlan bw_plan(const ConvShape &s)
     BwPlan b{};
     const long taps = (long)s.kh * s.kw;
     if (taps > 52) return b;
-    b.tpw = taps <= 16 ? 4 : (taps <= 28 ? 7 : 13);
+    b.rowsplit = taps == 1 || taps == 9;
+    b.tpw = b.rowsplit ? (int)taps : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
     b.Kp = (s.K + 31) / 32 * 32;
     b.Cp = (s.C + 31) / 32 * 32;
     b.n_fblk = b.Kp / 32;
     b.n_cblk = b.Cp / 32;
     b.xrows = PH + s.kh - 1;
     const long xcols = (long)PW + (long)(s.kw - 1) * s.d;
-    if (xcols > 64 || s.kh > 7) return b;       // one wave-wide load per x-tile row; XR <= 10
+    // one wave-wide load per x-tile row; XR = 8 rows except for the 13-taps-per-wave variant (10)
+    if (xcols > 64 || s.kh > (b.tpw == 13 ? 7 : 5)) return b;
     b.xcols = (int)xcols;
     b.xstride = (b.xrows * b.xcols) | 1;
     b.lds_bytes = 4 * ((size_t)32 * DY_STRIDE + (size_t)32 * b.xstride);
@@ -556,7 +566,8 @@ static BwPlan bw_plan(const ConvShape &s)
     if (S > b.n_ptile / 4) S = b.n_ptile / 4;
     if (S < 1) S = 1;
     b.S = (int)S;
-    b.part_bytes = 4 * ((size_t)b.S * b.Kp * b.Cp * taps + (size_t)s.K * kBiasSplit);
+    b.n_part = b.rowsplit ? 4 * b.S : b.S;
+    b.part_bytes = 4 * ((size_t)b.n_part * b.Kp * b.Cp * taps + (size_t)s.K * kBiasSplit);
     b.ok = true;
     return b;
 }
@@ -624,29 +635,34 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
     p.n_fblk = b.n_fblk; p.n_cblk = b.n_cblk;
     const unsigned grid = (unsigned)((long)b.n_fblk * b.n_cblk * b.S);
-#define DSK_BW_LAUNCH(TPW, XR)                                                                         \
+#define DSK_BW_LAUNCH(TPW, XR, RS, PF)                                                                 \
     do {                                                                                               \
         if (in == DSK_F32) {                                                                           \
-            allow_lds(conv_bwd_weight_mfma_kernel<float, TPW, XR>, b.lds_bytes);                       \
-            conv_bwd_weight_mfma_kernel<float, TPW, XR><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p); \
+            allow_lds(conv_bwd_weight_mfma_kernel<float, TPW, XR, RS, PF>, b.lds_bytes);               \
+            conv_bwd_weight_mfma_kernel<float, TPW, XR, RS, PF>                                        \
+                <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                  \
         } else {                                                                                       \
-            allow_lds(conv_bwd_weight_mfma_kernel<bf16, TPW, XR>, b.lds_bytes);                        \
-            conv_bwd_weight_mfma_kernel<bf16, TPW, XR><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p); \
+            allow_lds(conv_bwd_weight_mfma_kernel<bf16, TPW, XR, RS, PF>, b.lds_bytes);                \
+            conv_bwd_weight_mfma_kernel<bf16, TPW, XR, RS, PF>                                         \
+                <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                  \
         }                                                                                              \
     } while (0)
-    const bool tall = b.xrows > 8;
-    if (b.tpw == 4) { if (tall) DSK_BW_LAUNCH(4, 10); else DSK_BW_LAUNCH(4, 8); }
-    else if (b.tpw == 7) { if (tall) DSK_BW_LAUNCH(7, 10); else DSK_BW_LAUNCH(7, 8); }
-    else DSK_BW_LAUNCH(13, 10);
+    if (b.rowsplit && b.tpw == 1) DSK_BW_LAUNCH(1, 8, true, true);
+    else if (b.rowsplit) DSK_BW_LAUNCH(9, 8, true, false);
+    else if (b.tpw == 1) DSK_BW_LAUNCH(1, 8, false, true);
+    else if (b.tpw == 2) DSK_BW_LAUNCH(2, 8, false, true);
+    else if (b.tpw == 4) DSK_BW_LAUNCH(4, 8, false, true);
+    else if (b.tpw == 7) DSK_BW_LAUNCH(7, 8, false, false);
+    else DSK_BW_LAUNCH(13, 10, false, false);
 #undef DSK_BW_LAUNCH
     int rc = check_launch();
     if (rc != DSK_OK) return rc;
     const long total = (long)s.K * s.C * taps;
     bw_reduce_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
-        (const float *)ws, dw, s.K, s.C, taps, b.Kp, b.Cp, b.S);
+        (const float *)ws, dw, s.K, s.C, taps, b.Kp, b.Cp, b.n_part);
     rc = check_launch();
     if (rc != DSK_OK || !db) return rc;
-    float *bpart = (float *)ws + (size_t)b.S * b.Kp * b.Cp * taps;
+    float *bpart = (float *)ws + (size_t)b.n_part * b.Kp * b.Cp * taps;
     if (in == DSK_F32)
         bias_partial_kernel<float><<<dim3(s.K * kBiasSplit), dim3(kThreads), 0, st>>>((const float *)dy, bpart, s.N,
                                                                                     s.K, (long)s.Ho * s.Wo);

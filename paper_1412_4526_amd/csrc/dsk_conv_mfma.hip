@@ -335,7 +335,7 @@ static constexpr int DY_STRIDE = PH * PW + 1;   // odd: lanes = filters read con
 
 struct BwParams {
     const void *x, *dy;
-    float *part;         // [S][Kp][Cp][taps]
+    float *part;         // [split][taps][Kp][Cp]
     int N, C, H, W, K, Ho, Wo, kh, kw, d;
     int Kp, Cp;          // padded to 32
     int xrows, xcols, xstride;   // x tile: PH+kh-1 by PW+(kw-1)*d, channel stride odd
@@ -343,6 +343,7 @@ struct BwParams {
     long n_ptile;        // N * n_rowtile * n_coltile
     int S;               // split count
     int n_fblk, n_cblk;
+    int dbg;
 };
 
 // TPW: accumulator tiles (taps) per wave; XR: rows of the x tile, at most.
@@ -365,10 +366,16 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     const int lo = lane & 31, hi = lane >> 5;
     const int taps = p.kh * p.kw;
 
-    int b = blockIdx.x;
-    const int s = b % p.S; b /= p.S;
+    // All (filter block, channel block) workgroups of one pixel share are neighbours in the
+    // logical order and, through the XCD-aware mapping, run on the same XCD at the same time:
+    // the x tiles are then fetched from HBM once, not once per filter block (and dy likewise).
+    const int nblk = p.n_fblk * p.n_cblk * p.S;
+    const int per_xcd = (nblk + kXcds - 1) / kXcds;
+    int b = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
+    if (b >= nblk) return;
+    const int fb = b % p.n_fblk; b /= p.n_fblk;
     const int cb = b % p.n_cblk;
-    const int fb = b / p.n_cblk;
+    const int s = b / p.n_cblk;
 
     const TI *x = (const TI *)p.x;
     const TI *dy = (const TI *)p.dy;
@@ -393,57 +400,80 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     float dr[16];          // dy tile share: (filter, row) segments wave*2+hi+8i, column lo
     float xr[8][XR];       // x tile share: channels wave+4*ci, rows r, column lane
 
+    // Every tile starts inside both maps (the host enumerates only such tiles), so the tile's
+    // base is always a valid address: loads that fall outside the maps are redirected there and
+    // replaced by zero when the registers are written to LDS.  Nothing depends on a loaded
+    // value before that point, so all loads of a tile are in flight together, and the address
+    // is a wave-uniform base plus one per-lane offset shared by all loads of the tile.
+    const unsigned HoWo = (unsigned)(p.Ho * p.Wo), dWo = (unsigned)(p.d * p.Wo);
+    const unsigned HW = (unsigned)(p.H * p.W), dW = (unsigned)(p.d * p.W);
+    const int nf_valid = p.K - fb * 32, nc_valid = p.C - cb * 32;
+    int st_nr_dy = 0, st_nr_x = 0;             // rows of the staged tile that exist
+    bool st_dcol_ok = false, st_col_ok = false; // this lane's column exists
     auto load_tile = [&](long pt) {
         const int ct = (int)(pt % p.n_coltile);
         const int rt = (int)((pt / p.n_coltile) % p.n_rowtile);
         const int n = (int)(pt / ((long)p.n_coltile * p.n_rowtile));
         const int u0 = (rt / p.d) * p.d * PH + (rt % p.d);
         const int v0 = ct * PW;
+        const TI *dyt = dy + (((long)n * p.K + fb * 32) * p.Ho + u0) * p.Wo + v0;
+        const TI *xt = x + (((long)n * p.C + cb * 32) * p.H + u0) * p.W + v0;
+        // dy: segment i of this wave is filter f_i, rows r_i (lanes 0-31) and r_i+1 (lanes 32-63)
+        st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;           // dy rows u0 + r*d that exist (>= 1)
+        st_dcol_ok = v0 + lo < p.Wo;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int seg = wave * 2 + hi + 8 * i;
-            const int gf = fb * 32 + (seg >> 2);
-            const int row = u0 + (seg & 3) * p.d, col = v0 + lo;
-            float v = 0.f;
-            if (gf < p.K && row < p.Ho && col < p.Wo)
-                v = ldf(dy, (((long)n * p.K + gf) * p.Ho + row) * p.Wo + col);
-            dr[i] = v;
+            const int seg = wave * 2 + 8 * i;              // even: the lower half's segment
+            const int f = seg >> 2, r = seg & 3;
+            const bool ok_s = f < nf_valid && r < st_nr_dy;   // uniform
+            const TI *base = ok_s ? dyt + ((unsigned)f * HoWo + (unsigned)r * dWo) : dyt;
+            const bool ok = ok_s && st_dcol_ok && r + hi < st_nr_dy;
+            dr[i] = ldf(base, (long)(ok ? (unsigned)hi * dWo + (unsigned)lo : 0u));
         }
-        const bool col_ok = lane < p.xcols && v0 + lane < p.W;
+        st_col_ok = lane < p.xcols && v0 + lane < p.W;
+        const unsigned xlane_off = st_col_ok ? (unsigned)lane : 0u;
+        st_nr_x = (p.H - u0 + p.d - 1) / p.d;             // x rows u0 + r*d that exist
+        st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
 #pragma unroll
         for (int ci = 0; ci < 8; ++ci) {
-            const int gc = cb * 32 + wave + 4 * ci;
+            const int c = wave + 4 * ci;
 #pragma unroll
             for (int r = 0; r < XR; ++r) {
-                const int row = u0 + r * p.d;
-                float v = 0.f;
-                if (col_ok && gc < p.C && r < p.xrows && row < p.H)
-                    v = ldf(x, (((long)n * p.C + gc) * p.H + row) * p.W + v0 + lane);
-                xr[ci][r] = v;
+                const bool ok_s = c < nc_valid && r < st_nr_x;              // uniform
+                const TI *base = ok_s ? xt + ((unsigned)c * HW + (unsigned)r * dW) : xt;
+                xr[ci][r] = ldf(base, (long)xlane_off);
             }
         }
     };
 
     long pt = s;
     if (PREFETCH && pt < p.n_ptile) load_tile(pt);
+    bool first = true;
     while (pt < p.n_ptile) {
+        if ((p.dbg & 1) && !first) goto compute;
+        first = false;
         if (!PREFETCH) load_tile(pt);
         __syncthreads();        // every wave is done with the previous tile
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int seg = wave * 2 + hi + 8 * i;
-            dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = dr[i];
+            const bool ok = st_dcol_ok && (seg >> 2) < nf_valid && (seg & 3) < st_nr_dy;
+            dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = ok ? dr[i] : 0.f;
         }
         if (lane < p.xcols) {
 #pragma unroll
             for (int ci = 0; ci < 8; ++ci)
 #pragma unroll
                 for (int r = 0; r < XR; ++r)
-                    if (r < p.xrows) xs[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = xr[ci][r];
+                    if (r < p.xrows) {
+                        const bool ok = st_col_ok && wave + 4 * ci < nc_valid && r < st_nr_x;
+                        xs[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = ok ? xr[ci][r] : 0.f;
+                    }
         }
         __syncthreads();
+        if (PREFETCH && pt + p.S < p.n_ptile && !(p.dbg & 1)) load_tile(pt + p.S);      // in flight while the matrix cores run
+    compute:
         pt += p.S;
-        if (PREFETCH && pt < p.n_ptile) load_tile(pt);      // in flight while the matrix cores run
         // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
         const float *ab = dys + lo * DY_STRIDE + hi;
         const float *bb = xs + lo * p.xstride + hi;
@@ -461,7 +491,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         }
     }
 
-    // ---- partial block out: part[split][f][c][tap]; lane = channel, registers = filters
+    // ---- partial block out: part[split][tap][f][c]; lane = channel, registers = filters
     const long split = ROWSPLIT ? (long)s * 4 + wave : s;
     float *part = p.part + split * p.Kp * p.Cp * taps;
 #pragma unroll
@@ -472,7 +502,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         for (int i = 0; i < 16; ++i) {
             const int f = fb * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
             const int c = cb * 32 + lo;
-            part[((long)f * p.Cp + c) * taps + tap] = acc[t][i];
+            part[((long)tap * p.Kp + f) * p.Cp + c] = acc[t][i];      // 32 consecutive channels per store
         }
     }
 }
@@ -486,7 +516,7 @@ bw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, 
     const int t = (int)(idx % taps);
     const int c = (int)((idx / taps) % C);
     const int f = (int)(idx / ((long)taps * C));
-    const long o = ((long)f * Cp + c) * taps + t;
+    const long o = ((long)t * Kp + f) * Cp + c;
     const long stride = (long)Kp * Cp * taps;
     float acc = 0.f;
     for (int s = 0; s < S; ++s) acc += part[s * stride + o];
@@ -553,11 +583,17 @@ static BwPlan bw_plan(const ConvShape &s)
     const long xcols = (long)PW + (long)(s.kw - 1) * s.d;
     // one wave-wide load per x-tile row; XR = 8 rows except for the 13-taps-per-wave variant (10)
     if (xcols > 64 || s.kh > (b.tpw == 13 ? 7 : 5)) return b;
+    if ((long)s.H * s.W >= (1L << 24)) return b;         // 32-channel block offsets stay below 2^29 elements
     b.xcols = (int)xcols;
     b.xstride = (b.xrows * b.xcols) | 1;
     b.lds_bytes = 4 * ((size_t)32 * DY_STRIDE + (size_t)32 * b.xstride);
     if (b.lds_bytes > kMaxLdsBw) return b;
-    b.n_rowtile = (s.Ho + s.d * PH - 1) / (s.d * PH) * s.d;
+    // residue classes of the last row block that start beyond the map hold no pixel: skip them
+    {
+        const int nrb = (s.Ho + s.d * PH - 1) / (s.d * PH);
+        const int last = s.Ho - (nrb - 1) * s.d * PH;
+        b.n_rowtile = (nrb - 1) * s.d + (last < s.d ? last : s.d);
+    }
     b.n_coltile = (s.Wo + PW - 1) / PW;
     b.n_ptile = (long)s.N * b.n_rowtile * b.n_coltile;
     const long blocks = (long)b.n_fblk * b.n_cblk;
@@ -634,7 +670,8 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     p.Kp = b.Kp; p.Cp = b.Cp; p.xrows = b.xrows; p.xcols = b.xcols; p.xstride = b.xstride;
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
     p.n_fblk = b.n_fblk; p.n_cblk = b.n_cblk;
-    const unsigned grid = (unsigned)((long)b.n_fblk * b.n_cblk * b.S);
+    { const char *e = getenv("DSK_DBG"); p.dbg = e ? atoi(e) : 0; }
+    const unsigned grid = (unsigned)(((long)b.n_fblk * b.n_cblk * b.S + kXcds - 1) / kXcds * kXcds);
 #define DSK_BW_LAUNCH(TPW, XR, RS, PF)                                                                 \
     do {                                                                                               \
         if (in == DSK_F32) {                                                                           \

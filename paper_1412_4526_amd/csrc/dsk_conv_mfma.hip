@@ -47,14 +47,18 @@ struct GcParams {
     void *out;
     const float *wt;     // [n_fgrp][Cpad][taps][TF], zero padded
     const float *bias;   // may be null
+    float *partial;      // split tiles: [2 * n_wg][WM * 64][256] raw accumulators
     int N, Cin, Hin, Win, Fout, Hout, Wout;
     int kh, kw, d, off_h, off_w, act;
-    int Cpad, Cc;        // padded channel count, channels per LDS chunk (even)
+    int Cpad, Cc, NC;    // padded channel count, channels per LDS chunk (even), chunks per tile
     int rows, cols;      // LDS tile: TH+kh-1 by TW+(kw-1)*d
     int chan_stride;     // rows*cols
     int xs_floats;       // Cc*chan_stride rounded up to a multiple of 4
     int n_rowtile, n_coltile, n_fgrp;
-    long total, per_xcd;
+    long tiles;          // N * n_rowtile * n_coltile * n_fgrp output tiles
+    long units;          // tiles * NC: a unit is one channel chunk of one tile
+    long q;              // units per workgroup (NC: one whole tile each)
+    long n_wg, per_xcd;  // logical workgroups; the grid is per_xcd * 8
     int dbg;
 };
 
@@ -82,139 +86,23 @@ gc_weight_prep_kernel(const float *__restrict__ w, float *__restrict__ wt, int K
     wt[idx] = round_bf16 ? bf16_to_f32(f32_to_bf16(v)) : v;
 }
 
-// XI / WI: upper bounds of what one thread stages per chunk: input-tile elements
-// (Cc*chan_stride <= 256*XI) and weight float4s (Cc*taps*TF <= 1024*WI).
-//
-// Pipeline: the global loads of chunk t+1 are issued before the matrix cores start on chunk
-// t and land in registers meanwhile; they are written to LDS after chunk t is done.  Inside
-// a chunk the LDS operands of k-step s+1 are read before the MFMAs of step s are issued.
-template <typename TI, typename TO, int WM, int XI, int WI>
-__global__ void __launch_bounds__(kThreads, 2)
-gemm_conv_kernel(GcParams p)
+// tile index -> filter group, image, first output row (of its residue class), first column
+__device__ inline void gc_decode_tile(const GcParams &p, long tile, int &fg, int &n, int &u0, int &v0)
 {
-    extern __shared__ __align__(16) float smem[];
+    fg = (int)(tile % p.n_fgrp); tile /= p.n_fgrp;
+    const int ct = (int)(tile % p.n_coltile); tile /= p.n_coltile;
+    const int rt = (int)(tile % p.n_rowtile);
+    n = (int)(tile / p.n_rowtile);
+    u0 = (rt / p.d) * p.d * TH + (rt % p.d);
+    v0 = ct * TW;
+}
+
+// bias, non-linearity, store; 32 consecutive pixels per filter per store instruction
+template <typename TO, int WM>
+__device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][4], int fg, int n, int u0, int v0,
+                                   int wave, int lo, int hi)
+{
     constexpr int TF = WM * 32;
-    float *xs = smem;                   // [Cc][rows][cols]
-    float *wsm = smem + p.xs_floats;    // [Cc][taps][TF]
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lo = lane & 31, hi = lane >> 5;
-
-    // consecutive physical workgroups go to different XCDs; give each XCD one contiguous
-    // run of logical tiles so that neighbours (shared halo, same input tile) share an L2
-    long j = (long)(blockIdx.x % kXcds) * p.per_xcd + blockIdx.x / kXcds;
-    if (j >= p.total) return;
-    const int fg = (int)(j % p.n_fgrp); j /= p.n_fgrp;
-    const int ct = (int)(j % p.n_coltile); j /= p.n_coltile;
-    const int rt = (int)(j % p.n_rowtile);
-    const int n = (int)(j / p.n_rowtile);
-    const int u0 = (rt / p.d) * p.d * TH + (rt % p.d);
-    const int v0 = ct * TW;
-    if (u0 >= p.Hout) return;
-
-    const unsigned HW = (unsigned)(p.Hin * p.Win);   // Cin*Hin*Win < 2^30 is checked on the host
-    const TI *in_n = (const TI *)p.in + (long)n * p.Cin * (long)HW;
-    const int taps = p.kh * p.kw;
-
-    // Where this thread's share of the input tile comes from; the same for every chunk.
-    // Element e = tid + 256*i of the tile [Cc][rows][cols]:  >= 0: (local channel << 28) |
-    // offset inside the channel plane;  -2: inside the tile but outside the map (zero);
-    // -1: beyond the tile.
-    int xoff[XI];
-    {
-        const int n_x = p.Cc * p.chan_stride;
-#pragma unroll
-        for (int i = 0; i < XI; ++i) {
-            const int e = tid + i * kThreads;
-            int pk = -1;
-            if (e < n_x) {
-                const int c = e / p.chan_stride, rem = e - c * p.chan_stride;
-                const int r = rem / p.cols, col = rem - r * p.cols;
-                const int irow = u0 + r * p.d - p.off_h, icol = v0 + col - p.off_w;
-                pk = (irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win) ? ((c << 28) | (irow * p.Win + icol)) : -2;
-            }
-            xoff[i] = pk;
-        }
-    }
-
-    f32x16 acc[WM][4];
-#pragma unroll
-    for (int wm = 0; wm < WM; ++wm)
-#pragma unroll
-        for (int wn = 0; wn < 4; ++wn)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
-
-    const int n4 = p.Cc * taps * TF / 4;
-    float xv[XI];
-    float4 wv[WI];
-    auto fetch = [&](int c0) {
-#pragma unroll
-        for (int i = 0; i < XI; ++i) {
-            const int pk = xoff[i];
-            float v = 0.f;
-            if (pk >= 0) {
-                // channels beyond Cin meet zero weights; clamp so the address stays inside the tensor
-                unsigned gc = (unsigned)(c0 + (pk >> 28));
-                gc = gc < (unsigned)p.Cin ? gc : (unsigned)p.Cin - 1u;
-                v = ldf(in_n, (long)(gc * HW + (unsigned)(pk & 0x0fffffff)));
-            }
-            xv[i] = v;
-        }
-        const float4 *wsrc = (const float4 *)(p.wt + ((long)fg * p.Cpad + c0) * taps * TF);
-#pragma unroll
-        for (int q = 0; q < WI; ++q) {
-            const int idx = q * kThreads + tid;
-            wv[q] = idx < n4 ? wsrc[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    };
-
-    // per-lane LDS bases; the k-step offsets are uniform over the wave
-    const float *xlane = xs + hi * p.chan_stride + (2 * wave) * p.cols + lo;
-    const float *wlane = wsm + hi * taps * TF + lo;
-    auto read_ops = [&](int xo, int wo, const float *xb, const float *wb, float (&A)[WM], float (&B)[4]) {
-#pragma unroll
-        for (int wm = 0; wm < WM; ++wm) A[wm] = wb[wo + wm * 32];
-#pragma unroll
-        for (int wn = 0; wn < 4; ++wn) B[wn] = xb[xo + (wn >> 1) * p.cols + (wn & 1) * 32];
-    };
-
-    fetch(0);
-    for (int c0 = 0; c0 < p.Cpad; c0 += p.Cc) {
-        if (!(p.dbg & 1) || c0 == 0) {
-        __syncthreads();      // every wave is done reading the previous chunk
-#pragma unroll
-        for (int i = 0; i < XI; ++i)
-            if (xoff[i] != -1) xs[tid + i * kThreads] = xv[i];
-#pragma unroll
-        for (int q = 0; q < WI; ++q) {
-            const int idx = q * kThreads + tid;
-            if (idx < n4) ((float4 *)wsm)[idx] = wv[q];
-        }
-        __syncthreads();
-        if (c0 + p.Cc < p.Cpad && !(p.dbg & 1)) fetch(c0 + p.Cc);      // in flight while the matrix cores run
-        }
-
-        // ---- matrix cores: k index = (channel pair, tap); lanes 32..63 take the odd channel
-        for (int cp = 0; cp < p.Cc; cp += 2) {
-            const float *xb = xlane + cp * p.chan_stride;
-            const float *wb = wlane + cp * taps * TF;
-            for (int ta = 0; ta < p.kh; ++ta) {
-                for (int tb = 0; tb < p.kw; ++tb) {
-                    float A[WM], B[4];
-                    read_ops(ta * p.cols + tb * p.d, (ta * p.kw + tb) * TF, xb, wb, A, B);
-#pragma unroll
-                    for (int wm = 0; wm < WM; ++wm)
-#pragma unroll
-                        for (int wn = 0; wn < 4; ++wn)
-                            acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
-                }
-            }
-        }
-    }
-
-    // ---- epilogue: bias, non-linearity, store; 32 consecutive pixels per filter per store
     TO *out = (TO *)p.out;
 #pragma unroll
     for (int wn = 0; wn < 4; ++wn) {
@@ -237,17 +125,202 @@ gemm_conv_kernel(GcParams p)
     }
 }
 
+// XI / WI: upper bounds of what one thread stages per chunk: input-tile elements
+// (Cc*chan_stride <= 256*XI) and weight float4s (Cc*taps*TF <= 1024*WI).
+//
+// Work distribution: the (tile, channel chunk) units are numbered tile-major and logical
+// workgroup g takes units [g*q, (g+1)*q).  With q = NC every workgroup owns exactly one tile.
+// With fewer, persistent workgroups (q > NC, chosen by the host when the tile count is not
+// a comfortable multiple of what the chip holds at once) a range may begin or end inside a
+// tile; such a piece is written as raw accumulators to `partial` and gc_fixup_kernel adds
+// the two pieces of every split tile in a fixed order and applies the epilogue.
+//
+// Pipeline: the global loads of chunk t+1 are issued before the matrix cores start on chunk
+// t and land in registers meanwhile; they are written to LDS after chunk t is done.
+template <typename TI, typename TO, int WM, int XI, int WI, bool SPLIT>
+__global__ void __launch_bounds__(kThreads, 2)
+gemm_conv_kernel(GcParams p)
+{
+    extern __shared__ __align__(16) float smem[];
+    constexpr int TF = WM * 32;
+    float *xs = smem;                   // [Cc][rows][cols]
+    float *wsm = smem + p.xs_floats;    // [Cc][taps][TF]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lo = lane & 31, hi = lane >> 5;
+
+    // consecutive physical workgroups go to different XCDs; give each XCD one contiguous
+    // run of logical workgroups so that neighbours (shared halo, same input tile) share an L2
+    const long wg = (long)(blockIdx.x % kXcds) * p.per_xcd + blockIdx.x / kXcds;
+    if (wg >= p.n_wg) return;
+    long ub = SPLIT ? wg * p.q : wg * p.NC;
+    const long ue = SPLIT ? (ub + p.q < p.units ? ub + p.q : p.units) : ub + p.NC;
+
+    const unsigned HW = (unsigned)(p.Hin * p.Win);   // Cin*Hin*Win < 2^30 is checked on the host
+    const int taps = p.kh * p.kw;
+    const int n4 = p.Cc * taps * TF / 4;
+
+    // per-lane LDS bases; the k-step offsets are uniform over the wave
+    const float *xlane = xs + hi * p.chan_stride + (2 * wave) * p.cols + lo;
+    const float *wlane = wsm + hi * taps * TF + lo;
+
+    bool first_piece = true;
+    do {
+        const long tile = SPLIT ? ub / p.NC : wg;
+        const int cb = SPLIT ? (int)(ub - tile * p.NC) : 0;
+        const int ce = SPLIT ? ((long)cb + (ue - ub) < p.NC ? cb + (int)(ue - ub) : p.NC) : p.NC;
+        int fg, n, u0, v0;
+        gc_decode_tile(p, tile, fg, n, u0, v0);
+        const TI *in_n = (const TI *)p.in + (long)n * p.Cin * (long)HW;
+
+        // Where this thread's share of the input tile comes from; the same for every chunk.
+        // Element e = tid + 256*i of the tile [Cc][rows][cols]:  >= 0: (local channel << 28) |
+        // offset inside the channel plane;  -2: inside the tile but outside the map (zero);
+        // -1: beyond the tile.
+        int xoff[XI];
+        {
+            const int n_x = p.Cc * p.chan_stride;
+#pragma unroll
+            for (int i = 0; i < XI; ++i) {
+                const int e = tid + i * kThreads;
+                int pk = -1;
+                if (e < n_x) {
+                    const int c = e / p.chan_stride, rem = e - c * p.chan_stride;
+                    const int r = rem / p.cols, col = rem - r * p.cols;
+                    const int irow = u0 + r * p.d - p.off_h, icol = v0 + col - p.off_w;
+                    pk = (irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win) ? ((c << 28) | (irow * p.Win + icol)) : -2;
+                }
+                xoff[i] = pk;
+            }
+        }
+
+        f32x16 acc[WM][4];
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+            for (int wn = 0; wn < 4; ++wn)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
+
+        float xv[XI];
+        float4 wv[WI];
+        auto fetch = [&](int c0) {
+#pragma unroll
+            for (int i = 0; i < XI; ++i) {
+                const int pk = xoff[i];
+                float v = 0.f;
+                if (pk >= 0) {
+                    // channels beyond Cin meet zero weights; clamp so the address stays inside the tensor
+                    unsigned gc = (unsigned)(c0 + (pk >> 28));
+                    gc = gc < (unsigned)p.Cin ? gc : (unsigned)p.Cin - 1u;
+                    v = ldf(in_n, (long)(gc * HW + (unsigned)(pk & 0x0fffffff)));
+                }
+                xv[i] = v;
+            }
+            const float4 *wsrc = (const float4 *)(p.wt + ((long)fg * p.Cpad + c0) * taps * TF);
+#pragma unroll
+            for (int q = 0; q < WI; ++q) {
+                const int idx = q * kThreads + tid;
+                wv[q] = idx < n4 ? wsrc[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        };
+
+        fetch(cb * p.Cc);
+        for (int ch = cb; ch < ce; ++ch) {
+            __syncthreads();      // every wave is done reading the previous chunk
+#pragma unroll
+            for (int i = 0; i < XI; ++i)
+                if (xoff[i] != -1) xs[tid + i * kThreads] = xv[i];
+#pragma unroll
+            for (int q = 0; q < WI; ++q) {
+                const int idx = q * kThreads + tid;
+                if (idx < n4) ((float4 *)wsm)[idx] = wv[q];
+            }
+            __syncthreads();
+            if (ch + 1 < ce) fetch((ch + 1) * p.Cc);      // in flight while the matrix cores run
+
+            // ---- matrix cores: k index = (channel pair, tap); lanes 32..63 take the odd channel
+            for (int cp = 0; cp < p.Cc; cp += 2) {
+                const float *xb = xlane + cp * p.chan_stride;
+                const float *wb = wlane + cp * taps * TF;
+                for (int ta = 0; ta < p.kh; ++ta) {
+                    for (int tb = 0; tb < p.kw; ++tb) {
+                        const int xo = ta * p.cols + tb * p.d, wo = (ta * p.kw + tb) * TF;
+                        float A[WM], B[4];
+#pragma unroll
+                        for (int wm = 0; wm < WM; ++wm) A[wm] = wb[wo + wm * 32];
+#pragma unroll
+                        for (int wn = 0; wn < 4; ++wn) B[wn] = xb[xo + (wn >> 1) * p.cols + (wn & 1) * 32];
+#pragma unroll
+                        for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                            for (int wn = 0; wn < 4; ++wn)
+                                acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
+                    }
+                }
+            }
+        }
+
+        if (!SPLIT || (cb == 0 && ce == p.NC)) {
+            gc_epilogue<TO, WM>(p, acc, fg, n, u0, v0, wave, lo, hi);
+        } else {
+            // a piece of a split tile: slot 2g holds the piece a range begins with, 2g+1 the one it ends with
+            float *slot = p.partial + (2 * wg + (first_piece ? 0 : 1)) * (long)(WM * 64 * kThreads);
+#pragma unroll
+            for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                for (int wn = 0; wn < 4; ++wn)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) slot[((wm * 4 + wn) * 16 + i) * kThreads + tid] = acc[wm][wn][i];
+        }
+        ub += ce - cb;
+        first_piece = false;
+    } while (SPLIT && ub < ue);
+}
+
+// Adds the two pieces of the tile that the boundary between logical workgroups g and g+1
+// cuts (the end piece of g first, then the begin piece of g+1) and finishes it.
+template <typename TO, int WM>
+__global__ void __launch_bounds__(kThreads)
+gc_fixup_kernel(GcParams p)
+{
+    const long g = blockIdx.x;
+    const long boundary = (g + 1) * p.q;
+    if (boundary >= p.units || boundary % p.NC == 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lo = lane & 31, hi = lane >> 5;
+    int fg, n, u0, v0;
+    gc_decode_tile(p, boundary / p.NC, fg, n, u0, v0);
+    const float *end_piece = p.partial + (2 * g + 1) * (long)(WM * 64 * kThreads);
+    const float *begin_piece = p.partial + (2 * (g + 1)) * (long)(WM * 64 * kThreads);
+    f32x16 acc[WM][4];
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+        for (int wn = 0; wn < 4; ++wn)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int o = ((wm * 4 + wn) * 16 + i) * kThreads + tid;
+                acc[wm][wn][i] = end_piece[o] + begin_piece[o];
+            }
+    gc_epilogue<TO, WM>(p, acc, fg, n, u0, v0, wave, lo, hi);
+}
+
 static constexpr int kXI = 16;   // input-tile elements per thread per chunk, at most
 static constexpr int kWI = 8;    // weight float4s per thread per chunk, at most
+static constexpr long kSlots = 512;   // workgroups resident at once: 2 per CU, 256 CUs
 
 struct GcPlan {
-    bool ok;
-    int TF, WM, Cc, Cpad, rows, cols, chan_stride, xs_floats, n_fgrp;
-    size_t lds_bytes, wt_bytes;
+    bool ok, split;      // split: persistent workgroups with split tiles
+    int TF, WM, Cc, Cpad, NC, rows, cols, chan_stride, xs_floats, n_fgrp, n_rowtile, n_coltile;
+    long tiles, units, q, n_wg;
+    size_t lds_bytes, wt_bytes, partial_bytes;
 };
 
-// Cin / Fout: channel and output counts of the GEMM (swapped for backward-data)
-static GcPlan gc_plan(int Cin, int Fout, int kh, int kw, int d)
+// Cin / Fout: channel and output counts of the GEMM (swapped for backward-data); N images of
+// Hout x Wout outputs
+static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int kw, int d)
 {
     GcPlan g{};
     g.WM = Fout > 32 ? 2 : 1;
@@ -270,9 +343,34 @@ static GcPlan gc_plan(int Cin, int Fout, int kh, int kw, int d)
     if (best == 0) return g;
     g.Cc = best;
     g.Cpad = best_pad;
+    g.NC = g.Cpad / g.Cc;
     g.xs_floats = (g.Cc * g.chan_stride + 3) & ~3;
     g.lds_bytes = 4 * ((size_t)g.xs_floats + (size_t)g.Cc * taps * g.TF);
-    g.wt_bytes = 4 * (size_t)g.n_fgrp * g.Cpad * taps * g.TF;
+    g.wt_bytes = (4 * (size_t)g.n_fgrp * g.Cpad * taps * g.TF + 255) & ~(size_t)255;
+    // residue classes of the last row block that start beyond the map hold no output: not enumerated
+    {
+        const int nrb = (Hout + d * TH - 1) / (d * TH);
+        const int last = Hout - (nrb - 1) * d * TH;
+        g.n_rowtile = (nrb - 1) * d + (last < d ? last : d);
+    }
+    g.n_coltile = (Wout + TW - 1) / TW;
+    g.tiles = (long)N * g.n_rowtile * g.n_coltile * g.n_fgrp;
+    // Tiles are all equally long, so with T tiles and S resident workgroups the last round of a
+    // one-tile-per-workgroup launch leaves S - (T mod S) slots idle.  When that costs more than
+    // a few per cent, S persistent workgroups take T*NC/S chunks each instead.
+    g.split = g.tiles > kSlots && g.tiles < 12 * kSlots && g.tiles % kSlots != 0;
+    if (g.split) {
+        g.n_wg = kSlots;
+        g.units = g.tiles * g.NC;
+        g.q = (g.units + g.n_wg - 1) / g.n_wg;
+        g.n_wg = (g.units + g.q - 1) / g.q;
+        g.partial_bytes = 4 * (size_t)(2 * g.n_wg) * g.WM * 64 * kThreads;
+    } else {
+        g.n_wg = g.tiles;
+        g.units = g.tiles * g.NC;
+        g.q = g.NC;
+        g.partial_bytes = 0;
+    }
     g.ok = true;
     return g;
 }
@@ -281,19 +379,27 @@ template <typename TI, typename TO>
 static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
 {
     const unsigned grid = (unsigned)(p.per_xcd * kXcds);
-    size_t lds = g.lds_bytes;
-    if (p.dbg & 2) { lds = 100 * 1024; allow_lds(gemm_conv_kernel<TI, TO, 2, kXI, kWI>, lds); }
-    if (g.WM == 2)
-        gemm_conv_kernel<TI, TO, 2, kXI, kWI><<<dim3(grid), dim3(kThreads), lds, st>>>(p);
+    if (g.WM == 2 && g.split)
+        gemm_conv_kernel<TI, TO, 2, kXI, kWI, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    else if (g.WM == 2)
+        gemm_conv_kernel<TI, TO, 2, kXI, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    else if (g.split)
+        gemm_conv_kernel<TI, TO, 1, kXI, kWI, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else
-        gemm_conv_kernel<TI, TO, 1, kXI, kWI><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 1, kXI, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    if (g.split) {
+        if (g.WM == 2)
+            gc_fixup_kernel<TO, 2><<<dim3((unsigned)(g.n_wg - 1)), dim3(kThreads), 0, st>>>(p);
+        else
+            gc_fixup_kernel<TO, 1><<<dim3((unsigned)(g.n_wg - 1)), dim3(kThreads), 0, st>>>(p);
+    }
 }
 
 static int gc_run(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Hin, int Win,
                   int Fout, int Hout, int Wout, int kh, int kw, int d, int off, int act, int flip,
                   int K, int C, dsk_dtype tin, dsk_dtype tout, void *ws, hipStream_t st)
 {
-    const GcPlan g = gc_plan(Cin, Fout, kh, kw, d);
+    const GcPlan g = gc_plan(N, Cin, Fout, Hout, Wout, kh, kw, d);
     if (!g.ok) return DSK_ESHAPE;
     const int taps = kh * kw;
     float *wt = (float *)ws;
@@ -304,18 +410,17 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     }
     GcParams p{};
     p.in = in; p.out = out; p.wt = wt; p.bias = bias;
+    p.partial = g.split ? (float *)((char *)ws + g.wt_bytes) : nullptr;
     p.N = N; p.Cin = Cin; p.Hin = Hin; p.Win = Win; p.Fout = Fout; p.Hout = Hout; p.Wout = Wout;
     p.kh = kh; p.kw = kw; p.d = d; p.off_h = off ? (kh - 1) * d : 0; p.off_w = off ? (kw - 1) * d : 0;
     p.act = act;
-    p.Cpad = g.Cpad; p.Cc = g.Cc; p.rows = g.rows; p.cols = g.cols; p.chan_stride = g.chan_stride;
+    p.Cpad = g.Cpad; p.Cc = g.Cc; p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.chan_stride = g.chan_stride;
     p.xs_floats = g.xs_floats;
-    p.n_rowtile = (Hout + d * TH - 1) / (d * TH) * d;
-    p.n_coltile = (Wout + TW - 1) / TW;
-    p.n_fgrp = g.n_fgrp;
-    p.total = (long)N * p.n_rowtile * p.n_coltile * p.n_fgrp;
-    p.per_xcd = (p.total + kXcds - 1) / kXcds;
-    { const char *e = getenv("DSK_DBG"); p.dbg = e ? atoi(e) : 0; }
+    p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp;
+    p.tiles = g.tiles; p.units = g.units; p.q = g.q; p.n_wg = g.n_wg;
+    p.per_xcd = (p.n_wg + kXcds - 1) / kXcds;
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;
+    { const char *e = getenv("DSK_DBG"); p.dbg = e ? atoi(e) : 0; }
     if (tin == DSK_F32 && tout == DSK_F32) gc_launch<float, float>(p, g, st);
     else if (tin == DSK_F32 && tout == DSK_BF16) gc_launch<float, bf16>(p, g, st);
     else if (tin == DSK_BF16 && tout == DSK_BF16) gc_launch<bf16, bf16>(p, g, st);
@@ -615,12 +720,12 @@ size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
 {
     (void)in;
     if (which == DSK_WS_CONV_FWD) {
-        const GcPlan g = gc_plan(s.C, s.K, s.kh, s.kw, s.d);
-        return g.ok ? g.wt_bytes : 0;
+        const GcPlan g = gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d);
+        return g.ok ? g.wt_bytes + g.partial_bytes : 0;
     }
     if (which == DSK_WS_CONV_BWD_DATA) {
-        const GcPlan g = gc_plan(s.K, s.C, s.kh, s.kw, s.d);
-        return g.ok ? g.wt_bytes : 0;
+        const GcPlan g = gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d);
+        return g.ok ? g.wt_bytes + g.partial_bytes : 0;
     }
     if (which == DSK_WS_CONV_BWD_WEIGHT) {
         const BwPlan b = bw_plan(s);
@@ -637,8 +742,8 @@ bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype 
     if ((long)s.H * s.W >= (1L << 28) || (long)s.C * s.H * s.W >= (1L << 30) ||
         (long)s.K * s.Ho * s.Wo >= (1L << 30))
         return false;
-    if (which == DSK_WS_CONV_FWD) return gc_plan(s.C, s.K, s.kh, s.kw, s.d).ok;
-    if (which == DSK_WS_CONV_BWD_DATA) return gc_plan(s.K, s.C, s.kh, s.kw, s.d).ok;
+    if (which == DSK_WS_CONV_FWD) return gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
+    if (which == DSK_WS_CONV_BWD_DATA) return gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
     if (which == DSK_WS_CONV_BWD_WEIGHT) return bw_plan(s).ok;
     return false;
 }

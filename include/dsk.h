@@ -167,6 +167,16 @@ int dsk_avgpool_bwd(const void *dy, void *dx,
  * ReLU: [y > 0];  tanh: 1 - y*y;  none: no-op.  y and dy have type t. */
 int dsk_act_bwd(const void *y, void *dy, size_t count, dsk_act act, dsk_dtype t, void *stream);
 
+/* The same, fused with the bias gradient of the conv layer that produced y (Sec. 4.1: the
+ * gradient of b_k is the sum of all entries of the error map), in one pass over the map:
+ *   dy[n][f][u][v] *= act'(.)   in place (act = DSK_ACT_NONE leaves dy untouched, y may be NULL)
+ *   db[f] = sum_{n,u,v} dy[n][f][u][v]   of the values as stored back (fp32, fixed order)
+ * dy[N][K][Ho][Wo] and y have type t.  A caller that uses this passes db = NULL to
+ * dsk_conv_bwd_weight.  Workspace: dsk_act_bwd_bias_workspace_bytes(K). */
+size_t dsk_act_bwd_bias_workspace_bytes(int K);
+int dsk_act_bwd_bias(const void *y, void *dy, float *db, int N, int K, int Ho, int Wo,
+                     dsk_act act, dsk_dtype t, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Last layer: masked softmax cross-entropy (pixel mask of Sec. 4.3)           */
 /* ------------------------------------------------------------------------- */

@@ -23,7 +23,8 @@ DSK_WS_CONV_FWD, DSK_WS_CONV_BWD_DATA, DSK_WS_CONV_BWD_WEIGHT = 0, 1, 2
 SYMBOLS = ("dsk_plan", "dsk_status_string", "dsk_pad_image", "dsk_conv_workspace_bytes",
            "dsk_conv_fwd", "dsk_conv_bwd_data", "dsk_conv_bwd_weight",
            "dsk_maxpool_fwd", "dsk_maxpool_bwd", "dsk_avgpool_fwd", "dsk_avgpool_bwd",
-           "dsk_act_bwd", "dsk_softmax_xent_workspace_bytes", "dsk_masked_softmax_xent",
+           "dsk_act_bwd", "dsk_act_bwd_bias_workspace_bytes", "dsk_act_bwd_bias",
+           "dsk_softmax_xent_workspace_bytes", "dsk_masked_softmax_xent",
            "dsk_set_conv_algo")
 
 
@@ -70,6 +71,9 @@ def _load():
     lib.dsk_avgpool_fwd.argtypes = [vp, vp] + [ci] * 6 + [ci, vp]
     lib.dsk_avgpool_bwd.argtypes = [vp, vp] + [ci] * 6 + [ci, vp]
     lib.dsk_act_bwd.argtypes = [vp, vp, sz, ci, ci, vp]
+    lib.dsk_act_bwd_bias_workspace_bytes.argtypes = [ci]
+    lib.dsk_act_bwd_bias_workspace_bytes.restype = sz
+    lib.dsk_act_bwd_bias.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.dsk_softmax_xent_workspace_bytes.argtypes = [ci] * 4
     lib.dsk_softmax_xent_workspace_bytes.restype = sz
     lib.dsk_masked_softmax_xent.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
@@ -262,6 +266,25 @@ def dsk_act_bwd(y, dy, act):
     assert y.shape == dy.shape and y.dtype == dy.dtype
     _check(lib.dsk_act_bwd(_dev(y), _dev(dy), y.numel(), act, _dtype_code(y), _stream()), "dsk_act_bwd")
     return dy
+
+
+def dsk_act_bwd_bias_workspace_bytes(K):
+    return int(lib.dsk_act_bwd_bias_workspace_bytes(K))
+
+
+def dsk_act_bwd_bias(y, dy, act, db=None, ws=None):
+    """In place on dy; returns db [K] (fp32)."""
+    N, K, Ho, Wo = dy.shape
+    assert act == DSK_ACT_NONE or (y.shape == dy.shape and y.dtype == dy.dtype)
+    if db is None:
+        db = torch.empty((K,), dtype=torch.float32, device=dy.device)
+    need = dsk_act_bwd_bias_workspace_bytes(K)
+    if ws is None or ws.numel() * ws.element_size() < need:
+        ws = torch.empty(need, dtype=torch.uint8, device=dy.device)
+    wsp, wsb = _ws(ws)
+    _check(lib.dsk_act_bwd_bias(None if act == DSK_ACT_NONE else _dev(y), _dev(dy), _dev(db, torch.float32),
+                                N, K, Ho, Wo, act, _dtype_code(dy), wsp, wsb, _stream()), "dsk_act_bwd_bias")
+    return db
 
 
 def dsk_softmax_xent_workspace_bytes(N, Cls, H, W):

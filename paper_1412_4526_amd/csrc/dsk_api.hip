@@ -218,6 +218,23 @@ int dsk_act_bwd(const void *y, void *dy, size_t count, dsk_act act, dsk_dtype t,
     return launch_act_bwd(y, dy, count, act, t, (hipStream_t)stream);
 }
 
+size_t dsk_act_bwd_bias_workspace_bytes(int K)
+{
+    return K < 1 ? 0 : act_bwd_bias_ws_bytes(K);
+}
+
+int dsk_act_bwd_bias(const void *y, void *dy, float *db, int N, int K, int Ho, int Wo, dsk_act act, dsk_dtype t,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    if (bad_ptr(dy) || bad_ptr(db) || bad_dtype(t)) return DSK_EINVAL;
+    if (act < DSK_ACT_NONE || act > DSK_ACT_TANH) return DSK_EINVAL;
+    if (act != DSK_ACT_NONE && bad_ptr(y)) return DSK_EINVAL;
+    if (N < 1 || K < 1 || Ho < 1 || Wo < 1) return DSK_EINVAL;
+    if ((long)N * K * Ho * Wo > kMaxElems) return DSK_ESHAPE;
+    if (ws == nullptr || !aligned16(ws) || ws_bytes < act_bwd_bias_ws_bytes(K)) return DSK_EWORKSPACE;
+    return launch_act_bwd_bias(y, dy, db, N, K, (long)Ho * Wo, act, t, ws, (hipStream_t)stream);
+}
+
 size_t dsk_softmax_xent_workspace_bytes(int N, int Cls, int H, int W)
 {
     if (N < 1 || Cls < 1 || H < 1 || W < 1) return 0;

@@ -612,20 +612,22 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     }
 }
 
+// dw[f][c][t] = sum over the partial blocks, in block order.  Threads run over [t][f][c] with c
+// fastest, the order the partial blocks are stored in, so the reads are coalesced.
 __global__ void __launch_bounds__(kThreads)
 bw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int taps, int Kp, int Cp, int S)
 {
     const long total = (long)K * C * taps;
     const long idx = (long)blockIdx.x * kThreads + threadIdx.x;
     if (idx >= total) return;
-    const int t = (int)(idx % taps);
-    const int c = (int)((idx / taps) % C);
-    const int f = (int)(idx / ((long)taps * C));
+    const int c = (int)(idx % C);
+    const int f = (int)((idx / C) % K);
+    const int t = (int)(idx / ((long)C * K));
     const long o = ((long)t * Kp + f) * Cp + c;
     const long stride = (long)Kp * Cp * taps;
     float acc = 0.f;
     for (int s = 0; s < S; ++s) acc += part[s * stride + o];
-    dw[idx] = acc;
+    dw[((long)f * C + c) * taps + t] = acc;
 }
 
 // db[f] = sum over n, u, v of dy, in two fixed-order stages: kBiasSplit workgroups per filter

@@ -86,6 +86,9 @@ int launch_avgpool_bwd(const void *dy, void *dx, int N, int C, int H, int W, int
 int launch_pad_image(const float *x, void *xpad, int N, int C, int H, int W, int lo, int hi, dsk_dtype out,
                      hipStream_t st);
 int launch_act_bwd(const void *y, void *dy, size_t count, int act, dsk_dtype t, hipStream_t st);
+size_t act_bwd_bias_ws_bytes(int K);
+int launch_act_bwd_bias(const void *y, void *dy, float *db, int N, int K, long plane, int act, dsk_dtype t,
+                        void *ws, hipStream_t st);
 size_t softmax_xent_ws_bytes(long pixels);
 int launch_masked_softmax_xent(const float *scores, const int32_t *labels, const uint8_t *mask, float *loss,
                                void *dscores, dsk_dtype dt, int N, int Cls, int H, int W, void *ws,

@@ -53,6 +53,7 @@ class WholeImageNet:
                 self.biases.append(torch.zeros((p.K,), dtype=torch.float32, device=dev))
         if train:
             ws_bytes = max(ws_bytes, B.dsk_softmax_xent_workspace_bytes(N, last.K, H, W))
+            ws_bytes = max([ws_bytes] + [B.dsk_act_bwd_bias_workspace_bytes(p.K) for p in self.plan])
             self.loss = torch.zeros((1,), dtype=torch.float32, device=dev)
             self.dw = [torch.empty_like(w) for w in self.weights]
             self.db = [torch.empty_like(b) for b in self.biases]
@@ -120,10 +121,10 @@ class WholeImageNet:
             x, y = self.maps[l], self.maps[l + 1]
             gin = self._g[1 - cur][:x.numel()].view(x.shape) if l > 0 else None
             if p.kind == B.DSK_CONV:
-                if p.act != B.DSK_ACT_NONE:
-                    self._timed("act_bwd", l, B.dsk_act_bwd, y, g, p.act)
+                # non-linearity backward and bias gradient in one pass over the error map
+                self._timed("act_bwd", l, B.dsk_act_bwd_bias, y, g, p.act, db=self.db[ci], ws=self.ws)
                 self._timed("conv_bwd_weight", l, B.dsk_conv_bwd_weight, x, g, p.k, p.k, p.d, dw=self.dw[ci],
-                            db=self.db[ci], ws=self.ws)
+                            want_db=False, ws=self.ws)
                 if l > 0:        # nobody needs the error map of the image itself
                     self._timed("conv_bwd_data", l, B.dsk_conv_bwd_data, g, self.weights[ci], p.d, p.H, p.W,
                                 dx=gin, ws=self.ws)

@@ -82,12 +82,18 @@ def test_conv_bwd(case, algo):
         dw, db = dsk.dsk_conv_bwd_weight(xt, g, k, k, d)
         dw2, db2 = dsk.dsk_conv_bwd_weight(xt, g, k, k, d)
         dx = dsk.dsk_conv_bwd_data(g, wt, d, H, W)
+        # the fused form: non-linearity backward and bias gradient in one pass
+        g2 = _t(dy)
+        db_fused = dsk.dsk_act_bwd_bias(y, g2, act)
+        dw_nobias, none = dsk.dsk_conv_bwd_weight(xt, g2, k, k, d, want_db=False)
         torch.cuda.synchronize()
     finally:
         dsk.dsk_set_conv_algo(prev)
     assert_close(dw, rdw, "dw")
     assert_close(db, rdb, "db")
     assert_close(dx, rdx, "dx")
+    assert none is None and torch.equal(g2, g) and torch.equal(dw_nobias, dw)
+    assert_close(db_fused, rdb, "db (fused with the non-linearity backward)")
     assert torch.equal(dw, dw2) and torch.equal(db, db2), "bwd_weight is not run-to-run deterministic"
 
 

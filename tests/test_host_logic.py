@@ -142,6 +142,11 @@ def test_pool_act_loss_argument_errors():
     assert L.dsk_act_bwd(P, None, 10, 1, 0, None) == dsk.DSK_EINVAL
     assert L.dsk_act_bwd(P, P, 10, 4, 0, None) == dsk.DSK_EINVAL
     assert L.dsk_pad_image(P, P, 1, 3, 8, 8, -1, 0, 0, None) == dsk.DSK_EINVAL
+    nb = L.dsk_act_bwd_bias_workspace_bytes(7)
+    assert nb > 0
+    assert L.dsk_act_bwd_bias(P, P, P, 1, 7, 8, 8, 1, 0, None, 0, None) == dsk.DSK_EWORKSPACE
+    assert L.dsk_act_bwd_bias(None, P, P, 1, 7, 8, 8, 1, 0, P, nb, None) == dsk.DSK_EINVAL   # y needed for ReLU
+    assert L.dsk_act_bwd_bias(P, P, None, 1, 7, 8, 8, 0, 0, P, nb, None) == dsk.DSK_EINVAL
     need = L.dsk_softmax_xent_workspace_bytes(1, 5, 8, 8)
     assert need > 0
     assert L.dsk_masked_softmax_xent(P, P, P, P, P, 0, 1, 5, 8, 8, None, 0, None) == dsk.DSK_EWORKSPACE

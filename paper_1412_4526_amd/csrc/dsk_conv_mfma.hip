@@ -14,8 +14,6 @@
 //
 // fp32 path: v_mfma_f32_32x32x2_f32.  Lane l supplies A[i = l%32][k = l/32] and
 // B[k = l/32][j = l%32]; register r of the 16 results holds D[8*(r/4) + 4*(l/32) + r%4][l%32].
-#include <cstdlib>
-
 #include "dsk_internal.h"
 
 namespace dsk {
@@ -59,7 +57,6 @@ struct GcParams {
     long units;          // tiles * NC: a unit is one channel chunk of one tile
     long q;              // units per workgroup (NC: one whole tile each)
     long n_wg, per_xcd;  // logical workgroups; the grid is per_xcd * 8
-    int dbg;
 };
 
 // Weight layout transform.  flip = 0: wt[g][c][t][fl] = w[g*TF+fl][c][t]            (forward)
@@ -420,7 +417,6 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     p.tiles = g.tiles; p.units = g.units; p.q = g.q; p.n_wg = g.n_wg;
     p.per_xcd = (p.n_wg + kXcds - 1) / kXcds;
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;
-    { const char *e = getenv("DSK_DBG"); p.dbg = e ? atoi(e) : 0; }
     if (tin == DSK_F32 && tout == DSK_F32) gc_launch<float, float>(p, g, st);
     else if (tin == DSK_F32 && tout == DSK_BF16) gc_launch<float, bf16>(p, g, st);
     else if (tin == DSK_BF16 && tout == DSK_BF16) gc_launch<bf16, bf16>(p, g, st);
@@ -448,7 +444,6 @@ struct BwParams {
     long n_ptile;        // N * n_rowtile * n_coltile
     int S;               // split count
     int n_fblk, n_cblk;
-    int dbg;
 };
 
 // TPW: accumulator tiles (taps) per wave; XR: rows of the x tile, at most.
@@ -553,10 +548,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 
     long pt = s;
     if (PREFETCH && pt < p.n_ptile) load_tile(pt);
-    bool first = true;
     while (pt < p.n_ptile) {
-        if ((p.dbg & 1) && !first) goto compute;
-        first = false;
         if (!PREFETCH) load_tile(pt);
         __syncthreads();        // every wave is done with the previous tile
 #pragma unroll
@@ -576,8 +568,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
                     }
         }
         __syncthreads();
-        if (PREFETCH && pt + p.S < p.n_ptile && !(p.dbg & 1)) load_tile(pt + p.S);      // in flight while the matrix cores run
-    compute:
+        if (PREFETCH && pt + p.S < p.n_ptile) load_tile(pt + p.S);      // in flight while the matrix cores run
         pt += p.S;
         // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
         const float *ab = dys + lo * DY_STRIDE + hi;
@@ -777,7 +768,6 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     p.Kp = b.Kp; p.Cp = b.Cp; p.xrows = b.xrows; p.xcols = b.xcols; p.xstride = b.xstride;
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
     p.n_fblk = b.n_fblk; p.n_cblk = b.n_cblk;
-    { const char *e = getenv("DSK_DBG"); p.dbg = e ? atoi(e) : 0; }
     const unsigned grid = (unsigned)(((long)b.n_fblk * b.n_cblk * b.S + kXcds - 1) / kXcds * kXcds);
 #define DSK_BW_LAUNCH(TPW, XR, RS, PF)                                                                 \
     do {                                                                                               \

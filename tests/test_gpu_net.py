@@ -148,7 +148,9 @@ def test_benchmark_configs_sampled(ci):
     else:
         N, H, W = cfg.N, cfg.H, cfg.W
     dtypes = ["f32", "bf16"] if ci == 2 else [cfg.dtype]
-    n_fwd, n_bwd = (256, 256) if net.patch <= 67 else (96, 64)
+    # bf16 error maps carry zero-mean rounding noise that averages out over the masked patches; the
+    # real mask of the wide network has 20972 of them, so its check uses a larger sample than 64
+    n_fwd, n_bwd = (256, 256) if net.patch <= 67 else (96, 192)
     _say("config", ci, net.name, N, H, W, dtypes)
     wl = make_workload(net, N, H, W, cfg.mask_frac, cfg.seed, positive_frac=cfg.positive_frac)
     params = oracle.pack_params(wl.weights, wl.biases)

@@ -453,7 +453,11 @@ struct BwParams {
 // PREFETCH: fetch the next pixel tile into registers while the matrix cores work on the
 //   current one (needs the registers); otherwise the loads of a tile are issued together
 //   right before it is staged and a second resident workgroup covers their latency.
-template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH>
+// PACKB (layers with at most four input channels, e.g. the image): the 32 columns of the B
+//   operand are (channel, tap column b) pairs instead of 32 channels, so the accumulator
+//   tiles are indexed by the tap ROW only and a 5x5x3 kernel costs 5 MFMA columns of which
+//   15/32 are useful instead of 25 of which 3/32 are.
+template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false>
 __global__ void __launch_bounds__(kThreads, (TPW <= 9 ? 2 : 1))
 conv_bwd_weight_mfma_kernel(BwParams p)
 {
@@ -464,7 +468,8 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lo = lane & 31, hi = lane >> 5;
-    const int taps = p.kh * p.kw;
+    const int taps = PACKB ? p.kh : p.kh * p.kw;     // accumulator tiles per block
+    constexpr int NCI = PACKB ? 1 : 8;              // channels of the x tile each wave stages
 
     // All (filter block, channel block) workgroups of one pixel share are neighbours in the
     // logical order and, through the XCD-aware mapping, run on the same XCD at the same time:
@@ -487,8 +492,14 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     for (int t = 0; t < TPW; ++t) {
         int tap = ROWSPLIT ? t : wave + 4 * t;
         tap = tap < taps ? tap : 0;
-        const int a = tap / p.kw;
-        boff[t] = a * p.xcols + (tap - a * p.kw) * p.d;
+        const int a = PACKB ? tap : tap / p.kw;
+        boff[t] = a * p.xcols + (PACKB ? 0 : (tap - a * p.kw) * p.d);
+    }
+    // per-lane part of the B address: the lane's channel, and with PACKB also its tap column
+    int blane = lo * p.xstride;
+    if (PACKB) {
+        const int j = lo < p.C * p.kw ? lo : 0;      // lanes beyond the last pair repeat pair 0
+        blane = (j / p.kw) * p.xstride + (j % p.kw) * p.d;
     }
 
     f32x16 acc[TPW];
@@ -498,7 +509,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
     float dr[16];          // dy tile share: (filter, row) segments wave*2+hi+8i, column lo
-    float xr[8][XR];       // x tile share: channels wave+4*ci, rows r, column lane
+    float xr[NCI][XR];     // x tile share: channels wave+4*ci, rows r, column lane
 
     // Every tile starts inside both maps (the host enumerates only such tiles), so the tile's
     // base is always a valid address: loads that fall outside the maps are redirected there and
@@ -535,7 +546,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         st_nr_x = (p.H - u0 + p.d - 1) / p.d;             // x rows u0 + r*d that exist
         st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
 #pragma unroll
-        for (int ci = 0; ci < 8; ++ci) {
+        for (int ci = 0; ci < NCI; ++ci) {
             const int c = wave + 4 * ci;
 #pragma unroll
             for (int r = 0; r < XR; ++r) {
@@ -559,7 +570,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         }
         if (lane < p.xcols) {
 #pragma unroll
-            for (int ci = 0; ci < 8; ++ci)
+            for (int ci = 0; ci < NCI; ++ci)
 #pragma unroll
                 for (int r = 0; r < XR; ++r)
                     if (r < p.xrows) {
@@ -572,7 +583,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         pt += p.S;
         // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
         const float *ab = dys + lo * DY_STRIDE + hi;
-        const float *bb = xs + lo * p.xstride + hi;
+        const float *bb = xs + blane + hi;
         for (int r = ROWSPLIT ? wave : 0; r < (ROWSPLIT ? wave + 1 : PH); ++r) {
 #pragma unroll 4
             for (int q = 0; q < PW / 2; ++q) {
@@ -621,6 +632,25 @@ bw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, 
     dw[((long)f * C + c) * taps + t] = acc;
 }
 
+// The same for blocks whose 32 columns are (channel, tap column) pairs and whose tiles are tap rows.
+__global__ void __launch_bounds__(kThreads)
+bw_reduce_packb_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int kh, int kw, int Kp,
+                       int S)
+{
+    const int CB = C * kw;
+    const long total = (long)K * CB * kh;
+    const long idx = (long)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= total) return;
+    const int j = (int)(idx % CB);
+    const int f = (int)((idx / CB) % K);
+    const int a = (int)(idx / ((long)CB * K));
+    const long o = ((long)a * Kp + f) * 32 + j;
+    const long stride = (long)Kp * 32 * kh;
+    float acc = 0.f;
+    for (int s = 0; s < S; ++s) acc += part[s * stride + o];
+    dw[(((long)f * C + j / kw) * kh + a) * kw + j % kw] = acc;
+}
+
 // db[f] = sum over n, u, v of dy, in two fixed-order stages: kBiasSplit workgroups per filter
 // each reduce a contiguous share of every image's plane, then one thread per filter adds them.
 static constexpr int kBiasSplit = 32;
@@ -660,7 +690,7 @@ bias_reduce_kernel(const float *__restrict__ part, float *__restrict__ db, int K
 struct BwPlan {
     bool ok;
     int Kp, Cp, xrows, xcols, xstride, n_rowtile, n_coltile, S, n_fblk, n_cblk, tpw;
-    bool rowsplit;
+    bool rowsplit, packb;
     int n_part;          // partial blocks the reduce kernel adds up
     long n_ptile;
     size_t lds_bytes, part_bytes;
@@ -671,8 +701,10 @@ static BwPlan bw_plan(const ConvShape &s)
     BwPlan b{};
     const long taps = (long)s.kh * s.kw;
     if (taps > 52) return b;
-    b.rowsplit = taps == 1 || taps == 9;
-    b.tpw = b.rowsplit ? (int)taps : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
+    // few input channels: pack (channel, tap column) pairs into the 32 B-operand columns
+    b.packb = s.C <= 4 && s.C * s.kw <= 32 && s.kh >= 2 && s.kh <= 7;
+    b.rowsplit = !b.packb && (taps == 1 || taps == 9);
+    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
     b.Kp = (s.K + 31) / 32 * 32;
     b.Cp = (s.C + 31) / 32 * 32;
     b.n_fblk = b.Kp / 32;
@@ -680,7 +712,7 @@ static BwPlan bw_plan(const ConvShape &s)
     b.xrows = PH + s.kh - 1;
     const long xcols = (long)PW + (long)(s.kw - 1) * s.d;
     // one wave-wide load per x-tile row; XR = 8 rows except for the 13-taps-per-wave variant (10)
-    if (xcols > 64 || s.kh > (b.tpw == 13 ? 7 : 5)) return b;
+    if (xcols > 64 || s.kh > (b.tpw == 13 || b.packb ? 7 : 5)) return b;
     if ((long)s.H * s.W >= (1L << 24)) return b;         // 32-channel block offsets stay below 2^29 elements
     b.xcols = (int)xcols;
     b.xstride = (b.xrows * b.xcols) | 1;
@@ -701,7 +733,7 @@ static BwPlan bw_plan(const ConvShape &s)
     if (S < 1) S = 1;
     b.S = (int)S;
     b.n_part = b.rowsplit ? 4 * b.S : b.S;
-    b.part_bytes = 4 * ((size_t)b.n_part * b.Kp * b.Cp * taps + (size_t)s.K * kBiasSplit);
+    b.part_bytes = 4 * ((size_t)b.n_part * b.Kp * b.Cp * (b.packb ? s.kh : taps) + (size_t)s.K * kBiasSplit);
     b.ok = true;
     return b;
 }
@@ -769,34 +801,40 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
     p.n_fblk = b.n_fblk; p.n_cblk = b.n_cblk;
     const unsigned grid = (unsigned)(((long)b.n_fblk * b.n_cblk * b.S + kXcds - 1) / kXcds * kXcds);
-#define DSK_BW_LAUNCH(TPW, XR, RS, PF)                                                                 \
+#define DSK_BW_LAUNCH(TPW, XR, RS, PF, PB)                                                                 \
     do {                                                                                               \
         if (in == DSK_F32) {                                                                           \
-            allow_lds(conv_bwd_weight_mfma_kernel<float, TPW, XR, RS, PF>, b.lds_bytes);               \
-            conv_bwd_weight_mfma_kernel<float, TPW, XR, RS, PF>                                        \
+            allow_lds(conv_bwd_weight_mfma_kernel<float, TPW, XR, RS, PF, PB>, b.lds_bytes);               \
+            conv_bwd_weight_mfma_kernel<float, TPW, XR, RS, PF, PB>                                        \
                 <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                  \
         } else {                                                                                       \
-            allow_lds(conv_bwd_weight_mfma_kernel<bf16, TPW, XR, RS, PF>, b.lds_bytes);                \
-            conv_bwd_weight_mfma_kernel<bf16, TPW, XR, RS, PF>                                         \
+            allow_lds(conv_bwd_weight_mfma_kernel<bf16, TPW, XR, RS, PF, PB>, b.lds_bytes);                \
+            conv_bwd_weight_mfma_kernel<bf16, TPW, XR, RS, PF, PB>                                         \
                 <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                  \
         }                                                                                              \
     } while (0)
-    if (b.rowsplit && b.tpw == 1) DSK_BW_LAUNCH(1, 8, true, true);
-    else if (b.rowsplit) DSK_BW_LAUNCH(9, 8, true, false);
-    else if (b.tpw == 1) DSK_BW_LAUNCH(1, 8, false, true);
-    else if (b.tpw == 2) DSK_BW_LAUNCH(2, 8, false, true);
-    else if (b.tpw == 4) DSK_BW_LAUNCH(4, 8, false, true);
-    else if (b.tpw == 7) DSK_BW_LAUNCH(7, 8, false, false);
-    else DSK_BW_LAUNCH(13, 10, false, false);
+    if (b.packb && b.xrows <= 8) DSK_BW_LAUNCH(2, 8, false, true, true);
+    else if (b.packb) DSK_BW_LAUNCH(2, 10, false, true, true);
+    else if (b.rowsplit && b.tpw == 1) DSK_BW_LAUNCH(1, 8, true, true, false);
+    else if (b.rowsplit) DSK_BW_LAUNCH(9, 8, true, false, false);
+    else if (b.tpw == 1) DSK_BW_LAUNCH(1, 8, false, true, false);
+    else if (b.tpw == 2) DSK_BW_LAUNCH(2, 8, false, true, false);
+    else if (b.tpw == 4) DSK_BW_LAUNCH(4, 8, false, true, false);
+    else if (b.tpw == 7) DSK_BW_LAUNCH(7, 8, false, false, false);
+    else DSK_BW_LAUNCH(13, 10, false, false, false);
 #undef DSK_BW_LAUNCH
     int rc = check_launch();
     if (rc != DSK_OK) return rc;
     const long total = (long)s.K * s.C * taps;
-    bw_reduce_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
-        (const float *)ws, dw, s.K, s.C, taps, b.Kp, b.Cp, b.n_part);
+    if (b.packb)
+        bw_reduce_packb_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+            (const float *)ws, dw, s.K, s.C, s.kh, s.kw, b.Kp, b.n_part);
+    else
+        bw_reduce_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+            (const float *)ws, dw, s.K, s.C, taps, b.Kp, b.Cp, b.n_part);
     rc = check_launch();
     if (rc != DSK_OK || !db) return rc;
-    float *bpart = (float *)ws + (size_t)b.n_part * b.Kp * b.Cp * taps;
+    float *bpart = (float *)ws + (size_t)b.n_part * b.Kp * b.Cp * (b.packb ? s.kh : taps);
     if (in == DSK_F32)
         bias_partial_kernel<float><<<dim3(s.K * kBiasSplit), dim3(kThreads), 0, st>>>((const float *)dy, bpart, s.N,
                                                                                     s.K, (long)s.Ho * s.Wo);

@@ -97,6 +97,33 @@ def test_conv_bwd(case, algo):
     assert torch.equal(dw, dw2) and torch.equal(db, db2), "bwd_weight is not run-to-run deterministic"
 
 
+@pytest.mark.parametrize("case", CONV_CASES + [(1, 32, 200, 300, 64, 5, 2, 1), (1, 64, 150, 600, 128, 4, 8, 1)],
+                         ids=lambda c: "N%dC%dH%dW%dK%dk%dd%da%d" % c)
+def test_conv_workspace_is_enough_and_respected(case):
+    """The three conv calls stay inside the workspace size the library asks for: a guard band
+    behind it keeps its pattern (no oracle here: results are covered by the parity tests)."""
+    N, C, H, W, K, k, d, act = case
+    _say("conv workspace", case)
+    x = torch.rand((N, C, H, W), device=DEV) - 0.5
+    w = torch.randn((K, C, k, k), device=DEV) * 0.1
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    dy = torch.randn((N, K, Ho, Wo), device=DEV)
+    guard = 1 << 16
+    for which in (dsk.DSK_WS_CONV_FWD, dsk.DSK_WS_CONV_BWD_DATA, dsk.DSK_WS_CONV_BWD_WEIGHT):
+        need = dsk.dsk_conv_workspace_bytes(which, N, C, H, W, K, k, k, d, dsk.DSK_F32)
+        need16 = (need + 15) // 16 * 16
+        buf = torch.full((need16 + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+        ws = buf[:max(need16, 16)]
+        if which == dsk.DSK_WS_CONV_FWD:
+            dsk.dsk_conv_fwd(x, w, None, d, act, ws=ws)
+        elif which == dsk.DSK_WS_CONV_BWD_DATA:
+            dsk.dsk_conv_bwd_data(dy, w, d, H, W, ws=ws)
+        else:
+            dsk.dsk_conv_bwd_weight(x, dy, k, k, d, ws=ws)
+        torch.cuda.synchronize()
+        assert bool((buf[need16:] == 0xA5).all()), "write beyond the workspace (call %d)" % which
+
+
 def test_conv_bf16_variant():
     """bf16 activations/weights, fp32 accumulate: within 2e-2 of the fp32 oracle on the
     unrounded inputs, and within fp32 tolerance of the oracle fed the rounded inputs."""

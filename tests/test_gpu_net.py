@@ -88,6 +88,28 @@ def test_empty_mask_gives_zero_loss_and_gradients():
     assert all(not t.any().item() for t in dws + dbs)
 
 
+def test_whole_net_is_run_to_run_deterministic():
+    """No atomics anywhere on the path: two passes over the same input give bit-identical
+    scores, loss and gradients (split-K partial sums and split tiles are added in a fixed order)."""
+    cfg = CONFIGS[1]
+    net = cfg.net
+    N, H, W = 2, 150, 210
+    wl = make_workload(net, N, H, W, 0.05, seed=5, bias_std=0.1)
+    m = dsk.WholeImageNet(net, N, H, W, "f32", DEV)
+    m.load_params(wl.weights, wl.biases)
+    image = torch.from_numpy(wl.image).to(DEV)
+    labels = torch.from_numpy(wl.labels).to(DEV)
+    mask = torch.from_numpy(wl.mask).to(DEV)
+    runs = []
+    for _ in range(2):
+        scores = m.forward(image).clone()
+        loss, dws, dbs = m.loss_backward(labels, mask)
+        torch.cuda.synchronize()
+        runs.append([scores, loss.clone()] + [t.clone() for t in dws + dbs])
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
+
+
 def _check_intermediates(net, m, wl, params, xpad, pix, bf16):
     """Layer-by-layer correspondence at a few pixels, and argmax agreement."""
     D = np.cumprod([L.s for L in net.layers])

@@ -54,8 +54,8 @@ struct GcParams {
     int xs_floats;       // Cc*chan_stride rounded up to a multiple of 4
     int n_rowtile, n_coltile, n_fgrp;
     long tiles;          // N * n_rowtile * n_coltile * n_fgrp output tiles
-    long units;          // tiles * NC: a unit is one channel chunk of one tile
-    long q;              // units per workgroup (NC: one whole tile each)
+    int rounds;          // persistent workgroups: whole tiles each of them takes first
+    int rem_units;       // (tiles - rounds * n_wg) * NC: chunks of the tiles left after that
     long n_wg, per_xcd;  // logical workgroups; the grid is per_xcd * 8
 };
 
@@ -125,12 +125,16 @@ __device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][4]
 // XI / WI: upper bounds of what one thread stages per chunk: input-tile elements
 // (Cc*chan_stride <= 256*XI) and weight float4s (Cc*taps*TF <= 1024*WI).
 //
-// Work distribution: the (tile, channel chunk) units are numbered tile-major and logical
-// workgroup g takes units [g*q, (g+1)*q).  With q = NC every workgroup owns exactly one tile.
-// With fewer, persistent workgroups (q > NC, chosen by the host when the tile count is not
-// a comfortable multiple of what the chip holds at once) a range may begin or end inside a
-// tile; such a piece is written as raw accumulators to `partial` and gc_fixup_kernel adds
-// the two pieces of every split tile in a fixed order and applies the epilogue.
+// Work distribution.  SPLIT = false: logical workgroup g owns tile g.  SPLIT = true (chosen
+// by the host when the tile count is not a comfortable multiple of what the chip holds at
+// once): n_wg persistent workgroups first take `rounds` whole tiles each, round r giving
+// tile r*n_wg + g to workgroup g, so that workgroups running side by side work on
+// neighbouring tiles and share their input through the L2.  The channel chunks of the
+// tiles left over (fewer than n_wg) are numbered tile-major and workgroup g takes chunks
+// [g*U/n_wg, (g+1)*U/n_wg) of these U, so the shares differ by one chunk at most and every
+// XCD stays busy.  Such a range may begin or end inside a tile; a piece of a tile is
+// written as raw accumulators to `partial`, and gc_fixup_kernel adds the pieces of every
+// left-over tile in a fixed order and applies the epilogue.
 //
 // Pipeline: the global loads of chunk t+1 are issued before the matrix cores start on chunk
 // t and land in registers meanwhile; they are written to LDS after chunk t is done.
@@ -151,8 +155,9 @@ gemm_conv_kernel(GcParams p)
     // run of logical workgroups so that neighbours (shared halo, same input tile) share an L2
     const long wg = (long)(blockIdx.x % kXcds) * p.per_xcd + blockIdx.x / kXcds;
     if (wg >= p.n_wg) return;
-    long ub = SPLIT ? wg * p.q : wg * p.NC;
-    const long ue = SPLIT ? (ub + p.q < p.units ? ub + p.q : p.units) : ub + p.NC;
+    int round = 0;
+    int ub = (int)wg * p.rem_units / (int)p.n_wg;      // rem_units * n_wg < 2^31 by the host's choice
+    const int ue = ((int)wg + 1) * p.rem_units / (int)p.n_wg;
 
     const unsigned HW = (unsigned)(p.Hin * p.Win);   // Cin*Hin*Win < 2^30 is checked on the host
     const int taps = p.kh * p.kw;
@@ -163,10 +168,20 @@ gemm_conv_kernel(GcParams p)
     const float *wlane = wsm + hi * taps * TF + lo;
 
     bool first_piece = true;
-    do {
-        const long tile = SPLIT ? ub / p.NC : wg;
-        const int cb = SPLIT ? (int)(ub - tile * p.NC) : 0;
-        const int ce = SPLIT ? ((long)cb + (ue - ub) < p.NC ? cb + (int)(ue - ub) : p.NC) : p.NC;
+    for (;;) {
+        long tile = wg;
+        int cb = 0, ce = p.NC;
+        if (SPLIT) {
+            if (round < p.rounds) {
+                tile = round * p.n_wg + wg;
+            } else {
+                if (ub >= ue) break;
+                const int lt = ub / p.NC;
+                tile = p.rounds * p.n_wg + lt;
+                cb = ub - lt * p.NC;
+                ce = cb + (ue - ub) < p.NC ? cb + (ue - ub) : p.NC;
+            }
+        }
         int fg, n, u0, v0;
         gc_decode_tile(p, tile, fg, n, u0, v0);
         const TI *in_n = (const TI *)p.in + (long)n * p.Cin * (long)HW;
@@ -271,37 +286,66 @@ gemm_conv_kernel(GcParams p)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) slot[((wm * 4 + wn) * 16 + i) * kThreads + tid] = acc[wm][wn][i];
         }
-        ub += ce - cb;
-        first_piece = false;
-    } while (SPLIT && ub < ue);
+        if (!SPLIT) break;
+        if (round < p.rounds) {
+            ++round;
+        } else {
+            ub += ce - cb;
+            first_piece = false;
+        }
+    }
 }
 
-// Adds the two pieces of the tile that the boundary between logical workgroups g and g+1
-// cuts (the end piece of g first, then the begin piece of g+1) and finishes it.
+// Adds the pieces of every left-over tile in the order of the workgroups that computed them
+// and finishes it.  A workgroup's range is at most NC chunks long, so it meets at most two
+// tiles: slot 2g holds the piece its range begins with, 2g+1 the other one.  A thread owns
+// kFixRows accumulator registers of one lane of the tile; a tile takes WM*64/kFixRows workgroups.
+static constexpr int kFixRows = 8;
+
 template <typename TO, int WM>
 __global__ void __launch_bounds__(kThreads)
 gc_fixup_kernel(GcParams p)
 {
-    const long g = blockIdx.x;
-    const long boundary = (g + 1) * p.q;
-    if (boundary >= p.units || boundary % p.NC == 0) return;
+    constexpr int TF = WM * 32;
+    constexpr int BPT = WM * 64 / kFixRows;
+    const int lt = blockIdx.x / BPT, r0 = (blockIdx.x % BPT) * kFixRows;
+    // chunk u belongs to the last workgroup g with g*U/n_wg <= u; U*n_wg < 2^31 by the host's choice
+    const int U = p.rem_units, P = (int)p.n_wg;
+    const int g_first = ((lt * p.NC + 1) * P + U - 1) / U - 1;
+    const int g_last = ((lt + 1) * p.NC * P + U - 1) / U - 1;
+    if (g_first == g_last) return;     // one workgroup had the whole tile and finished it
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lo = lane & 31, hi = lane >> 5;
+    float acc[kFixRows];
+#pragma unroll
+    for (int r = 0; r < kFixRows; ++r) acc[r] = 0.f;
+    for (int g = g_first; g <= g_last; ++g) {
+        const int g_begin = g * U / P;
+        if (g_begin == (g + 1) * U / P) continue;     // fewer chunks than workgroups: empty range
+        const int second = g_begin / p.NC == lt ? 0 : 1;
+        const float *piece = p.partial + (long)(2 * g + second) * (WM * 64 * kThreads) + r0 * kThreads + tid;
+#pragma unroll
+        for (int r = 0; r < kFixRows; ++r) acc[r] += piece[r * kThreads];
+    }
     int fg, n, u0, v0;
-    gc_decode_tile(p, boundary / p.NC, fg, n, u0, v0);
-    const float *end_piece = p.partial + (2 * g + 1) * (long)(WM * 64 * kThreads);
-    const float *begin_piece = p.partial + (2 * (g + 1)) * (long)(WM * 64 * kThreads);
-    f32x16 acc[WM][4];
+    gc_decode_tile(p, (long)p.rounds * P + lt, fg, n, u0, v0);
+    // register r0 + r of the lane is acc[wm][wn][i] of the convolution kernel
+    const int wm = r0 / 64, wn = (r0 / 16) % 4, i0 = r0 % 16;
+    const int row = u0 + (2 * wave + (wn >> 1)) * p.d;
+    const int col = v0 + (wn & 1) * 32 + lo;
+    if (row >= p.Hout || col >= p.Wout) return;
+    TO *out = (TO *)p.out;
 #pragma unroll
-    for (int wm = 0; wm < WM; ++wm)
-#pragma unroll
-        for (int wn = 0; wn < 4; ++wn)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int o = ((wm * 4 + wn) * 16 + i) * kThreads + tid;
-                acc[wm][wn][i] = end_piece[o] + begin_piece[o];
-            }
-    gc_epilogue<TO, WM>(p, acc, fg, n, u0, v0, wave, lo, hi);
+    for (int r = 0; r < kFixRows; ++r) {
+        const int i = i0 + r;
+        const int f = fg * TF + wm * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
+        if (f < p.Fout) {
+            float v = acc[r];
+            if (p.bias) v += p.bias[f];
+            v = act_apply(p.act, v);
+            stf(out, (((long)n * p.Fout + f) * p.Hout + row) * p.Wout + col, v);
+        }
+    }
 }
 
 static constexpr int kXI = 16;   // input-tile elements per thread per chunk, at most
@@ -311,7 +355,8 @@ static constexpr long kSlots = 512;   // workgroups resident at once: 2 per CU, 
 struct GcPlan {
     bool ok, split;      // split: persistent workgroups with split tiles
     int TF, WM, Cc, Cpad, NC, rows, cols, chan_stride, xs_floats, n_fgrp, n_rowtile, n_coltile;
-    long tiles, units, q, n_wg;
+    long tiles, n_wg;
+    int rounds, rem_units;
     size_t lds_bytes, wt_bytes, partial_bytes;
 };
 
@@ -354,18 +399,19 @@ static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
     g.tiles = (long)N * g.n_rowtile * g.n_coltile * g.n_fgrp;
     // Tiles are all equally long, so with T tiles and S resident workgroups the last round of a
     // one-tile-per-workgroup launch leaves S - (T mod S) slots idle.  When that costs more than
-    // a few per cent, S persistent workgroups take T*NC/S chunks each instead.
-    g.split = g.tiles > kSlots && g.tiles < 12 * kSlots && g.tiles % kSlots != 0;
+    // a few per cent, S persistent workgroups take T/S whole tiles each and share the channel
+    // chunks of the remaining T mod S tiles evenly.
+    // (NC <= 4096 keeps the 32-bit chunk arithmetic of the kernels exact)
+    g.split = g.tiles > kSlots && g.tiles < 12 * kSlots && g.tiles % kSlots != 0 && g.NC <= 4096;
     if (g.split) {
         g.n_wg = kSlots;
-        g.units = g.tiles * g.NC;
-        g.q = (g.units + g.n_wg - 1) / g.n_wg;
-        g.n_wg = (g.units + g.q - 1) / g.q;
+        g.rounds = (int)(g.tiles / g.n_wg);
+        g.rem_units = (int)(g.tiles - g.rounds * g.n_wg) * g.NC;
         g.partial_bytes = 4 * (size_t)(2 * g.n_wg) * g.WM * 64 * kThreads;
     } else {
         g.n_wg = g.tiles;
-        g.units = g.tiles * g.NC;
-        g.q = g.NC;
+        g.rounds = 0;
+        g.rem_units = 0;
         g.partial_bytes = 0;
     }
     g.ok = true;
@@ -385,10 +431,11 @@ static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
     else
         gemm_conv_kernel<TI, TO, 1, kXI, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     if (g.split) {
+        const unsigned left = (unsigned)(g.rem_units / g.NC);
         if (g.WM == 2)
-            gc_fixup_kernel<TO, 2><<<dim3((unsigned)(g.n_wg - 1)), dim3(kThreads), 0, st>>>(p);
+            gc_fixup_kernel<TO, 2><<<dim3(left * (2 * 64 / kFixRows)), dim3(kThreads), 0, st>>>(p);
         else
-            gc_fixup_kernel<TO, 1><<<dim3((unsigned)(g.n_wg - 1)), dim3(kThreads), 0, st>>>(p);
+            gc_fixup_kernel<TO, 1><<<dim3(left * (64 / kFixRows)), dim3(kThreads), 0, st>>>(p);
     }
 }
 
@@ -414,7 +461,7 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     p.Cpad = g.Cpad; p.Cc = g.Cc; p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.chan_stride = g.chan_stride;
     p.xs_floats = g.xs_floats;
     p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp;
-    p.tiles = g.tiles; p.units = g.units; p.q = g.q; p.n_wg = g.n_wg;
+    p.tiles = g.tiles; p.rounds = g.rounds; p.rem_units = g.rem_units; p.n_wg = g.n_wg;
     p.per_xcd = (p.n_wg + kXcds - 1) / kXcds;
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;
     if (tin == DSK_F32 && tout == DSK_F32) gc_launch<float, float>(p, g, st);
@@ -614,22 +661,47 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     }
 }
 
-// dw[f][c][t] = sum over the partial blocks, in block order.  Threads run over [t][f][c] with c
-// fastest, the order the partial blocks are stored in, so the reads are coalesced.
+// dw[f][c][t] = sum over the S partial blocks, in a fixed order.  A workgroup takes 32
+// consecutive outputs in the order the blocks are stored in ([t][f][c], c fastest: coalesced
+// reads) and its eight groups of 32 threads take every eighth block each, with four running
+// sums so that loads overlap; the 32 partial sums of an output are then added in one order.
+static constexpr int kRedOut = 32, kRedGroups = kThreads / kRedOut;
+
+__device__ inline float bw_reduce_sum(const float *__restrict__ src, long stride, int S, bool valid, float *red)
+{
+    const int j = threadIdx.x % kRedOut, sg = threadIdx.x / kRedOut;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    if (valid) {
+        int s = sg;
+        for (; s + 3 * kRedGroups < S; s += 4 * kRedGroups) {
+            a0 += src[s * stride];
+            a1 += src[(s + kRedGroups) * stride];
+            a2 += src[(s + 2 * kRedGroups) * stride];
+            a3 += src[(s + 3 * kRedGroups) * stride];
+        }
+        for (; s < S; s += kRedGroups) a0 += src[s * stride];
+    }
+    red[sg * kRedOut + j] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    float v = 0.f;
+    if (sg == 0)
+        for (int q = 0; q < kRedGroups; ++q) v += red[q * kRedOut + j];
+    return v;
+}
+
 __global__ void __launch_bounds__(kThreads)
 bw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int taps, int Kp, int Cp, int S)
 {
+    __shared__ float red[kThreads];
     const long total = (long)K * C * taps;
-    const long idx = (long)blockIdx.x * kThreads + threadIdx.x;
-    if (idx >= total) return;
+    const long idx = (long)blockIdx.x * kRedOut + threadIdx.x % kRedOut;
+    const bool valid = idx < total;
     const int c = (int)(idx % C);
     const int f = (int)((idx / C) % K);
     const int t = (int)(idx / ((long)C * K));
     const long o = ((long)t * Kp + f) * Cp + c;
-    const long stride = (long)Kp * Cp * taps;
-    float acc = 0.f;
-    for (int s = 0; s < S; ++s) acc += part[s * stride + o];
-    dw[((long)f * C + c) * taps + t] = acc;
+    const float v = bw_reduce_sum(part + (valid ? o : 0), (long)Kp * Cp * taps, S, valid, red);
+    if (valid && threadIdx.x < kRedOut) dw[((long)f * C + c) * taps + t] = v;
 }
 
 // The same for blocks whose 32 columns are (channel, tap column) pairs and whose tiles are tap rows.
@@ -637,18 +709,17 @@ __global__ void __launch_bounds__(kThreads)
 bw_reduce_packb_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int kh, int kw, int Kp,
                        int S)
 {
+    __shared__ float red[kThreads];
     const int CB = C * kw;
     const long total = (long)K * CB * kh;
-    const long idx = (long)blockIdx.x * kThreads + threadIdx.x;
-    if (idx >= total) return;
+    const long idx = (long)blockIdx.x * kRedOut + threadIdx.x % kRedOut;
+    const bool valid = idx < total;
     const int j = (int)(idx % CB);
     const int f = (int)((idx / CB) % K);
     const int a = (int)(idx / ((long)CB * K));
     const long o = ((long)a * Kp + f) * 32 + j;
-    const long stride = (long)Kp * 32 * kh;
-    float acc = 0.f;
-    for (int s = 0; s < S; ++s) acc += part[s * stride + o];
-    dw[(((long)f * C + j / kw) * kh + a) * kw + j % kw] = acc;
+    const float v = bw_reduce_sum(part + (valid ? o : 0), (long)Kp * 32 * kh, S, valid, red);
+    if (valid && threadIdx.x < kRedOut) dw[(((long)f * C + j / kw) * kh + a) * kw + j % kw] = v;
 }
 
 // db[f] = sum over n, u, v of dy, in two fixed-order stages: kBiasSplit workgroups per filter
@@ -827,10 +898,10 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     if (rc != DSK_OK) return rc;
     const long total = (long)s.K * s.C * taps;
     if (b.packb)
-        bw_reduce_packb_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+        bw_reduce_packb_kernel<<<dim3((unsigned)((total + kRedOut - 1) / kRedOut)), dim3(kThreads), 0, st>>>(
             (const float *)ws, dw, s.K, s.C, s.kh, s.kw, b.Kp, b.n_part);
     else
-        bw_reduce_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+        bw_reduce_kernel<<<dim3((unsigned)((total + kRedOut - 1) / kRedOut)), dim3(kThreads), 0, st>>>(
             (const float *)ws, dw, s.K, s.C, taps, b.Kp, b.Cp, b.n_part);
     rc = check_launch();
     if (rc != DSK_OK || !db) return rc;

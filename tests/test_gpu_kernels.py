@@ -97,6 +97,38 @@ def test_conv_bwd(case, algo):
     assert torch.equal(dw, dw2) and torch.equal(db, db2), "bwd_weight is not run-to-run deterministic"
 
 
+# More output tiles than the 512 workgroups the chip holds at once, and not a multiple of it:
+# persistent workgroups take whole tiles first and share the channel chunks of the rest.
+SPLIT_CASES = [
+    (1, 24, 826, 322, 32, 3, 1, 1),    # fwd: 515 tiles, 3 left over, fewer chunks than workgroups
+    (2, 16, 300, 400, 40, 3, 2, 1),    # fwd: 532 tiles of 2 chunks
+    (1, 24, 500, 700, 16, 3, 1, 0),    # fwd: 693 tiles of 3 chunks, 181 left over
+]
+
+
+@pytest.mark.parametrize("case", SPLIT_CASES, ids=lambda c: "N%dC%dH%dW%dK%dk%dd%da%d" % c)
+def test_conv_split_tiles(case):
+    N, C, H, W, K, k, d, act = case
+    _say("conv split tiles", case)
+    rng = np.random.default_rng(hash(case) % 2**31 + 2)
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = (rng.standard_normal((K, C, k, k)) * np.sqrt(2.0 / (C * k * k))).astype(np.float32)
+    b = (rng.standard_normal(K) * 0.2).astype(np.float32)
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    dy = rng.standard_normal((N, K, Ho, Wo)).astype(np.float32)
+    dy[rng.random(dy.shape) < 0.5] = 0.0
+    ref = oracle_conv_fwd(x, w, b, d, dsk.DSK_ACT_NONE)
+    rdw, rdb, rdx = oracle_conv_bwd(x, w, b, d, dsk.DSK_ACT_NONE, dy)
+    xt, wt, g = _t(x), _t(w), _t(dy)
+    y = dsk.dsk_conv_fwd(xt, wt, _t(b), d, dsk.DSK_ACT_NONE)
+    dx = dsk.dsk_conv_bwd_data(g, wt, d, H, W)
+    dx2 = dsk.dsk_conv_bwd_data(g, wt, d, H, W)
+    torch.cuda.synchronize()
+    assert_close(y, ref, "conv_fwd")
+    assert_close(dx, rdx, "dx")
+    assert torch.equal(dx, dx2), "bwd_data is not run-to-run deterministic"
+
+
 @pytest.mark.parametrize("case", CONV_CASES + [(1, 32, 200, 300, 64, 5, 2, 1), (1, 64, 150, 600, 128, 4, 8, 1)],
                          ids=lambda c: "N%dC%dH%dW%dK%dk%dd%da%d" % c)
 def test_conv_workspace_is_enough_and_respected(case):

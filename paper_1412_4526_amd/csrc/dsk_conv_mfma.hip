@@ -19,6 +19,7 @@
 namespace dsk {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 static constexpr int kThreads = 256;
 static constexpr int kXcds = 8;
@@ -51,7 +52,8 @@ struct GcParams {
     int Cpad, Cc, NC;    // padded channel count, channels per LDS chunk (even), chunks per tile
     int rows, cols;      // LDS tile: TH+kh-1 by TW+(kw-1)*d
     int chan_stride;     // rows*cols
-    int xs_floats;       // Cc*chan_stride rounded up to a multiple of 4
+    int xs_floats;       // Cc*chan_stride rounded up to a multiple of 256
+    int n_xi, n_wi;      // per thread and chunk: input-tile floats, weight float4s (both LDS parts padded)
     int n_rowtile, n_coltile, n_fgrp;
     long tiles;          // N * n_rowtile * n_coltile * n_fgrp output tiles
     int rounds;          // persistent workgroups: whole tiles each of them takes first
@@ -94,28 +96,36 @@ __device__ inline void gc_decode_tile(const GcParams &p, long tile, int &fg, int
     v0 = ct * TW;
 }
 
-// bias, non-linearity, store; 32 consecutive pixels per filter per store instruction
+// bias, non-linearity, store; 32 consecutive pixels per filter per store instruction.
+// Register i of a lane belongs to filter 8*(i/4) + (i%4) + 4*hi of its 32-filter block: the
+// two candidates are uniform over the wave, so their biases come through scalar loads.
 template <typename TO, int WM>
 __device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][4], int fg, int n, int u0, int v0,
                                    int wave, int lo, int hi)
 {
     constexpr int TF = WM * 32;
-    TO *out = (TO *)p.out;
+    const long plane = (long)p.Hout * p.Wout;
+    TO *out_n = (TO *)p.out + ((long)n * p.Fout + (long)fg * TF) * plane;
+    const int f_left = p.Fout - fg * TF;      // filters of this group that exist
 #pragma unroll
     for (int wn = 0; wn < 4; ++wn) {
         const int row = u0 + (2 * wave + (wn >> 1)) * p.d;
         const int col = v0 + (wn & 1) * 32 + lo;
         if (row >= p.Hout || col >= p.Wout) continue;
+        TO *o = out_n + (long)row * p.Wout + col + (hi ? 4 * plane : 0);
 #pragma unroll
         for (int wm = 0; wm < WM; ++wm) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int f = fg * TF + wm * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
-                if (f < p.Fout) {
+                const int fl = wm * 32 + 8 * (i / 4) + (i % 4);      // filter of the hi = 0 lanes
+                if (fl + 4 * hi < f_left) {
                     float v = acc[wm][wn][i];
-                    if (p.bias) v += p.bias[f];
-                    v = act_apply(p.act, v);
-                    stf(out, (((long)n * p.Fout + f) * p.Hout + row) * p.Wout + col, v);
+                    if (p.bias) {
+                        const float b0 = p.bias[fg * TF + fl];
+                        const float b1 = fl + 4 < f_left ? p.bias[fg * TF + fl + 4] : 0.f;
+                        v += hi ? b1 : b0;
+                    }
+                    stf(o, (long)fl * plane, act_apply(p.act, v));
                 }
             }
         }
@@ -187,23 +197,23 @@ gemm_conv_kernel(GcParams p)
         const TI *in_n = (const TI *)p.in + (long)n * p.Cin * (long)HW;
 
         // Where this thread's share of the input tile comes from; the same for every chunk.
-        // Element e = tid + 256*i of the tile [Cc][rows][cols]:  >= 0: (local channel << 28) |
-        // offset inside the channel plane;  -2: inside the tile but outside the map (zero);
-        // -1: beyond the tile.
-        int xoff[XI];
+        // Element e = tid + 256*i of the tile [Cc][rows][cols] (padded to a multiple of 256)
+        // is read at voff[i] floats beyond the first channel of the chunk; elements outside
+        // the map, or in the padding, are read from offset 0 instead, which is always a valid
+        // address, and bit i of `zero` says that the tile gets 0 there.
+        unsigned voff[XI];
+        unsigned zero = 0;
         {
             const int n_x = p.Cc * p.chan_stride;
 #pragma unroll
             for (int i = 0; i < XI; ++i) {
                 const int e = tid + i * kThreads;
-                int pk = -1;
-                if (e < n_x) {
-                    const int c = e / p.chan_stride, rem = e - c * p.chan_stride;
-                    const int r = rem / p.cols, col = rem - r * p.cols;
-                    const int irow = u0 + r * p.d - p.off_h, icol = v0 + col - p.off_w;
-                    pk = (irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win) ? ((c << 28) | (irow * p.Win + icol)) : -2;
-                }
-                xoff[i] = pk;
+                const int c = e / p.chan_stride, rem = e - c * p.chan_stride;
+                const int r = rem / p.cols, col = rem - r * p.cols;
+                const int irow = u0 + r * p.d - p.off_h, icol = v0 + col - p.off_w;
+                const bool ok = e < n_x && irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win;
+                voff[i] = ok ? (unsigned)c * HW + (unsigned)(irow * p.Win + icol) : 0u;
+                zero |= ok ? 0u : 1u << i;
             }
         }
 
@@ -216,25 +226,30 @@ gemm_conv_kernel(GcParams p)
                 for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
 
         float xv[XI];
-        float4 wv[WI];
-        auto fetch = [&](int c0) {
+        f32x4 wv[WI];
+        // Every load is issued unconditionally (padding reads offset 0): a load under a
+        // condition makes the compiler wait for it right away to merge the two values.
+        auto fetch = [&](int c0) __attribute__((always_inline)) {
+            const TI *src = in_n + (long)c0 * (long)HW;
+            if (c0 + p.Cc <= p.Cin) {
 #pragma unroll
-            for (int i = 0; i < XI; ++i) {
-                const int pk = xoff[i];
-                float v = 0.f;
-                if (pk >= 0) {
-                    // channels beyond Cin meet zero weights; clamp so the address stays inside the tensor
-                    unsigned gc = (unsigned)(c0 + (pk >> 28));
-                    gc = gc < (unsigned)p.Cin ? gc : (unsigned)p.Cin - 1u;
-                    v = ldf(in_n, (long)(gc * HW + (unsigned)(pk & 0x0fffffff)));
+                for (int i = 0; i < XI; ++i) xv[i] = ldf(src, voff[i]);
+            } else {
+                // last chunk of a padded channel count: channels beyond Cin meet zero weights;
+                // read the chunk's first channel instead so the address stays inside the tensor
+#pragma unroll
+                for (int i = 0; i < XI; ++i) {
+                    unsigned v = voff[i];
+                    const unsigned cl = v / HW;
+                    v -= c0 + (int)cl >= p.Cin ? cl * HW : 0u;
+                    xv[i] = ldf(src, v);
                 }
-                xv[i] = v;
             }
-            const float4 *wsrc = (const float4 *)(p.wt + ((long)fg * p.Cpad + c0) * taps * TF);
+            const f32x4 *wsrc = (const f32x4 *)(p.wt + ((long)fg * p.Cpad + c0) * taps * TF);
 #pragma unroll
             for (int q = 0; q < WI; ++q) {
                 const int idx = q * kThreads + tid;
-                wv[q] = idx < n4 ? wsrc[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+                wv[q] = wsrc[idx < n4 ? idx : 0];
             }
         };
 
@@ -243,12 +258,10 @@ gemm_conv_kernel(GcParams p)
             __syncthreads();      // every wave is done reading the previous chunk
 #pragma unroll
             for (int i = 0; i < XI; ++i)
-                if (xoff[i] != -1) xs[tid + i * kThreads] = xv[i];
+                if (i < p.n_xi) xs[tid + i * kThreads] = (zero >> i) & 1u ? 0.f : xv[i];
 #pragma unroll
-            for (int q = 0; q < WI; ++q) {
-                const int idx = q * kThreads + tid;
-                if (idx < n4) ((float4 *)wsm)[idx] = wv[q];
-            }
+            for (int q = 0; q < WI; ++q)
+                if (q < p.n_wi) ((f32x4 *)wsm)[q * kThreads + tid] = wv[q];
             __syncthreads();
             if (ch + 1 < ce) fetch((ch + 1) * p.Cc);      // in flight while the matrix cores run
 
@@ -354,7 +367,7 @@ static constexpr long kSlots = 512;   // workgroups resident at once: 2 per CU, 
 
 struct GcPlan {
     bool ok, split;      // split: persistent workgroups with split tiles
-    int TF, WM, Cc, Cpad, NC, rows, cols, chan_stride, xs_floats, n_fgrp, n_rowtile, n_coltile;
+    int TF, WM, Cc, Cpad, NC, rows, cols, chan_stride, xs_floats, n_xi, n_wi, n_fgrp, n_rowtile, n_coltile;
     long tiles, n_wg;
     int rounds, rem_units;
     size_t lds_bytes, wt_bytes, partial_bytes;
@@ -375,10 +388,12 @@ static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
     g.cols = (int)cols;
     g.chan_stride = g.rows * g.cols;
     int best = 0, best_pad = 0;
+    // both LDS parts are padded to what 256 threads write in whole rounds
+    auto xs_padded = [&](int cc) { return (size_t)((cc * g.chan_stride + kThreads - 1) / kThreads * kThreads); };
+    auto w_padded = [&](int cc) { return (size_t)((cc * taps * g.TF + 4 * kThreads - 1) / (4 * kThreads) * (4 * kThreads)); };
     for (int cc = 8; cc >= 2; cc -= 2) {
-        const size_t bytes = 4 * ((size_t)((cc * g.chan_stride + 3) & ~3) + (size_t)cc * taps * g.TF);
-        if (bytes > kMaxLds || cc * g.chan_stride > kXI * kThreads || (long)cc * taps * g.TF > 4L * kWI * kThreads)
-            continue;
+        if (xs_padded(cc) > (size_t)kXI * kThreads || w_padded(cc) > (size_t)4 * kWI * kThreads) continue;
+        if (4 * (xs_padded(cc) + w_padded(cc)) > kMaxLds) continue;
         const int pad = (Cin + cc - 1) / cc * cc;
         if (best == 0 || pad < best_pad) { best = cc; best_pad = pad; }
     }
@@ -386,8 +401,10 @@ static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
     g.Cc = best;
     g.Cpad = best_pad;
     g.NC = g.Cpad / g.Cc;
-    g.xs_floats = (g.Cc * g.chan_stride + 3) & ~3;
-    g.lds_bytes = 4 * ((size_t)g.xs_floats + (size_t)g.Cc * taps * g.TF);
+    g.xs_floats = (int)xs_padded(g.Cc);
+    g.n_xi = g.xs_floats / kThreads;
+    g.n_wi = (int)(w_padded(g.Cc) / (4 * kThreads));
+    g.lds_bytes = 4 * ((size_t)g.xs_floats + w_padded(g.Cc));
     g.wt_bytes = (4 * (size_t)g.n_fgrp * g.Cpad * taps * g.TF + 255) & ~(size_t)255;
     // residue classes of the last row block that start beyond the map hold no output: not enumerated
     {
@@ -459,7 +476,7 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     p.kh = kh; p.kw = kw; p.d = d; p.off_h = off ? (kh - 1) * d : 0; p.off_w = off ? (kw - 1) * d : 0;
     p.act = act;
     p.Cpad = g.Cpad; p.Cc = g.Cc; p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.chan_stride = g.chan_stride;
-    p.xs_floats = g.xs_floats;
+    p.xs_floats = g.xs_floats; p.n_xi = g.n_xi; p.n_wi = g.n_wi;
     p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp;
     p.tiles = g.tiles; p.rounds = g.rounds; p.rem_units = g.rem_units; p.n_wg = g.n_wg;
     p.per_xcd = (p.n_wg + kXcds - 1) / kXcds;

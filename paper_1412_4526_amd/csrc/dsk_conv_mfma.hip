@@ -34,6 +34,29 @@ static void allow_lds(F kernel, size_t bytes)
                               (int)bytes);
 }
 
+
+// Buffer loads: a 128-bit descriptor of [base, end) held in scalar registers, one per-lane
+// offset and one scalar offset per load (both in elements), so that a load costs one scalar
+// instruction besides itself.  Offsets at or beyond `end` read zero.
+typedef __amdgpu_buffer_rsrc_t BufRsrc;
+template <typename T>
+__device__ inline BufRsrc buf_rsrc(const T *base, const T *end)
+{
+    const unsigned long bytes = (unsigned long)((const char *)end - (const char *)base);
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, bytes < 0xfffffffcul ? (int)(unsigned)bytes : (int)0xfffffffcu,
+                                             0x00020000);
+}
+__device__ inline float buf_ld(BufRsrc r, const float *, unsigned lane_off, unsigned uniform_off)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)(lane_off * 4u), (int)(uniform_off * 4u), 0));
+}
+__device__ inline float buf_ld(BufRsrc r, const bf16 *, unsigned lane_off, unsigned uniform_off)
+{
+    bf16 v;
+    v.v = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)(lane_off * 2u), (int)(uniform_off * 2u), 0);
+    return bf16_to_f32(v);
+}
+
 // ============================================================================
 // forward / backward-data: out[n][f][u][v] = epi( sum_{c,a,b} wt[c][a][b][f] *
 //                                   in[n][c][u + a*d - off][v + b*d - off] ), in = 0 outside
@@ -157,9 +180,7 @@ gemm_conv_kernel(GcParams p)
     float *xs = smem;                   // [Cc][rows][cols]
     float *wsm = smem + p.xs_floats;    // [Cc][taps][TF]
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lo = lane & 31, hi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     // consecutive physical workgroups go to different XCDs; give each XCD one contiguous
     // run of logical workgroups so that neighbours (shared halo, same input tile) share an L2
@@ -173,12 +194,16 @@ gemm_conv_kernel(GcParams p)
     const int taps = p.kh * p.kw;
     const int n4 = p.Cc * taps * TF / 4;
 
-    // per-lane LDS bases; the k-step offsets are uniform over the wave
-    const float *xlane = xs + hi * p.chan_stride + (2 * wave) * p.cols + lo;
-    const float *wlane = wsm + hi * taps * TF + lo;
-
     bool first_piece = true;
     for (;;) {
+        // Everything derived from the lane index is derived again for every tile: carried
+        // across tiles it would take registers the accumulators and the prefetch need.
+        int tid = threadIdx.x;
+        if (SPLIT) asm volatile("" : "+v"(tid));
+        const int lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+        // per-lane LDS bases; the k-step offsets are uniform over the wave
+        const float *xlane = xs + hi * p.chan_stride + (2 * wave) * p.cols + lo;
+        const float *wlane = wsm + hi * taps * TF + lo;
         long tile = wg;
         int cb = 0, ce = p.NC;
         if (SPLIT) {
@@ -196,21 +221,22 @@ gemm_conv_kernel(GcParams p)
         gc_decode_tile(p, tile, fg, n, u0, v0);
         const TI *in_n = (const TI *)p.in + (long)n * p.Cin * (long)HW;
 
-        // Where this thread's share of the input tile comes from; the same for every chunk.
-        // Element e = tid + 256*i of the tile [Cc][rows][cols] (padded to a multiple of 256)
-        // is read at voff[i] floats beyond the first channel of the chunk; elements outside
+        // Where this thread's share of the input tile comes from; the same for every chunk:
+        // element e = tid + 256*i of the LDS tile [Cc][rows][cols] (padded to a multiple of 256)
+        // is read at voff[i] floats beyond the first channel of the chunk.  Elements outside
         // the map, or in the padding, are read from offset 0 instead, which is always a valid
         // address, and bit i of `zero` says that the tile gets 0 there.
         unsigned voff[XI];
         unsigned zero = 0;
         {
             const int n_x = p.Cc * p.chan_stride;
+            const int row0 = u0 - p.off_h, col0 = v0 - p.off_w;
 #pragma unroll
             for (int i = 0; i < XI; ++i) {
                 const int e = tid + i * kThreads;
                 const int c = e / p.chan_stride, rem = e - c * p.chan_stride;
                 const int r = rem / p.cols, col = rem - r * p.cols;
-                const int irow = u0 + r * p.d - p.off_h, icol = v0 + col - p.off_w;
+                const int irow = row0 + r * p.d, icol = col0 + col;
                 const bool ok = e < n_x && irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win;
                 voff[i] = ok ? (unsigned)c * HW + (unsigned)(irow * p.Win + icol) : 0u;
                 zero |= ok ? 0u : 1u << i;
@@ -583,6 +609,8 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     const unsigned HoWo = (unsigned)(p.Ho * p.Wo), dWo = (unsigned)(p.d * p.Wo);
     const unsigned HW = (unsigned)(p.H * p.W), dW = (unsigned)(p.d * p.W);
     const int nf_valid = p.K - fb * 32, nc_valid = p.C - cb * 32;
+    const bool full_blocks = !PACKB && nf_valid >= 32 && nc_valid >= 32;
+    const TI *dy_end = dy + (long)p.N * p.K * HoWo, *x_end = x + (long)p.N * p.C * HW;
     int st_nr_dy = 0, st_nr_x = 0;             // rows of the staged tile that exist
     bool st_dcol_ok = false, st_col_ok = false; // this lane's column exists
     auto load_tile = [&](long pt) {
@@ -596,6 +624,32 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         // dy: segment i of this wave is filter f_i, rows r_i (lanes 0-31) and r_i+1 (lanes 32-63)
         st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;           // dy rows u0 + r*d that exist (>= 1)
         st_dcol_ok = v0 + lo < p.Wo;
+        st_col_ok = lane < p.xcols && v0 + lane < p.W;
+        const unsigned xlane_off = st_col_ok ? (unsigned)lane : 0u;
+        st_nr_x = (p.H - u0 + p.d - 1) / p.d;             // x rows u0 + r*d that exist
+        st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
+        if (full_blocks && st_nr_dy >= PH && st_nr_x == p.xrows) {
+            // every row, filter and channel of the tile exists (all but the tiles at the bottom
+            // of a map): buffer loads with one per-lane offset for the whole tile and a scalar
+            // offset per load; only the lane's column may fall outside (read column 0 then)
+            const unsigned dlane_off = st_dcol_ok ? (unsigned)hi * dWo + (unsigned)lo : 0u;
+            const BufRsrc rd = buf_rsrc(dyt, dy_end);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int seg = wave * 2 + 8 * i;
+                dr[i] = buf_ld(rd, dyt, dlane_off, (unsigned)(seg >> 2) * HoWo + (unsigned)(seg & 3) * dWo);
+            }
+            const BufRsrc rx = buf_rsrc(xt, x_end);
+#pragma unroll
+            for (int ci = 0; ci < NCI; ++ci) {
+#pragma unroll
+                for (int r = 0; r < XR; ++r) {
+                    const int rr = r < p.xrows ? r : 0;      // rows beyond the tile are not staged
+                    xr[ci][r] = buf_ld(rx, xt, xlane_off, (unsigned)(wave + 4 * ci) * HW + (unsigned)rr * dW);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int seg = wave * 2 + 8 * i;              // even: the lower half's segment
@@ -605,10 +659,6 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             const bool ok = ok_s && st_dcol_ok && r + hi < st_nr_dy;
             dr[i] = ldf(base, (long)(ok ? (unsigned)hi * dWo + (unsigned)lo : 0u));
         }
-        st_col_ok = lane < p.xcols && v0 + lane < p.W;
-        const unsigned xlane_off = st_col_ok ? (unsigned)lane : 0u;
-        st_nr_x = (p.H - u0 + p.d - 1) / p.d;             // x rows u0 + r*d that exist
-        st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
 #pragma unroll
         for (int ci = 0; ci < NCI; ++ci) {
             const int c = wave + 4 * ci;

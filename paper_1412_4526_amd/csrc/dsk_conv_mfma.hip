@@ -220,6 +220,7 @@ gemm_conv_kernel(GcParams p)
         int fg, n, u0, v0;
         gc_decode_tile(p, tile, fg, n, u0, v0);
         const TI *in_n = (const TI *)p.in + (long)n * p.Cin * (long)HW;
+        const TI *in_end = (const TI *)p.in + (long)p.N * p.Cin * (long)HW;
 
         // Where this thread's share of the input tile comes from; the same for every chunk:
         // element e = tid + 256*i of the LDS tile [Cc][rows][cols] (padded to a multiple of 256)
@@ -257,9 +258,10 @@ gemm_conv_kernel(GcParams p)
         // condition makes the compiler wait for it right away to merge the two values.
         auto fetch = [&](int c0) __attribute__((always_inline)) {
             const TI *src = in_n + (long)c0 * (long)HW;
+            const BufRsrc rx = buf_rsrc(src, in_end);
             if (c0 + p.Cc <= p.Cin) {
 #pragma unroll
-                for (int i = 0; i < XI; ++i) xv[i] = ldf(src, voff[i]);
+                for (int i = 0; i < XI; ++i) xv[i] = buf_ld(rx, src, voff[i], 0u);
             } else {
                 // last chunk of a padded channel count: channels beyond Cin meet zero weights;
                 // read the chunk's first channel instead so the address stays inside the tensor
@@ -268,15 +270,15 @@ gemm_conv_kernel(GcParams p)
                     unsigned v = voff[i];
                     const unsigned cl = v / HW;
                     v -= c0 + (int)cl >= p.Cin ? cl * HW : 0u;
-                    xv[i] = ldf(src, v);
+                    xv[i] = buf_ld(rx, src, v, 0u);
                 }
             }
-            const f32x4 *wsrc = (const f32x4 *)(p.wt + ((long)fg * p.Cpad + c0) * taps * TF);
+            // the descriptor ends with the chunk's weights: the padding of the LDS part reads zero
+            const float *wsrc = p.wt + ((long)fg * p.Cpad + c0) * taps * TF;
+            const BufRsrc rw = buf_rsrc(wsrc, wsrc + 4 * n4);
 #pragma unroll
-            for (int q = 0; q < WI; ++q) {
-                const int idx = q * kThreads + tid;
-                wv[q] = wsrc[idx < n4 ? idx : 0];
-            }
+            for (int q = 0; q < WI; ++q)
+                wv[q] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, (q * kThreads + tid) * 16, 0, 0));
         };
 
         fetch(cb * p.Cc);

@@ -84,6 +84,22 @@ def cpu_baseline(cfg, wl, forward_only, budget_s=20.0):
                          "forward only" if forward_only else "forward + backward", t)}
 
 
+def measured_traffic(config, dtype, call, layer):
+    """HBM bytes one launch of (call, layer) moved, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    summary committed under profiles/ for this workload (bench.py cannot collect counters itself);
+    None when no summary covers the workload or the call."""
+    name = "bench_config%d_%s_hbm_traffic.md" % (config, {"f32": "fp32"}.get(dtype, dtype))
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", name)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) == 5 and cells[0] == call and cells[1] == str(layer):
+            return {"fetched_bytes": int(float(cells[2]) * (1 << 20)), "written_bytes": int(float(cells[3]) * (1 << 20)),
+                    "bytes": int(float(cells[4]) * (1 << 20)), "source": "profiles/" + name}
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -176,7 +192,11 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM, "unit": "GB/s",
                 "frac": round(dom["gbs"] / PEAK_HBM, 4)}
-    roof["traffic"] = None
+    tr = measured_traffic(args.config, dtype, dom["call"], dom["layer"])
+    roof["traffic"] = None if tr is None else tr["bytes"]        # HBM bytes per launch (fetched + written)
+    roof["traffic_detail"] = tr
+    roof["algorithmic_bytes"] = int(c["bytes"])
+    roof["algorithmic_flops"] = int(c["flops"])
     roof["kernel"] = "%s layer %d (%s)" % (dom["call"], dom["layer"], dom.get("shape", ""))
     roof["ms"] = dom["ms"]
 

@@ -35,28 +35,6 @@ static void allow_lds(F kernel, size_t bytes)
 }
 
 
-// Buffer loads: a 128-bit descriptor of [base, end) held in scalar registers, one per-lane
-// offset and one scalar offset per load (both in elements), so that a load costs one scalar
-// instruction besides itself.  Offsets at or beyond `end` read zero.
-typedef __amdgpu_buffer_rsrc_t BufRsrc;
-template <typename T>
-__device__ inline BufRsrc buf_rsrc(const T *base, const T *end)
-{
-    const unsigned long bytes = (unsigned long)((const char *)end - (const char *)base);
-    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, bytes < 0xfffffffcul ? (int)(unsigned)bytes : (int)0xfffffffcu,
-                                             0x00020000);
-}
-__device__ inline float buf_ld(BufRsrc r, const float *, unsigned lane_off, unsigned uniform_off)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)(lane_off * 4u), (int)(uniform_off * 4u), 0));
-}
-__device__ inline float buf_ld(BufRsrc r, const bf16 *, unsigned lane_off, unsigned uniform_off)
-{
-    bf16 v;
-    v.v = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)(lane_off * 2u), (int)(uniform_off * 2u), 0);
-    return bf16_to_f32(v);
-}
-
 // ============================================================================
 // forward / backward-data: out[n][f][u][v] = epi( sum_{c,a,b} wt[c][a][b][f] *
 //                                   in[n][c][u + a*d - off][v + b*d - off] ), in = 0 outside

@@ -40,6 +40,44 @@ __device__ inline float ldf(const bf16 *p, long i) { return bf16_to_f32(p[i]); }
 __device__ inline void stf(float *p, long i, float v) { p[i] = v; }
 __device__ inline void stf(bf16 *p, long i, float v) { p[i] = f32_to_bf16(v); }
 
+// Buffer loads: a 128-bit descriptor of [base, end) held in scalar registers, one per-lane
+// offset and one scalar offset per load (both in elements), so that a load costs one scalar
+// instruction besides itself.  Offsets at or beyond `end` read zero.
+typedef __amdgpu_buffer_rsrc_t BufRsrc;
+template <typename T>
+__device__ inline BufRsrc buf_rsrc(const T *base, const T *end)
+{
+    const unsigned long bytes = (unsigned long)((const char *)end - (const char *)base);
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, bytes < 0xfffffffcul ? (int)(unsigned)bytes : (int)0xfffffffcu,
+                                             0x00020000);
+}
+__device__ inline float buf_ld(BufRsrc r, const float *, unsigned lane_off, unsigned uniform_off)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)(lane_off * 4u), (int)(uniform_off * 4u), 0));
+}
+__device__ inline float buf_ld(BufRsrc r, const bf16 *, unsigned lane_off, unsigned uniform_off)
+{
+    bf16 v;
+    v.v = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)(lane_off * 2u), (int)(uniform_off * 2u), 0);
+    return bf16_to_f32(v);
+}
+__device__ inline int buf_ld(BufRsrc r, const uint8_t *, unsigned lane_off, unsigned uniform_off)
+{
+    return (int)(uint8_t)__builtin_amdgcn_raw_buffer_load_b8(r, (int)lane_off, (int)uniform_off, 0);
+}
+__device__ inline void buf_st(BufRsrc r, float *, unsigned lane_off, unsigned uniform_off, float v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)(lane_off * 4u), (int)(uniform_off * 4u), 0);
+}
+__device__ inline void buf_st(BufRsrc r, bf16 *, unsigned lane_off, unsigned uniform_off, float v)
+{
+    __builtin_amdgcn_raw_buffer_store_b16(f32_to_bf16(v).v, r, (int)(lane_off * 2u), (int)(uniform_off * 2u), 0);
+}
+__device__ inline void buf_st(BufRsrc r, uint8_t *, unsigned lane_off, unsigned uniform_off, int v)
+{
+    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)v, r, (int)lane_off, (int)uniform_off, 0);
+}
+
 // value a kernel computing in type T sees for an fp32 weight
 template <typename T> __device__ inline float round_w(float w);
 template <> __device__ inline float round_w<float>(float w) { return w; }

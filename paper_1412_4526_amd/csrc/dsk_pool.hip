@@ -36,39 +36,57 @@ __device__ inline void pool_decode(const PoolShape &s, int rows, int &plane, int
     (void)rows;
 }
 
+// All loads of a thread are issued before anything depends on one of them: rows and columns
+// that do not exist are clamped to ones that do (their values are never used), so no load sits
+// under a condition, and every access is a buffer access with one per-lane offset per tap
+// column and a scalar offset per row.
 template <typename T, int K, int R, bool IS_MAX>
 __global__ void __launch_bounds__(kPoolThreads)
 pool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restrict__ am, PoolShape s)
 {
     int plane, u0, v;
     pool_decode<R>(s, s.Ho, plane, u0, v);
-    if (v >= s.Wo || u0 >= s.Ho) return;
+    if (u0 >= s.Ho) return;
+    const bool col_ok = v < s.Wo;
+    const unsigned vc = col_ok ? (unsigned)v : 0u;      // column 0 exists; v + b*d < W whenever v < Wo
     const T *xp = x + (long)plane * s.H * s.W;
+    const BufRsrc rx = buf_rsrc(xp, xp + (long)s.H * s.W);
+    float xv[R + K - 1][K];
+#pragma unroll
+    for (int t = 0; t < R + K - 1; ++t) {
+        int row = u0 + t * s.d;
+        row = row < s.H ? row : s.H - 1;
+#pragma unroll
+        for (int b = 0; b < K; ++b) xv[t][b] = buf_ld(rx, xp, vc + (unsigned)(b * s.d), (unsigned)(row * s.W));
+    }
+    // the values are pinned here so that the loads are issued together above, not one by one
+    // where the branches below use them
+#pragma unroll
+    for (int t = 0; t < R + K - 1; ++t)
+#pragma unroll
+        for (int b = 0; b < K; ++b) asm volatile("" : "+v"(xv[t][b]));
     float rowv[R + K - 1];
     int rowi[R + K - 1];
 #pragma unroll
     for (int t = 0; t < R + K - 1; ++t) {
-        const int row = u0 + t * s.d;
-        rowv[t] = 0.f;
-        rowi[t] = 0;
-        if (row < s.H) {
-            const T *rp = xp + (long)row * s.W + v;
-            float best = ldf(rp, 0);
-            int bi = 0;
+        float best = xv[t][0];
+        int bi = 0;
+#pragma unroll
+        for (int b = 1; b < K; ++b) {
             if (IS_MAX) {
-#pragma unroll
-                for (int b = 1; b < K; ++b) {
-                    const float tv = ldf(rp, (long)b * s.d);
-                    if (tv > best) { best = tv; bi = b; }
-                }
+                if (xv[t][b] > best) { best = xv[t][b]; bi = b; }
             } else {
-#pragma unroll
-                for (int b = 1; b < K; ++b) best += ldf(rp, (long)b * s.d);
+                best += xv[t][b];
             }
-            rowv[t] = best;
-            rowi[t] = bi;
         }
+        rowv[t] = best;
+        rowi[t] = bi;
     }
+    if (!col_ok) return;
+    T *yp = y + (long)plane * s.Ho * s.Wo;
+    const BufRsrc ry = buf_rsrc(yp, yp + (long)s.Ho * s.Wo);
+    uint8_t *ap = IS_MAX && am ? am + (long)plane * s.Ho * s.Wo : nullptr;
+    const BufRsrc ra = buf_rsrc(ap, ap + (ap ? (long)s.Ho * s.Wo : 0));
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int u = u0 + r * s.d;
@@ -84,9 +102,8 @@ pool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restrict_
             for (int a = 1; a < K; ++a) best += rowv[r + a];
             best *= 1.0f / (float)(K * K);
         }
-        const long o = ((long)plane * s.Ho + u) * s.Wo + v;
-        stf(y, o, best);
-        if (IS_MAX && am) am[o] = (uint8_t)bi;
+        buf_st(ry, yp, (unsigned)v, (unsigned)(u * s.Wo), best);
+        if (ap) buf_st(ra, ap, (unsigned)v, (unsigned)(u * s.Wo), bi);
     }
 }
 
@@ -97,45 +114,70 @@ pool_bwd_kernel(const T *__restrict__ dy, const uint8_t *__restrict__ am, T *__r
 {
     int plane, p0, q;
     pool_decode<R>(s, s.H, plane, p0, q);
-    if (q >= s.W || p0 >= s.H) return;
+    if (p0 >= s.H) return;
+    const bool col_ok = q < s.W;
     const T *dyp = dy + (long)plane * s.Ho * s.Wo;
     const uint8_t *amp = IS_MAX ? am + (long)plane * s.Ho * s.Wo : nullptr;
+    const BufRsrc rg = buf_rsrc(dyp, dyp + (long)s.Ho * s.Wo);
+    const BufRsrc ra = buf_rsrc(amp, amp + (IS_MAX ? (long)s.Ho * s.Wo : 0));
+    // dy column q - b*d, clamped into the map; `cok` bit b says that it exists
+    unsigned vcol[K];
+    unsigned cok = 0;
+#pragma unroll
+    for (int b = 0; b < K; ++b) {
+        const int v = q - b * s.d;
+        const bool ok = col_ok && v >= 0 && v < s.Wo;
+        vcol[b] = ok ? (unsigned)v : 0u;
+        cok |= ok ? 1u << b : 0u;
+    }
+    // t indexes dy rows p0 + (t-(K-1))*d, t = 0 .. R+K-2; it feeds dx rows r = t-(K-1)+a
+    float g[R + K - 1][K];
+    int idx[R + K - 1][K];
+#pragma unroll
+    for (int t = 0; t < R + K - 1; ++t) {
+        int u = p0 + (t - (K - 1)) * s.d;
+        u = u < 0 ? 0 : (u >= s.Ho ? s.Ho - 1 : u);
+#pragma unroll
+        for (int b = 0; b < K; ++b) {
+            g[t][b] = buf_ld(rg, dyp, vcol[b], (unsigned)(u * s.Wo));
+            idx[t][b] = IS_MAX ? buf_ld(ra, amp, vcol[b], (unsigned)(u * s.Wo)) : 0;
+        }
+    }
+    // the values are pinned here so that the loads are issued together above, not one by one
+    // where the branches below use them
+#pragma unroll
+    for (int t = 0; t < R + K - 1; ++t)
+#pragma unroll
+        for (int b = 0; b < K; ++b) {
+            asm volatile("" : "+v"(g[t][b]));
+            if (IS_MAX) asm volatile("" : "+v"(idx[t][b]));
+        }
     float acc[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) acc[r] = 0.f;
-    // t indexes dy rows p0 + (t-(K-1))*d, t = 0 .. R+K-2; it feeds dx rows r = t-(K-1)+a
 #pragma unroll
     for (int t = 0; t < R + K - 1; ++t) {
         const int u = p0 + (t - (K - 1)) * s.d;
-        if (u < 0 || u >= s.Ho) continue;
+        const bool row_ok = u >= 0 && u < s.Ho;       // uniform
 #pragma unroll
         for (int b = 0; b < K; ++b) {
-            const int v = q - b * s.d;
-            if (v < 0 || v >= s.Wo) continue;
-            const long o = (long)u * s.Wo + v;
-            const float g = ldf(dyp, o);
-            if (IS_MAX) {
-                const int idx = amp[o];
+            const float gv = row_ok && ((cok >> b) & 1u) ? g[t][b] : 0.f;
 #pragma unroll
-                for (int a = 0; a < K; ++a) {
-                    const int r = t - (K - 1) + a;
-                    if (r >= 0 && r < R && idx == a * K + b) acc[r] += g;
-                }
-            } else {
-#pragma unroll
-                for (int a = 0; a < K; ++a) {
-                    const int r = t - (K - 1) + a;
-                    if (r >= 0 && r < R) acc[r] += g;
-                }
+            for (int a = 0; a < K; ++a) {
+                const int r = t - (K - 1) + a;
+                if (r >= 0 && r < R) acc[r] += !IS_MAX || idx[t][b] == a * K + b ? gv : 0.f;
             }
         }
     }
+    if (!col_ok) return;
+    T *dxp = dx + (long)plane * s.H * s.W;
+    const BufRsrc rd = buf_rsrc(dxp, dxp + (long)s.H * s.W);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int p = p0 + r * s.d;
         if (p >= s.H) break;
         const float v = IS_MAX ? acc[r] : acc[r] * (1.0f / (float)(K * K));
-        stf(dx, ((long)plane * s.H + p) * s.W + q, v);
+        buf_st(rd, dxp, (unsigned)q, (unsigned)(p * s.W), v);
     }
 }
 

@@ -933,6 +933,7 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     } while (0)
     if (b.packb && b.xrows <= 8) DSK_BW_LAUNCH(2, 8, false, true, true);
     else if (b.packb) DSK_BW_LAUNCH(2, 10, false, true, true);
+    else if (b.rowsplit && b.tpw == 1 && b.xrows <= 4) DSK_BW_LAUNCH(1, 4, true, true, false);
     else if (b.rowsplit && b.tpw == 1) DSK_BW_LAUNCH(1, 8, true, true, false);
     else if (b.rowsplit) DSK_BW_LAUNCH(9, 8, true, false, false);
     else if (b.tpw == 1) DSK_BW_LAUNCH(1, 8, false, true, false);

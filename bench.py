@@ -22,6 +22,9 @@ PEAK_FP32_MFMA = 157.3      # TFLOP/s, MI355X dense fp32 matrix
 PEAK_BF16_MFMA = 2500.0     # TFLOP/s, MI355X dense bf16 matrix
 PEAK_HBM = 8000.0           # GB/s
 kDenseIntensity = 100.0     # flop per byte from which a conv layer counts as a dense contraction
+# The paper's own measurement of configs[5] (Plain CNN_1, 3x388x388 padded, Tesla K40, fp32; Table 1):
+# forward 35.39 ms, backward 91.26 ms for 256 x 256 labelled pixels.  Another machine: context, not a target.
+PAPER_PLAIN_CNN1_MS = {"fwd": 35.39, "fwd+bwd": 35.39 + 91.26}
 
 
 def layer_costs(net, elem):
@@ -110,6 +113,11 @@ def main():
     ap.add_argument("--dtype", default=None)
     ap.add_argument("--forward-only", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--image-size", type=int, default=0,
+                    help="override the labelled image to S x S pixels (the paper's image-size sweep)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of the step captured in a HIP graph (per-call rates then come from an "
+                         "eager pass before the timed region)")
     ap.add_argument("--algo", type=int, default=0)
     ap.add_argument("--layers", action="store_true", help="print the per-call table to stderr")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -125,6 +133,9 @@ def main():
     from workloads import CONFIGS, make_workload
 
     cfg = CONFIGS[args.config]
+    if args.image_size > 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, H=args.image_size, W=args.image_size)
     dtype = args.dtype or cfg.dtype
     elem = 4 if dtype == "f32" else 2
     wl = make_workload(cfg.net, cfg.N, cfg.H, cfg.W, cfg.mask_frac, cfg.seed, positive_frac=cfg.positive_frac)
@@ -151,13 +162,32 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    net.timeline = []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    timeline, net.timeline = net.timeline, None
+    if args.graph:
+        # per-call events cannot be recorded into a graph: collect them from eager steps first
+        net.timeline = []
+        for _ in range(max(3, args.warmup)):
+            step()
+        torch.cuda.synchronize()
+        timeline, net.timeline = net.timeline, None
+        if args.forward_only:
+            net.capture(image)
+        else:
+            net.capture(image, labels, mask)
+        net.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            net.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    else:
+        net.timeline = []
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        timeline, net.timeline = net.timeline, None
 
     pixels = cfg.N * cfg.H * cfg.W
     # per-call device time from the events recorded inside the timed region
@@ -208,16 +238,21 @@ def main():
                       if "tflops" in r and r["intensity"] >= kDenseIntensity), default=None)
     worst_pool = min((r["gbs"] / PEAK_HBM for r in rows if "pool" in r["call"]), default=None)
 
+    vs_baseline = None
+    if args.config == 5 and dtype == "f32" and args.image_size == 0:
+        paper_ms = PAPER_PLAIN_CNN1_MS["fwd" if args.forward_only else "fwd+bwd"]
+        vs_baseline = round((pixels * args.steps / dt) / (pixels / (paper_ms * 1e-3)), 2)
     out = {
         "metric": "labelled pixels/s whole-image %s" % ("fwd" if args.forward_only else "fwd+bwd"),
         "value": pixels * args.steps / dt, "unit": "labelled pixels/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": vs_baseline, "dtype": dtype,
         "data": "synthetic",
         "config": {"workload": "configs[%d]: %s patch %d, %dx%dx%dx%d image, mask %.0f%%"
                                % (args.config, cfg.net.name, cfg.net.patch, cfg.N, cfg.net.C0, cfg.H, cfg.W,
                                   cfg.mask_frac * 100),
-                   "conv_algo": "auto" if args.algo == 0 else "direct"},
+                   "conv_algo": "auto" if args.algo == 0 else "direct",
+                   "launch": "hip graph replay" if args.graph else "eager"},
         "roofline": roof,
         "worst_dense_conv_frac_of_mfma_peak": None if worst_conv is None else round(worst_conv, 4),
         "worst_pool_frac_of_hbm_peak": None if worst_pool is None else round(worst_pool, 4),

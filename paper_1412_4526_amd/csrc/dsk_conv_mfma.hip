@@ -368,12 +368,14 @@ gc_fixup_kernel(GcParams p)
 }
 
 static constexpr int kXI = 16;   // input-tile elements per thread per chunk, at most
+static constexpr int kXIBig = 24;   // the same for tiles with a large halo (second set of kernels, never split)
 static constexpr int kWI = 8;    // weight float4s per thread per chunk, at most
 static constexpr long kSlots = 512;   // workgroups resident at once: 2 per CU, 256 CUs
 
 struct GcPlan {
     bool ok, split;      // split: persistent workgroups with split tiles
     int TF, WM, Cc, Cpad, NC, rows, cols, chan_stride, xs_floats, n_xi, n_wi, n_fgrp, n_rowtile, n_coltile;
+    int XI;              // kXI or kXIBig: which set of kernels
     long tiles, n_wg;
     int rounds, rem_units;
     size_t lds_bytes, wt_bytes, partial_bytes;
@@ -397,11 +399,15 @@ static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
     // both LDS parts are padded to what 256 threads write in whole rounds
     auto xs_padded = [&](int cc) { return (size_t)((cc * g.chan_stride + kThreads - 1) / kThreads * kThreads); };
     auto w_padded = [&](int cc) { return (size_t)((cc * taps * g.TF + 4 * kThreads - 1) / (4 * kThreads) * (4 * kThreads)); };
-    for (int cc = 8; cc >= 2; cc -= 2) {
-        if (xs_padded(cc) > (size_t)kXI * kThreads || w_padded(cc) > (size_t)4 * kWI * kThreads) continue;
-        if (4 * (xs_padded(cc) + w_padded(cc)) > kMaxLds) continue;
-        const int pad = (Cin + cc - 1) / cc * cc;
-        if (best == 0 || pad < best_pad) { best = cc; best_pad = pad; }
+    for (int xi : {kXI, kXIBig}) {
+        for (int cc = 8; cc >= 2; cc -= 2) {
+            if (xs_padded(cc) > (size_t)xi * kThreads || w_padded(cc) > (size_t)4 * kWI * kThreads) continue;
+            if (4 * (xs_padded(cc) + w_padded(cc)) > kMaxLds) continue;
+            const int pad = (Cin + cc - 1) / cc * cc;
+            if (best == 0 || pad < best_pad) { best = cc; best_pad = pad; }
+        }
+        g.XI = xi;
+        if (best != 0) break;
     }
     if (best == 0) return g;
     g.Cc = best;
@@ -425,7 +431,7 @@ static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
     // a few per cent, S persistent workgroups take T/S whole tiles each and share the channel
     // chunks of the remaining T mod S tiles evenly.
     // (NC <= 4096 keeps the 32-bit chunk arithmetic of the kernels exact)
-    g.split = g.tiles > kSlots && g.tiles < 12 * kSlots && g.tiles % kSlots != 0 && g.NC <= 4096;
+    g.split = g.tiles > kSlots && g.tiles < 12 * kSlots && g.tiles % kSlots != 0 && g.NC <= 4096 && g.XI == kXI;
     if (g.split) {
         g.n_wg = kSlots;
         g.rounds = (int)(g.tiles / g.n_wg);
@@ -445,7 +451,11 @@ template <typename TI, typename TO>
 static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
 {
     const unsigned grid = (unsigned)(p.per_xcd * kXcds);
-    if (g.WM == 2 && g.split)
+    if (g.XI == kXIBig && g.WM == 2)
+        gemm_conv_kernel<TI, TO, 2, kXIBig, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    else if (g.XI == kXIBig)
+        gemm_conv_kernel<TI, TO, 1, kXIBig, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    else if (g.WM == 2 && g.split)
         gemm_conv_kernel<TI, TO, 2, kXI, kWI, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.WM == 2)
         gemm_conv_kernel<TI, TO, 2, kXI, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
@@ -508,6 +518,7 @@ struct BwParams {
     const void *x, *dy;
     float *part;         // [split][taps][Kp][Cp]
     int N, C, H, W, K, Ho, Wo, kh, kw, d;
+    int col_shift;       // x is read this many columns to the right (one tap column of a wide kernel at a time)
     int Kp, Cp;          // padded to 32
     int xrows, xcols, xstride;   // x tile: PH+kh-1 by PW+(kw-1)*d, channel stride odd
     int n_rowtile, n_coltile;    // pixel tiles per image
@@ -600,11 +611,11 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         const int u0 = (rt / p.d) * p.d * PH + (rt % p.d);
         const int v0 = ct * PW;
         const TI *dyt = dy + (((long)n * p.K + fb * 32) * p.Ho + u0) * p.Wo + v0;
-        const TI *xt = x + (((long)n * p.C + cb * 32) * p.H + u0) * p.W + v0;
+        const TI *xt = x + (((long)n * p.C + cb * 32) * p.H + u0) * p.W + v0 + p.col_shift;
         // dy: segment i of this wave is filter f_i, rows r_i (lanes 0-31) and r_i+1 (lanes 32-63)
         st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;           // dy rows u0 + r*d that exist (>= 1)
         st_dcol_ok = v0 + lo < p.Wo;
-        st_col_ok = lane < p.xcols && v0 + lane < p.W;
+        st_col_ok = lane < p.xcols && v0 + lane + p.col_shift < p.W;
         const unsigned xlane_off = st_col_ok ? (unsigned)lane : 0u;
         st_nr_x = (p.H - u0 + p.d - 1) / p.d;             // x rows u0 + r*d that exist
         st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
@@ -737,7 +748,8 @@ __device__ inline float bw_reduce_sum(const float *__restrict__ src, long stride
 }
 
 __global__ void __launch_bounds__(kThreads)
-bw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int taps, int Kp, int Cp, int S)
+bw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int taps, int Kp, int Cp, int S,
+                 int taps_dw, int tap_stride, int tap_first)
 {
     __shared__ float red[kThreads];
     const long total = (long)K * C * taps;
@@ -748,7 +760,8 @@ bw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, 
     const int t = (int)(idx / ((long)C * K));
     const long o = ((long)t * Kp + f) * Cp + c;
     const float v = bw_reduce_sum(part + (valid ? o : 0), (long)Kp * Cp * taps, S, valid, red);
-    if (valid && threadIdx.x < kRedOut) dw[((long)f * C + c) * taps + t] = v;
+    // tap t of the blocks is tap tap_first + t*tap_stride of dw's taps_dw
+    if (valid && threadIdx.x < kRedOut) dw[((long)f * C + c) * taps_dw + tap_first + t * tap_stride] = v;
 }
 
 // The same for blocks whose 32 columns are (channel, tap column) pairs and whose tiles are tap rows.
@@ -809,18 +822,20 @@ struct BwPlan {
     bool ok;
     int Kp, Cp, xrows, xcols, xstride, n_rowtile, n_coltile, S, n_fblk, n_cblk, tpw;
     bool rowsplit, packb;
+    int col_passes;      // > 1: one launch per tap column b (a kh x 1 kernel on x shifted by b*d columns)
     int n_part;          // partial blocks the reduce kernel adds up
     long n_ptile;
     size_t lds_bytes, part_bytes;
 };
 
-static BwPlan bw_plan(const ConvShape &s)
+static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb)
 {
     BwPlan b{};
+    b.col_passes = 1;
     const long taps = (long)s.kh * s.kw;
     if (taps > 52) return b;
     // few input channels: pack (channel, tap column) pairs into the 32 B-operand columns
-    b.packb = s.C <= 4 && s.C * s.kw <= 32 && s.kh >= 2 && s.kh <= 7;
+    b.packb = allow_packb && s.C <= 4 && s.C * s.kw <= 32 && s.kh >= 2 && s.kh <= 7;
     b.rowsplit = !b.packb && (taps == 1 || taps == 9);
     b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
     b.Kp = (s.K + 31) / 32 * 32;
@@ -829,8 +844,9 @@ static BwPlan bw_plan(const ConvShape &s)
     b.n_cblk = b.Cp / 32;
     b.xrows = PH + s.kh - 1;
     const long xcols = (long)PW + (long)(s.kw - 1) * s.d;
-    // one wave-wide load per x-tile row; XR = 8 rows except for the 13-taps-per-wave variant (10)
-    if (xcols > 64 || s.kh > (b.tpw == 13 || b.packb ? 7 : 5)) return b;
+    // one wave-wide load per x-tile row; kernels staging up to 10 rows exist for 2 and 13
+    // accumulator tiles per wave and for the packed form, the others stage up to 8
+    if (xcols > 64 || s.kh > (b.tpw == 13 || b.tpw == 2 || b.packb ? 7 : 5)) return b;
     if ((long)s.H * s.W >= (1L << 24)) return b;         // 32-channel block offsets stay below 2^29 elements
     b.xcols = (int)xcols;
     b.xstride = (b.xrows * b.xcols) | 1;
@@ -853,6 +869,20 @@ static BwPlan bw_plan(const ConvShape &s)
     b.n_part = b.rowsplit ? 4 * b.S : b.S;
     b.part_bytes = 4 * ((size_t)b.n_part * b.Kp * b.Cp * (b.packb ? s.kh : taps) + (size_t)s.K * kBiasSplit);
     b.ok = true;
+    return b;
+}
+
+// A kernel whose tap columns are too far apart for one x tile (more than 64 columns wide) is
+// taken one tap column at a time: dw[:, :, :, b] is the weight gradient of a kh x 1 kernel on x
+// shifted by b*d columns, with the same dy.
+static BwPlan bw_plan(const ConvShape &s)
+{
+    BwPlan b = bw_plan_one(s, true);
+    if (b.ok || s.kw == 1) return b;
+    ConvShape c = s;
+    c.kw = 1;                      // Wo stays that of the whole kernel
+    b = bw_plan_one(c, false);
+    b.col_passes = s.kw;
     return b;
 }
 
@@ -910,11 +940,12 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
 {
     const BwPlan b = bw_plan(s);
     if (!b.ok) return DSK_ESHAPE;
-    const int taps = s.kh * s.kw;
+    const int kw_pass = b.col_passes > 1 ? 1 : s.kw;      // tap columns one launch covers
+    const int taps = s.kh * kw_pass;
     BwParams p{};
     p.x = x; p.dy = dy; p.part = (float *)ws;
     p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.Ho = s.Ho; p.Wo = s.Wo;
-    p.kh = s.kh; p.kw = s.kw; p.d = s.d;
+    p.kh = s.kh; p.kw = kw_pass; p.d = s.d;
     p.Kp = b.Kp; p.Cp = b.Cp; p.xrows = b.xrows; p.xcols = b.xcols; p.xstride = b.xstride;
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
     p.n_fblk = b.n_fblk; p.n_cblk = b.n_cblk;
@@ -931,26 +962,32 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
                 <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                  \
         }                                                                                              \
     } while (0)
-    if (b.packb && b.xrows <= 8) DSK_BW_LAUNCH(2, 8, false, true, true);
-    else if (b.packb) DSK_BW_LAUNCH(2, 10, false, true, true);
-    else if (b.rowsplit && b.tpw == 1 && b.xrows <= 4) DSK_BW_LAUNCH(1, 4, true, true, false);
-    else if (b.rowsplit && b.tpw == 1) DSK_BW_LAUNCH(1, 8, true, true, false);
-    else if (b.rowsplit) DSK_BW_LAUNCH(9, 8, true, false, false);
-    else if (b.tpw == 1) DSK_BW_LAUNCH(1, 8, false, true, false);
-    else if (b.tpw == 2) DSK_BW_LAUNCH(2, 8, false, true, false);
-    else if (b.tpw == 4) DSK_BW_LAUNCH(4, 8, false, true, false);
-    else if (b.tpw == 7) DSK_BW_LAUNCH(7, 8, false, false, false);
-    else DSK_BW_LAUNCH(13, 10, false, false, false);
+    int rc = DSK_OK;
+    for (int pass = 0; pass < b.col_passes; ++pass) {
+        p.col_shift = pass * s.d;      // the partial blocks are reused: the passes run one after the other
+        if (b.packb && b.xrows <= 8) DSK_BW_LAUNCH(2, 8, false, true, true);
+        else if (b.packb) DSK_BW_LAUNCH(2, 10, false, true, true);
+        else if (b.rowsplit && b.tpw == 1 && b.xrows <= 4) DSK_BW_LAUNCH(1, 4, true, true, false);
+        else if (b.rowsplit && b.tpw == 1) DSK_BW_LAUNCH(1, 8, true, true, false);
+        else if (b.rowsplit) DSK_BW_LAUNCH(9, 8, true, false, false);
+        else if (b.tpw == 1) DSK_BW_LAUNCH(1, 8, false, true, false);
+        else if (b.tpw == 2 && b.xrows <= 8) DSK_BW_LAUNCH(2, 8, false, true, false);
+        else if (b.tpw == 2) DSK_BW_LAUNCH(2, 10, false, true, false);
+        else if (b.tpw == 4) DSK_BW_LAUNCH(4, 8, false, true, false);
+        else if (b.tpw == 7) DSK_BW_LAUNCH(7, 8, false, false, false);
+        else DSK_BW_LAUNCH(13, 10, false, false, false);
+        rc = check_launch();
+        if (rc != DSK_OK) return rc;
+        const long total = (long)s.K * s.C * taps;
+        if (b.packb)
+            bw_reduce_packb_kernel<<<dim3((unsigned)((total + kRedOut - 1) / kRedOut)), dim3(kThreads), 0, st>>>(
+                (const float *)ws, dw, s.K, s.C, s.kh, s.kw, b.Kp, b.n_part);
+        else
+            bw_reduce_kernel<<<dim3((unsigned)((total + kRedOut - 1) / kRedOut)), dim3(kThreads), 0, st>>>(
+                (const float *)ws, dw, s.K, s.C, taps, b.Kp, b.Cp, b.n_part, s.kh * s.kw,
+                b.col_passes > 1 ? s.kw : 1, pass);
+    }
 #undef DSK_BW_LAUNCH
-    int rc = check_launch();
-    if (rc != DSK_OK) return rc;
-    const long total = (long)s.K * s.C * taps;
-    if (b.packb)
-        bw_reduce_packb_kernel<<<dim3((unsigned)((total + kRedOut - 1) / kRedOut)), dim3(kThreads), 0, st>>>(
-            (const float *)ws, dw, s.K, s.C, s.kh, s.kw, b.Kp, b.n_part);
-    else
-        bw_reduce_kernel<<<dim3((unsigned)((total + kRedOut - 1) / kRedOut)), dim3(kThreads), 0, st>>>(
-            (const float *)ws, dw, s.K, s.C, taps, b.Kp, b.Cp, b.n_part);
     rc = check_launch();
     if (rc != DSK_OK || !db) return rc;
     float *bpart = (float *)ws + (size_t)b.n_part * b.Kp * b.Cp * (b.packb ? s.kh : taps);

@@ -48,39 +48,47 @@ pool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restrict_
     pool_decode<R>(s, s.Ho, plane, u0, v);
     if (u0 >= s.Ho) return;
     const bool col_ok = v < s.Wo;
-    const unsigned vc = col_ok ? (unsigned)v : 0u;      // column 0 exists; v + b*d < W whenever v < Wo
+    unsigned vc = col_ok ? (unsigned)v : 0u;      // column 0 exists; v + b*d < W whenever v < Wo
     const T *xp = x + (long)plane * s.H * s.W;
     const BufRsrc rx = buf_rsrc(xp, xp + (long)s.H * s.W);
-    float xv[R + K - 1][K];
+    // rows per batch of loads: all of them for small windows; one row (K loads) for large ones,
+    // which would otherwise need (R+K-1)*K registers
+    constexpr int NT = R + K - 1, TB = K <= 3 ? NT : 1;
+    float rowv[NT];
+    int rowi[NT];
 #pragma unroll
-    for (int t = 0; t < R + K - 1; ++t) {
-        int row = u0 + t * s.d;
-        row = row < s.H ? row : s.H - 1;
+    for (int t0 = 0; t0 < NT; t0 += TB) {
+        float xv[TB][K];
 #pragma unroll
-        for (int b = 0; b < K; ++b) xv[t][b] = buf_ld(rx, xp, vc + (unsigned)(b * s.d), (unsigned)(row * s.W));
-    }
-    // the values are pinned here so that the loads are issued together above, not one by one
-    // where the branches below use them
+        for (int t = 0; t < TB; ++t) {
+            int row = u0 + (t0 + t) * s.d;
+            row = row < s.H ? row : s.H - 1;
 #pragma unroll
-    for (int t = 0; t < R + K - 1; ++t)
-#pragma unroll
-        for (int b = 0; b < K; ++b) asm volatile("" : "+v"(xv[t][b]));
-    float rowv[R + K - 1];
-    int rowi[R + K - 1];
-#pragma unroll
-    for (int t = 0; t < R + K - 1; ++t) {
-        float best = xv[t][0];
-        int bi = 0;
-#pragma unroll
-        for (int b = 1; b < K; ++b) {
-            if (IS_MAX) {
-                if (xv[t][b] > best) { best = xv[t][b]; bi = b; }
-            } else {
-                best += xv[t][b];
-            }
+            for (int b = 0; b < K; ++b) xv[t][b] = buf_ld(rx, xp, vc + (unsigned)(b * s.d), (unsigned)(row * s.W));
         }
-        rowv[t] = best;
-        rowi[t] = bi;
+        // the values are pinned here so that the loads of a batch are issued together above,
+        // not one by one where the branches below use them
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+#pragma unroll
+            for (int b = 0; b < K; ++b) asm volatile("" : "+v"(xv[t][b]));
+        // ... and the next batch is not hoisted above this one (its offset "changes" here)
+        if (TB < NT) asm volatile("" : "+v"(vc));
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+            float best = xv[t][0];
+            int bi = 0;
+#pragma unroll
+            for (int b = 1; b < K; ++b) {
+                if (IS_MAX) {
+                    if (xv[t][b] > best) { best = xv[t][b]; bi = b; }
+                } else {
+                    best += xv[t][b];
+                }
+            }
+            rowv[t0 + t] = best;
+            rowi[t0 + t] = bi;
+        }
     }
     if (!col_ok) return;
     T *yp = y + (long)plane * s.Ho * s.Wo;
@@ -130,42 +138,52 @@ pool_bwd_kernel(const T *__restrict__ dy, const uint8_t *__restrict__ am, T *__r
         vcol[b] = ok ? (unsigned)v : 0u;
         cok |= ok ? 1u << b : 0u;
     }
-    // t indexes dy rows p0 + (t-(K-1))*d, t = 0 .. R+K-2; it feeds dx rows r = t-(K-1)+a
-    float g[R + K - 1][K];
-    int idx[R + K - 1][K];
-#pragma unroll
-    for (int t = 0; t < R + K - 1; ++t) {
-        int u = p0 + (t - (K - 1)) * s.d;
-        u = u < 0 ? 0 : (u >= s.Ho ? s.Ho - 1 : u);
-#pragma unroll
-        for (int b = 0; b < K; ++b) {
-            g[t][b] = buf_ld(rg, dyp, vcol[b], (unsigned)(u * s.Wo));
-            idx[t][b] = IS_MAX ? buf_ld(ra, amp, vcol[b], (unsigned)(u * s.Wo)) : 0;
-        }
-    }
-    // the values are pinned here so that the loads are issued together above, not one by one
-    // where the branches below use them
-#pragma unroll
-    for (int t = 0; t < R + K - 1; ++t)
-#pragma unroll
-        for (int b = 0; b < K; ++b) {
-            asm volatile("" : "+v"(g[t][b]));
-            if (IS_MAX) asm volatile("" : "+v"(idx[t][b]));
-        }
+    // t indexes dy rows p0 + (t-(K-1))*d, t = 0 .. R+K-2; it feeds dx rows r = t-(K-1)+a.
+    // Rows per batch of loads: all of them for small windows, one row (2K loads) for large ones.
+    constexpr int NT = R + K - 1, TB = K <= 3 ? NT : 1;
     float acc[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) acc[r] = 0.f;
 #pragma unroll
-    for (int t = 0; t < R + K - 1; ++t) {
-        const int u = p0 + (t - (K - 1)) * s.d;
-        const bool row_ok = u >= 0 && u < s.Ho;       // uniform
+    for (int t0 = 0; t0 < NT; t0 += TB) {
+        float g[TB][K];
+        int idx[TB][K];
 #pragma unroll
-        for (int b = 0; b < K; ++b) {
-            const float gv = row_ok && ((cok >> b) & 1u) ? g[t][b] : 0.f;
+        for (int t = 0; t < TB; ++t) {
+            int u = p0 + (t0 + t - (K - 1)) * s.d;
+            u = u < 0 ? 0 : (u >= s.Ho ? s.Ho - 1 : u);
 #pragma unroll
-            for (int a = 0; a < K; ++a) {
-                const int r = t - (K - 1) + a;
-                if (r >= 0 && r < R) acc[r] += !IS_MAX || idx[t][b] == a * K + b ? gv : 0.f;
+            for (int b = 0; b < K; ++b) {
+                g[t][b] = buf_ld(rg, dyp, vcol[b], (unsigned)(u * s.Wo));
+                idx[t][b] = IS_MAX ? buf_ld(ra, amp, vcol[b], (unsigned)(u * s.Wo)) : 0;
+            }
+        }
+        // the values are pinned here so that the loads of a batch are issued together above,
+        // not one by one where the branches below use them
+#pragma unroll
+        for (int t = 0; t < TB; ++t)
+#pragma unroll
+            for (int b = 0; b < K; ++b) {
+                asm volatile("" : "+v"(g[t][b]));
+                if (IS_MAX) asm volatile("" : "+v"(idx[t][b]));
+            }
+        // ... and the next batch is not hoisted above this one (its offsets "change" here):
+        // one batch in flight per wave keeps the register count, and with it the occupancy, sane
+        if (TB < NT)
+#pragma unroll
+            for (int b = 0; b < K; ++b) asm volatile("" : "+v"(vcol[b]));
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+            const int u = p0 + (t0 + t - (K - 1)) * s.d;
+            const bool row_ok = u >= 0 && u < s.Ho;       // uniform
+#pragma unroll
+            for (int b = 0; b < K; ++b) {
+                const float gv = row_ok && ((cok >> b) & 1u) ? g[t][b] : 0.f;
+#pragma unroll
+                for (int a = 0; a < K; ++a) {
+                    const int r = t0 + t - (K - 1) + a;
+                    if (r >= 0 && r < R) acc[r] += !IS_MAX || idx[t][b] == a * K + b ? gv : 0.f;
+                }
             }
         }
     }
@@ -266,6 +284,12 @@ static int pool_fwd_dispatch(const void *x, void *y, uint8_t *am, int N, int C, 
     else if (k == 3 && tiled_blocks < 0x7fffffffL)
         pool_fwd_kernel<T, 3, R, IS_MAX><<<dim3((unsigned)tiled_blocks), dim3(kPoolThreads), 0, st>>>(
             (const T *)x, (T *)y, am, s);
+    else if (k == 4 && tiled_blocks < 0x7fffffffL)
+        pool_fwd_kernel<T, 4, R, IS_MAX><<<dim3((unsigned)tiled_blocks), dim3(kPoolThreads), 0, st>>>(
+            (const T *)x, (T *)y, am, s);
+    else if (k == 8 && tiled_blocks < 0x7fffffffL)
+        pool_fwd_kernel<T, 8, R, IS_MAX><<<dim3((unsigned)tiled_blocks), dim3(kPoolThreads), 0, st>>>(
+            (const T *)x, (T *)y, am, s);
     else {
         const long total = (long)s.planes * s.Ho * s.Wo;
         pool_fwd_generic_kernel<T, IS_MAX>
@@ -279,14 +303,22 @@ template <typename T, bool IS_MAX>
 static int pool_bwd_dispatch(const void *dy, const uint8_t *am, void *dx, int N, int C, int H, int W, int k,
                              int d, hipStream_t st)
 {
-    constexpr int R = 8;
-    PoolShape s = make_shape(N, C, H, W, k, d, R, H, W);
+    // rows per thread: 8 for small windows; 2 for 4x4 and 8x8 ones, whose k*k tests per row pair
+    // otherwise unroll into a kernel that needs every register of the SIMD
+    constexpr int R = 8, RL = 2;
+    PoolShape s = make_shape(N, C, H, W, k, d, k <= 3 ? R : RL, H, W);
     const long tiled_blocks = (long)s.planes * s.row_groups * s.col_blocks;
     if (k == 2 && tiled_blocks < 0x7fffffffL)
         pool_bwd_kernel<T, 2, R, IS_MAX><<<dim3((unsigned)tiled_blocks), dim3(kPoolThreads), 0, st>>>(
             (const T *)dy, am, (T *)dx, s);
     else if (k == 3 && tiled_blocks < 0x7fffffffL)
         pool_bwd_kernel<T, 3, R, IS_MAX><<<dim3((unsigned)tiled_blocks), dim3(kPoolThreads), 0, st>>>(
+            (const T *)dy, am, (T *)dx, s);
+    else if (k == 4 && tiled_blocks < 0x7fffffffL)
+        pool_bwd_kernel<T, 4, RL, IS_MAX><<<dim3((unsigned)tiled_blocks), dim3(kPoolThreads), 0, st>>>(
+            (const T *)dy, am, (T *)dx, s);
+    else if (k == 8 && tiled_blocks < 0x7fffffffL)
+        pool_bwd_kernel<T, 8, RL, IS_MAX><<<dim3((unsigned)tiled_blocks), dim3(kPoolThreads), 0, st>>>(
             (const T *)dy, am, (T *)dx, s);
     else {
         const long total = (long)s.planes * s.H * s.W;

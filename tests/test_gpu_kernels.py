@@ -35,6 +35,9 @@ CONV_CASES = [
     (2, 64, 37, 70, 33, 1, 8, 0),      # 1x1 with K = 33
     (1, 6, 64, 50, 48, 7, 1, 1),       # 7x7
     (1, 130, 20, 90, 2, 3, 3, 0),      # K = 2, C > 128
+    (1, 10, 130, 150, 12, 7, 16, 0),   # 7x7 taps 16 apart: 96-column halo, weight gradient one tap column at a time
+    (1, 8, 120, 140, 40, 7, 16, 1),    # the same with more than 32 filters
+    (1, 4, 90, 100, 9, 6, 12, 2),      # 6x6 taps 12 apart, four input channels
 ]
 
 
@@ -198,6 +201,8 @@ POOL_CASES = [
     (1, 8, 51, 51, 2, 1), (2, 5, 46, 300, 2, 2), (1, 3, 70, 530, 2, 4), (1, 4, 90, 61, 2, 8),
     (1, 6, 64, 77, 3, 2), (2, 3, 40, 280, 3, 4), (1, 2, 60, 44, 4, 3), (1, 3, 33, 20, 8, 1),
     (1, 2, 9, 9, 2, 8),   # d larger than the output
+    (1, 3, 100, 300, 8, 1), (1, 2, 90, 70, 8, 2), (2, 2, 50, 280, 4, 2),   # 8x8 and 4x4 windows over several tiles
+    (1, 2, 40, 50, 5, 2), (1, 2, 30, 30, 6, 1),                            # window sizes without a tiled kernel
 ]
 
 

@@ -63,7 +63,7 @@ def test_plan_reproduces_padded_sizes_of_paper_models():
 
 def test_plan_of_the_five_benchmark_networks():
     expect_d = {0: [1, 1, 2, 2, 4], 1: [1, 1, 2, 2, 4, 4, 8, 8], 3: [1, 1, 2, 2, 4, 4, 8, 8, 16, 16],
-                4: [1, 2, 4, 4, 8, 8]}      # Algorithm 1; the strided net has receptive field 67
+                4: [1, 2, 4, 4, 8, 8], 5: [1, 1, 8, 8, 16], 6: [1, 1, 4, 4, 8], 7: [1, 1, 2, 2, 4]}      # Algorithm 1; the strided net has receptive field 67
     for i, c in enumerate(CONFIGS):
         plan, rf, lo, hi = dsk.dsk_plan(c.net.layers, c.net.C0, c.H, c.W, c.net.patch)
         assert rf == c.net.patch and lo == c.net.patch // 2 and lo + hi == c.net.patch - 1

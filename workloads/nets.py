@@ -76,7 +76,7 @@ class Net:
 
 
 # ---------------------------------------------------------------------------
-# The five benchmark networks.  ReLU follows every conv / fc except the last;
+# The five benchmark networks, and the paper's own Plain CNN_1 (Table 1).  ReLU follows every conv / fc except the last;
 # pools whose type a configuration leaves open are max pools.
 # ---------------------------------------------------------------------------
 _R = ACT_RELU
@@ -108,6 +108,23 @@ _STRIDED = Net("strided67", 3, 67, (
     conv(21, 3, 1)))            # fc 192*3*3 -> 21
 
 
+# Plain CNN_1 of the paper's experiments (Table 1; Sec. 5.1): 133 x 133 patches, 32 outputs.  The table lists
+# tanh after each pool; it is applied before the pool here, in the convolution's epilogue: tanh is monotonic,
+# so the pooled values are the same, and in whole-image form both maps have the same size.
+_T = ACT_TANH
+def _plain(pool1):
+    n = 6 + pool1 * (3 + 2 * 7 - 1) - 1       # 133, 69, 37 for pool1 = 8, 4, 2
+    return Net("plain%d" % n, 3, n, (
+        conv(50, 6, 1, _T), maxpool(pool1, pool1),
+        conv(50, 3, 1, _T), maxpool(2, 2),
+        conv(32, 7, 1)))
+
+
+_PLAIN = _plain(8)
+# Table 4's variants: pool1 4x4 / 4 and 2x2 / 2 make the network take 69 x 69 and 37 x 37 patches
+_PLAIN69, _PLAIN37 = _plain(4), _plain(2)
+
+
 @dataclass(frozen=True)
 class Config:
     net: Net
@@ -126,6 +143,10 @@ CONFIGS = (
     Config(_SCENE, 4, 1024, 1024, 0.01),
     Config(_WIDE, 1, 1024, 1024, 0.02, dtype="bf16", positive_frac=0.3),
     Config(_STRIDED, 1, 2048, 2048, 0.01),
+    # the paper's own workload: 256 x 256 labelled pixels (3 x 388 x 388 padded), errors of 1024 chosen pixels
+    Config(_PLAIN, 1, 256, 256, 1024.0 / 65536.0),
+    Config(_PLAIN69, 1, 256, 256, 1024.0 / 65536.0),
+    Config(_PLAIN37, 1, 256, 256, 1024.0 / 65536.0),
 )
 
 

@@ -115,6 +115,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--image-size", type=int, default=0,
                     help="override the labelled image to S x S pixels (the paper's image-size sweep)")
+    ap.add_argument("--mask-frac", type=float, default=-1.0,
+                    help="override the fraction of labelled pixels whose errors are kept (Sec. 4.3: the cost "
+                         "of the backward pass does not depend on it)")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of the step captured in a HIP graph (per-call rates then come from an "
                          "eager pass before the timed region)")
@@ -133,9 +136,12 @@ def main():
     from workloads import CONFIGS, make_workload
 
     cfg = CONFIGS[args.config]
-    if args.image_size > 0:
+    if args.image_size > 0 or args.mask_frac >= 0:
         import dataclasses
-        cfg = dataclasses.replace(cfg, H=args.image_size, W=args.image_size)
+        if args.image_size > 0:
+            cfg = dataclasses.replace(cfg, H=args.image_size, W=args.image_size)
+        if args.mask_frac >= 0:
+            cfg = dataclasses.replace(cfg, mask_frac=args.mask_frac)
     dtype = args.dtype or cfg.dtype
     elem = 4 if dtype == "f32" else 2
     wl = make_workload(cfg.net, cfg.N, cfg.H, cfg.W, cfg.mask_frac, cfg.seed, positive_frac=cfg.positive_frac)

@@ -505,6 +505,166 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
 }
 
 // ============================================================================
+// 1x1 kernels (the last fully connected layers): out[n][f][q] = epi( sum_c wt[c][f] * in[n][c][q] )
+// over the flat pixel index q.  Few filters or few channels make these layers HBM-bound, so
+// nothing is staged: a wave owns 128 consecutive pixels and reads both MFMA operands straight
+// from global memory -- B (lane = pixel, 128 B per half wave and load) and A (lane = filter,
+// from the small re-laid-out weight matrix, which stays in the caches) -- eight channels ahead
+// of the matrix cores.  No LDS, no barriers; the waves are independent.
+// ============================================================================
+static constexpr int kPwCh = 8;     // channels per batch of loads (4 MFMA k-steps)
+
+struct PwParams {
+    const void *in;
+    void *out;
+    const float *wt;     // [n_fgrp][Cpad][TF], zero padded (Cpad a multiple of kPwCh)
+    const float *bias;   // may be null
+    int N, Cin, Fout, act, Cpad, n_fgrp;
+    long HW;             // pixels per plane, < 2^28
+    long n_wave;         // N * ceil(HW / 128)
+};
+
+template <typename TI, typename TO, int WM>
+__global__ void __launch_bounds__(kThreads, 2)
+pw_conv_kernel(PwParams p)
+{
+    constexpr int TF = WM * 32, KS = kPwCh / 2;
+    const int lane = threadIdx.x & 63, lo = lane & 31, hi = lane >> 5;
+    const long wv = (long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wv >= p.n_wave) return;
+    const long per_img = (p.HW + 127) / 128;
+    const int n = (int)(wv / per_img);
+    const unsigned q0 = (unsigned)(wv - n * per_img) * 128u;
+    const unsigned HW = (unsigned)p.HW;
+    const TI *in_n = (const TI *)p.in + (long)n * p.Cin * p.HW;
+    const BufRsrc rin = buf_rsrc(in_n, in_n + (long)p.Cin * p.HW);
+    // this lane's pixel of each of the four 32-pixel blocks; pixels beyond the plane read pixel 0
+    unsigned qoff[4];
+#pragma unroll
+    for (int wn = 0; wn < 4; ++wn) {
+        const unsigned q = q0 + 32u * wn + lo;
+        qoff[wn] = q < HW ? q : 0u;
+    }
+    const int NC = p.Cpad / kPwCh;
+    for (int fg = 0; fg < p.n_fgrp; ++fg) {
+        const float *wg = p.wt + (long)fg * p.Cpad * TF;
+        const BufRsrc rw = buf_rsrc(wg, wg + (long)p.Cpad * TF);
+        f32x16 acc[WM][4];
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+            for (int wn = 0; wn < 4; ++wn)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
+        float a_cur[KS][WM], b_cur[KS][4], a_nxt[KS][WM], b_nxt[KS][4];
+        // channels at or beyond Cin meet zero weights; they are read from the last channel
+        auto fetch = [&](int c0, float (&a)[KS][WM], float (&b)[KS][4]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const int c = c0 + 2 * s;                      // lanes 32..63 take c + 1
+                const unsigned ce = (unsigned)(c < p.Cin ? c : p.Cin - 1), co = (unsigned)(c + 1 < p.Cin ? c + 1 : p.Cin - 1);
+#pragma unroll
+                for (int wm = 0; wm < WM; ++wm) a[s][wm] = buf_ld(rw, wg, (unsigned)(hi * TF + wm * 32 + lo), (unsigned)c * TF);
+#pragma unroll
+                for (int wn = 0; wn < 4; ++wn) b[s][wn] = buf_ld(rin, in_n, qoff[wn] + (hi ? co : ce) * HW, 0u);
+            }
+        };
+        fetch(0, a_cur, b_cur);
+        for (int ch = 0; ch < NC; ++ch) {
+            // the next batch (the last one is fetched twice: a load under a condition would be waited for at once)
+            fetch((ch + 1 < NC ? ch + 1 : ch) * kPwCh, a_nxt, b_nxt);
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+#pragma unroll
+                for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                    for (int wn = 0; wn < 4; ++wn)
+                        acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[s][wm], b_cur[s][wn], acc[wm][wn], 0, 0, 0);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+#pragma unroll
+                for (int wm = 0; wm < WM; ++wm) a_cur[s][wm] = a_nxt[s][wm];
+#pragma unroll
+                for (int wn = 0; wn < 4; ++wn) b_cur[s][wn] = b_nxt[s][wn];
+            }
+        }
+        // bias, non-linearity, store (register i of a lane: filter 8*(i/4) + i%4 + 4*hi of its block)
+        TO *out_n = (TO *)p.out + ((long)n * p.Fout + (long)fg * TF) * p.HW;
+        const int f_left = p.Fout - fg * TF;
+#pragma unroll
+        for (int wn = 0; wn < 4; ++wn) {
+            const unsigned q = q0 + 32u * wn + lo;
+            if (q >= HW) continue;
+            TO *o = out_n + q + (hi ? 4 * p.HW : 0);
+#pragma unroll
+            for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int fl = wm * 32 + 8 * (i / 4) + (i % 4);
+                    if (fl + 4 * hi < f_left) {
+                        float v = acc[wm][wn][i];
+                        if (p.bias) {
+                            const float b0 = p.bias[fg * TF + fl];
+                            const float b1 = fl + 4 < f_left ? p.bias[fg * TF + fl + 4] : 0.f;
+                            v += hi ? b1 : b0;
+                        }
+                        stf(o, (long)fl * p.HW, act_apply(p.act, v));
+                    }
+                }
+        }
+    }
+}
+
+struct PwPlan {
+    bool ok;
+    int WM, TF, n_fgrp, Cpad;
+    size_t wt_bytes;
+};
+
+static PwPlan pw_plan(int Cin, int Fout, long HW, int kh, int kw)
+{
+    PwPlan g{};
+    if (kh != 1 || kw != 1 || HW >= (1L << 28) || (long)Cin * HW >= (1L << 30)) return g;
+    g.WM = Fout > 32 ? 2 : 1;
+    g.TF = g.WM * 32;
+    g.n_fgrp = (Fout + g.TF - 1) / g.TF;
+    g.Cpad = (Cin + kPwCh - 1) / kPwCh * kPwCh;
+    g.wt_bytes = (4 * (size_t)g.n_fgrp * g.Cpad * g.TF + 255) & ~(size_t)255;
+    g.ok = true;
+    return g;
+}
+
+template <typename TI, typename TO>
+static void pw_launch(const PwParams &p, int WM, hipStream_t st)
+{
+    const unsigned grid = (unsigned)((p.n_wave + 3) / 4);
+    if (WM == 2) pw_conv_kernel<TI, TO, 2><<<dim3(grid), dim3(kThreads), 0, st>>>(p);
+    else pw_conv_kernel<TI, TO, 1><<<dim3(grid), dim3(kThreads), 0, st>>>(p);
+}
+
+// K, C: dimensions of w; flip = 1 for backward-data (GEMM channels = filters of w)
+static int pw_run(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Fout, long HW,
+                  int act, int flip, int K, int C, dsk_dtype tin, dsk_dtype tout, void *ws, hipStream_t st)
+{
+    const PwPlan g = pw_plan(Cin, Fout, HW, 1, 1);
+    if (!g.ok) return DSK_ESHAPE;
+    float *wt = (float *)ws;
+    const long total = (long)g.n_fgrp * g.Cpad * g.TF;
+    gc_weight_prep_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+        w, wt, K, C, 1, g.Cpad, g.TF, g.n_fgrp, flip, tin == DSK_BF16 ? 1 : 0);
+    PwParams p{};
+    p.in = in; p.out = out; p.wt = wt; p.bias = bias;
+    p.N = N; p.Cin = Cin; p.Fout = Fout; p.act = act; p.Cpad = g.Cpad; p.n_fgrp = g.n_fgrp;
+    p.HW = HW; p.n_wave = (long)N * ((HW + 127) / 128);
+    if ((p.n_wave + 3) / 4 > 0x7fffffffL) return DSK_ESHAPE;
+    if (tin == DSK_F32 && tout == DSK_F32) pw_launch<float, float>(p, g.WM, st);
+    else if (tin == DSK_F32 && tout == DSK_BF16) pw_launch<float, bf16>(p, g.WM, st);
+    else if (tin == DSK_BF16 && tout == DSK_BF16) pw_launch<bf16, bf16>(p, g.WM, st);
+    else pw_launch<bf16, float>(p, g.WM, st);
+    return check_launch();
+}
+
+// ============================================================================
 // backward-weight: dw[f][c][a][b] = sum_{n,u,v} dy[n][f][u][v] * x[n][c][u+a*d][v+b*d]
 // One workgroup owns a 32-filter x 32-channel block of dw for ALL taps and walks over
 // a share of the pixel tiles (split-K); the four waves divide the taps.  Partial
@@ -893,10 +1053,14 @@ size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
 {
     (void)in;
     if (which == DSK_WS_CONV_FWD) {
+        const PwPlan pw = pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw);
+        if (pw.ok) return pw.wt_bytes;
         const GcPlan g = gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d);
         return g.ok ? g.wt_bytes + g.partial_bytes : 0;
     }
     if (which == DSK_WS_CONV_BWD_DATA) {
+        const PwPlan pw = pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw);
+        if (pw.ok) return pw.wt_bytes;
         const GcPlan g = gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d);
         return g.ok ? g.wt_bytes + g.partial_bytes : 0;
     }
@@ -915,8 +1079,10 @@ bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype 
     if ((long)s.H * s.W >= (1L << 28) || (long)s.C * s.H * s.W >= (1L << 30) ||
         (long)s.K * s.Ho * s.Wo >= (1L << 30))
         return false;
-    if (which == DSK_WS_CONV_FWD) return gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
-    if (which == DSK_WS_CONV_BWD_DATA) return gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
+    if (which == DSK_WS_CONV_FWD)
+        return pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw).ok || gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
+    if (which == DSK_WS_CONV_BWD_DATA)
+        return pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw).ok || gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
     if (which == DSK_WS_CONV_BWD_WEIGHT) return bw_plan(s).ok;
     return false;
 }
@@ -924,6 +1090,8 @@ bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype 
 int launch_conv_fwd_mfma(const void *x, const float *w, const float *b, void *y, const ConvShape &s,
                          dsk_dtype in, dsk_dtype out, int act, void *ws, hipStream_t st)
 {
+    if (pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw).ok)
+        return pw_run(x, y, w, b, s.N, s.C, s.K, (long)s.H * s.W, act, 0, s.K, s.C, in, out, ws, st);
     return gc_run(x, y, w, b, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d, 0, act, 0,
                   s.K, s.C, in, out, ws, st);
 }
@@ -931,6 +1099,8 @@ int launch_conv_fwd_mfma(const void *x, const float *w, const float *b, void *y,
 int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const ConvShape &s,
                               dsk_dtype in, dsk_dtype out, void *ws, hipStream_t st)
 {
+    if (pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw).ok)
+        return pw_run(dy, dx, w, nullptr, s.N, s.K, s.C, (long)s.H * s.W, DSK_ACT_NONE, 1, s.K, s.C, in, out, ws, st);
     return gc_run(dy, dx, w, nullptr, s.N, s.K, s.Ho, s.Wo, s.C, s.H, s.W, s.kh, s.kw, s.d, 1, DSK_ACT_NONE, 1,
                   s.K, s.C, in, out, ws, st);
 }

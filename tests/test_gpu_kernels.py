@@ -38,6 +38,8 @@ CONV_CASES = [
     (1, 10, 130, 150, 12, 7, 16, 0),   # 7x7 taps 16 apart: 96-column halo, weight gradient one tap column at a time
     (1, 8, 120, 140, 40, 7, 16, 1),    # the same with more than 32 filters
     (1, 4, 90, 100, 9, 6, 12, 2),      # 6x6 taps 12 apart, four input channels
+    (1, 20, 50, 61, 150, 1, 1, 1),     # 1x1 with three filter groups; pixel count not a multiple of 128
+    (3, 70, 9, 13, 3, 1, 2, 0),        # 1x1, planes smaller than one wave's 128 pixels
 ]
 
 

@@ -201,7 +201,9 @@ int dsk_masked_softmax_xent(const float *scores, const int32_t *labels, const ui
 /* ------------------------------------------------------------------------- */
 
 /* 0 = automatic (matrix-core kernels where they apply), 1 = force the plain
- * one-thread-per-output kernels.  Process-wide; returns the previous value. */
+ * one-thread-per-output kernels, 2 = automatic but bf16 maps are multiplied on the
+ * fp32 matrix path (converted while they are staged) instead of the bf16 one.
+ * Process-wide; returns the previous value. */
 int dsk_set_conv_algo(int algo);
 
 #ifdef __cplusplus

@@ -59,7 +59,7 @@ const char *dsk_status_string(int status)
 
 int dsk_set_conv_algo(int algo)
 {
-    if (algo < 0 || algo > 1) return g_conv_algo.load();
+    if (algo < 0 || algo > 2) return g_conv_algo.load();
     return g_conv_algo.exchange(algo);
 }
 
@@ -140,7 +140,9 @@ int dsk_conv_fwd(const void *x, const float *w, const float *b, void *y,
     const size_t need = conv_ws_bytes(DSK_WS_CONV_FWD, s, in);
     if (need > 0 && (ws == nullptr || !aligned16(ws) || ws_bytes < need)) return DSK_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    if (g_conv_algo.load() == 0 && conv_mfma_supported(DSK_WS_CONV_FWD, s, in, out))
+    if (g_conv_algo.load() == 0 && in == DSK_BF16 && conv_bf16_supported(DSK_WS_CONV_FWD, s))
+        return launch_conv_fwd_bf16(x, w, b, y, s, out, act, ws, st);
+    if (g_conv_algo.load() != 1 && conv_mfma_supported(DSK_WS_CONV_FWD, s, in, out))
         return launch_conv_fwd_mfma(x, w, b, y, s, in, out, act, ws, st);
     return launch_conv_fwd_direct(x, w, b, y, s, in, out, act, st);
 }
@@ -157,7 +159,9 @@ int dsk_conv_bwd_data(const void *dy, const float *w, void *dx,
     const size_t need = conv_ws_bytes(DSK_WS_CONV_BWD_DATA, s, in);
     if (need > 0 && (ws == nullptr || !aligned16(ws) || ws_bytes < need)) return DSK_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    if (g_conv_algo.load() == 0 && conv_mfma_supported(DSK_WS_CONV_BWD_DATA, s, in, out))
+    if (g_conv_algo.load() == 0 && in == DSK_BF16 && conv_bf16_supported(DSK_WS_CONV_BWD_DATA, s))
+        return launch_conv_bwd_data_bf16(dy, w, dx, s, out, ws, st);
+    if (g_conv_algo.load() != 1 && conv_mfma_supported(DSK_WS_CONV_BWD_DATA, s, in, out))
         return launch_conv_bwd_data_mfma(dy, w, dx, s, in, out, ws, st);
     return launch_conv_bwd_data_direct(dy, w, dx, s, in, out, st);
 }
@@ -174,7 +178,7 @@ int dsk_conv_bwd_weight(const void *x, const void *dy, float *dw, float *db,
     const size_t need = conv_ws_bytes(DSK_WS_CONV_BWD_WEIGHT, s, in);
     if (need > 0 && (ws == nullptr || !aligned16(ws) || ws_bytes < need)) return DSK_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    if (g_conv_algo.load() == 0 && conv_mfma_supported(DSK_WS_CONV_BWD_WEIGHT, s, in, DSK_F32))
+    if (g_conv_algo.load() != 1 && conv_mfma_supported(DSK_WS_CONV_BWD_WEIGHT, s, in, DSK_F32))
         return launch_conv_bwd_weight_mfma(x, dy, dw, db, s, in, ws, st);
     return launch_conv_bwd_weight_direct(x, dy, dw, db, s, in, st);
 }

@@ -1051,7 +1051,11 @@ static BwPlan bw_plan(const ConvShape &s)
 // ============================================================================
 size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
 {
-    (void)in;
+    // bf16 maps may take either set of kernels: room for both
+    if (in == DSK_BF16 && which != DSK_WS_CONV_BWD_WEIGHT && conv_bf16_supported(which, s)) {
+        const size_t a = conv_bf16_ws_bytes(which, s), b = conv_ws_bytes(which, s, DSK_F32);
+        return a > b ? a : b;
+    }
     if (which == DSK_WS_CONV_FWD) {
         const PwPlan pw = pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw);
         if (pw.ok) return pw.wt_bytes;

@@ -112,6 +112,14 @@ int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const Co
 int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
                                 dsk_dtype in, void *ws, hipStream_t st);
 
+// ---- bf16 matrix-core kernels for forward / backward-data on bf16 maps (dsk_conv_bf16.hip) ----
+size_t conv_bf16_ws_bytes(int which, const ConvShape &s);
+bool conv_bf16_supported(int which, const ConvShape &s);
+int launch_conv_fwd_bf16(const void *x, const float *w, const float *b, void *y, const ConvShape &s,
+                         dsk_dtype out, int act, void *ws, hipStream_t st);
+int launch_conv_bwd_data_bf16(const void *dy, const float *w, void *dx, const ConvShape &s, dsk_dtype out, void *ws,
+                              hipStream_t st);
+
 // ---- pooling, padding, activation, loss (dsk_pool.hip, dsk_misc.hip, dsk_loss.hip) ----
 int launch_maxpool_fwd(const void *x, void *y, uint8_t *am, int N, int C, int H, int W, int k, int d,
                        dsk_dtype t, hipStream_t st);

@@ -161,16 +161,26 @@ def test_conv_workspace_is_enough_and_respected(case):
         assert bool((buf[need16:] == 0xA5).all()), "write beyond the workspace (call %d)" % which
 
 
-def test_conv_bf16_variant():
+BF16_CASES = [
+    (1, 32, 50, 77, 48, 3, 2, 1),      # whole 16-channel chunks both ways
+    (1, 40, 60, 92, 70, 4, 8, 1),      # ragged last chunk both ways, 64-filter tiles
+    (2, 24, 40, 100, 64, 5, 2, 0),     # 25 taps
+    (1, 16, 30, 45, 10, 2, 4, 2),      # backward-data has 10 < 16 channels: fp32 matrix path
+]
+
+
+@pytest.mark.parametrize("case", BF16_CASES, ids=lambda c: "N%dC%dH%dW%dK%dk%dd%da%d" % c)
+def test_conv_bf16_variant(case):
     """bf16 activations/weights, fp32 accumulate: within 2e-2 of the fp32 oracle on the
-    unrounded inputs, and within fp32 tolerance of the oracle fed the rounded inputs."""
-    N, C, H, W, K, k, d, act = 1, 32, 50, 77, 48, 3, 2, 1
+    unrounded inputs, and within fp32 tolerance of the oracle fed the rounded inputs.
+    Algo 0: bf16 matrix cores where they apply; 1: plain kernels; 2: fp32 matrix path."""
+    N, C, H, W, K, k, d, act = case
     rng = np.random.default_rng(7)
     x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
     w = (rng.standard_normal((K, C, k, k)) * np.sqrt(2.0 / (C * k * k))).astype(np.float32)
     b = (rng.standard_normal(K) * 0.2).astype(np.float32)
-    for algo in (0, 1):
-        _say("conv bf16 algo", algo)
+    for algo in (0, 1, 2):
+        _say("conv bf16", case, "algo", algo)
         prev = dsk.dsk_set_conv_algo(algo)
         try:
             xb = _t(x, torch.bfloat16)

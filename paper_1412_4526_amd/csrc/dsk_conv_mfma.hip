@@ -20,6 +20,7 @@ namespace dsk {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 static constexpr int kThreads = 256;
 static constexpr int kXcds = 8;
@@ -673,6 +674,7 @@ static int pw_run(const void *in, void *out, const float *w, const float *bias, 
 static constexpr int PH = 4;    // pixel-tile rows (one residue class mod d)
 static constexpr int PW = 32;   // pixel-tile columns
 static constexpr int DY_STRIDE = PH * PW + 1;   // odd: lanes = filters read conflict-free
+static constexpr int DYB = PH * PW + 8;         // bf16 tiles: 272 bytes per filter
 
 struct BwParams {
     const void *x, *dy;
@@ -698,13 +700,22 @@ struct BwParams {
 //   operand are (channel, tap column b) pairs instead of 32 channels, so the accumulator
 //   tiles are indexed by the tap ROW only and a 5x5x3 kernel costs 5 MFMA columns of which
 //   15/32 are useful instead of 25 of which 3/32 are.
-template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false>
+// BFM (bf16 maps whose tap columns are a multiple of 8 pixels apart): the tiles are kept in LDS
+//   as bf16 in the same [filter or channel][row][column] order, and one v_mfma_f32_32x32x16_bf16
+//   contracts 16 consecutive pixels of a row, of which a lane supplies 8 with one 16-byte read
+//   (hence the alignment condition).  The matrix cores then have 1/16 of the work and the kernel
+//   runs at the speed of its staging.
+template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false, bool BFM = false>
 __global__ void __launch_bounds__(kThreads, (TPW <= 9 ? 2 : 1))
 conv_bwd_weight_mfma_kernel(BwParams p)
 {
     extern __shared__ __align__(16) float smem[];
     float *dys = smem;                       // [32 filters][DY_STRIDE]
     float *xs = smem + 32 * DY_STRIDE;       // [32 channels][xstride]
+    // the same two tiles as bf16: row pitch of the dy tile DYB, of an x channel p.xstride (both
+    // multiples of 8 elements and an odd number of 16-byte units, which spreads lanes over the banks)
+    unsigned short *dyb = (unsigned short *)smem;
+    unsigned short *xb16 = (unsigned short *)smem + 32 * DYB;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -831,7 +842,9 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         for (int i = 0; i < 16; ++i) {
             const int seg = wave * 2 + hi + 8 * i;
             const bool ok = st_dcol_ok && (seg >> 2) < nf_valid && (seg & 3) < st_nr_dy;
-            dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = ok ? dr[i] : 0.f;
+            const float v = ok ? dr[i] : 0.f;
+            if (BFM) dyb[(seg >> 2) * DYB + (seg & 3) * PW + lo] = f32_to_bf16(v).v;      // exact: v came from bf16
+            else dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
         }
         if (lane < p.xcols) {
 #pragma unroll
@@ -840,12 +853,32 @@ conv_bwd_weight_mfma_kernel(BwParams p)
                 for (int r = 0; r < XR; ++r)
                     if (r < p.xrows) {
                         const bool ok = st_col_ok && wave + 4 * ci < nc_valid && r < st_nr_x;
-                        xs[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = ok ? xr[ci][r] : 0.f;
+                        const float v = ok ? xr[ci][r] : 0.f;
+                        if (BFM) xb16[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = f32_to_bf16(v).v;
+                        else xs[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = v;
                     }
         }
         __syncthreads();
         if (PREFETCH && pt + p.S < p.n_ptile) load_tile(pt + p.S);      // in flight while the matrix cores run
         pt += p.S;
+        if (BFM) {
+            // ---- bf16 matrix cores: k index = 16 consecutive pixels of a row, 8 per lane
+            const unsigned short *ab = dyb + lo * DYB + 8 * hi;
+            const unsigned short *bb = xb16 + blane + 8 * hi;
+            for (int r = ROWSPLIT ? wave : 0; r < (ROWSPLIT ? wave + 1 : PH); ++r) {
+#pragma unroll
+                for (int q = 0; q < PW / 16; ++q) {
+                    const bf16x8 A = *(const bf16x8 *)(ab + r * PW + 16 * q);
+                    bf16x8 B[TPW];
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t) B[t] = *(const bf16x8 *)(bb + boff[t] + r * p.xcols + 16 * q);
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t)
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B[t], acc[t], 0, 0, 0);
+                }
+            }
+            continue;
+        }
         // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
         const float *ab = dys + lo * DY_STRIDE + hi;
         const float *bb = xs + blane + hi;
@@ -982,13 +1015,14 @@ struct BwPlan {
     bool ok;
     int Kp, Cp, xrows, xcols, xstride, n_rowtile, n_coltile, S, n_fblk, n_cblk, tpw;
     bool rowsplit, packb;
+    bool bfm;            // bf16 tiles in LDS, bf16 matrix cores
     int col_passes;      // > 1: one launch per tap column b (a kh x 1 kernel on x shifted by b*d columns)
     int n_part;          // partial blocks the reduce kernel adds up
     long n_ptile;
     size_t lds_bytes, part_bytes;
 };
 
-static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb)
+static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
 {
     BwPlan b{};
     b.col_passes = 1;
@@ -996,8 +1030,12 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb)
     if (taps > 52) return b;
     // few input channels: pack (channel, tap column) pairs into the 32 B-operand columns
     b.packb = allow_packb && s.C <= 4 && s.C * s.kw <= 32 && s.kh >= 2 && s.kh <= 7;
-    b.rowsplit = !b.packb && (taps == 1 || taps == 9);
-    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
+    // bf16 matrix cores: every 16-byte LDS read of 8 pixels must be aligned, i.e. the tap columns a
+    // multiple of 8 pixels apart; kernels exist for 3 and 4 accumulator tiles per wave
+    b.bfm = in == DSK_BF16 && !b.packb && s.kw > 1 && s.d % 8 == 0 && taps > 8 && taps <= 16 && s.kh <= 5;
+    b.rowsplit = !b.packb && !b.bfm && (taps == 1 || taps == 9);
+    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.bfm ? (taps <= 12 ? 3 : 4)
+          : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
     b.Kp = (s.K + 31) / 32 * 32;
     b.Cp = (s.C + 31) / 32 * 32;
     b.n_fblk = b.Kp / 32;
@@ -1011,6 +1049,10 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb)
     b.xcols = (int)xcols;
     b.xstride = (b.xrows * b.xcols) | 1;
     b.lds_bytes = 4 * ((size_t)32 * DY_STRIDE + (size_t)32 * b.xstride);
+    if (b.bfm) {
+        b.xstride = 8 * (((b.xrows * b.xcols + 7) / 8) | 1);
+        b.lds_bytes = 2 * ((size_t)32 * DYB + (size_t)32 * b.xstride);
+    }
     if (b.lds_bytes > kMaxLdsBw) return b;
     // residue classes of the last row block that start beyond the map hold no pixel: skip them
     {
@@ -1035,13 +1077,13 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb)
 // A kernel whose tap columns are too far apart for one x tile (more than 64 columns wide) is
 // taken one tap column at a time: dw[:, :, :, b] is the weight gradient of a kh x 1 kernel on x
 // shifted by b*d columns, with the same dy.
-static BwPlan bw_plan(const ConvShape &s)
+static BwPlan bw_plan(const ConvShape &s, dsk_dtype in)
 {
-    BwPlan b = bw_plan_one(s, true);
+    BwPlan b = bw_plan_one(s, true, in);
     if (b.ok || s.kw == 1) return b;
     ConvShape c = s;
     c.kw = 1;                      // Wo stays that of the whole kernel
-    b = bw_plan_one(c, false);
+    b = bw_plan_one(c, false, in);
     b.col_passes = s.kw;
     return b;
 }
@@ -1069,7 +1111,7 @@ size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
         return g.ok ? g.wt_bytes + g.partial_bytes : 0;
     }
     if (which == DSK_WS_CONV_BWD_WEIGHT) {
-        const BwPlan b = bw_plan(s);
+        const BwPlan b = bw_plan(s, in);
         return b.ok ? b.part_bytes : 0;
     }
     return 0;
@@ -1087,7 +1129,7 @@ bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype 
         return pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw).ok || gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
     if (which == DSK_WS_CONV_BWD_DATA)
         return pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw).ok || gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
-    if (which == DSK_WS_CONV_BWD_WEIGHT) return bw_plan(s).ok;
+    if (which == DSK_WS_CONV_BWD_WEIGHT) return bw_plan(s, in).ok;
     return false;
 }
 
@@ -1112,7 +1154,7 @@ int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const Co
 int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
                                 dsk_dtype in, void *ws, hipStream_t st)
 {
-    const BwPlan b = bw_plan(s);
+    const BwPlan b = bw_plan(s, in);
     if (!b.ok) return DSK_ESHAPE;
     const int kw_pass = b.col_passes > 1 ? 1 : s.kw;      // tap columns one launch covers
     const int taps = s.kh * kw_pass;
@@ -1139,7 +1181,13 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     int rc = DSK_OK;
     for (int pass = 0; pass < b.col_passes; ++pass) {
         p.col_shift = pass * s.d;      // the partial blocks are reused: the passes run one after the other
-        if (b.packb && b.xrows <= 8) DSK_BW_LAUNCH(2, 8, false, true, true);
+        if (b.bfm && b.tpw == 3)
+            conv_bwd_weight_mfma_kernel<bf16, 3, 8, false, true, false, true>
+                <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+        else if (b.bfm)
+            conv_bwd_weight_mfma_kernel<bf16, 4, 8, false, true, false, true>
+                <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+        else if (b.packb && b.xrows <= 8) DSK_BW_LAUNCH(2, 8, false, true, true);
         else if (b.packb) DSK_BW_LAUNCH(2, 10, false, true, true);
         else if (b.rowsplit && b.tpw == 1 && b.xrows <= 4) DSK_BW_LAUNCH(1, 4, true, true, false);
         else if (b.rowsplit && b.tpw == 1) DSK_BW_LAUNCH(1, 8, true, true, false);

@@ -166,6 +166,8 @@ BF16_CASES = [
     (1, 40, 60, 92, 70, 4, 8, 1),      # ragged last chunk both ways, 64-filter tiles
     (2, 24, 40, 100, 64, 5, 2, 0),     # 25 taps
     (1, 16, 30, 45, 10, 2, 4, 2),      # backward-data has 10 < 16 channels: fp32 matrix path
+    (1, 48, 70, 110, 40, 3, 16, 0),    # 3x3 taps 16 apart: weight gradient on the bf16 matrix cores too
+    (2, 32, 40, 64, 33, 3, 8, 1),
 ]
 
 

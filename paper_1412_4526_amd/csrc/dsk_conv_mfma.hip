@@ -21,6 +21,8 @@ namespace dsk {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 static constexpr int kThreads = 256;
 static constexpr int kXcds = 8;
@@ -700,12 +702,12 @@ struct BwParams {
 //   operand are (channel, tap column b) pairs instead of 32 channels, so the accumulator
 //   tiles are indexed by the tap ROW only and a 5x5x3 kernel costs 5 MFMA columns of which
 //   15/32 are useful instead of 25 of which 3/32 are.
-// BFM (bf16 maps whose tap columns are a multiple of 8 pixels apart): the tiles are kept in LDS
-//   as bf16 in the same [filter or channel][row][column] order, and one v_mfma_f32_32x32x16_bf16
-//   contracts 16 consecutive pixels of a row, of which a lane supplies 8 with one 16-byte read
-//   (hence the alignment condition).  The matrix cores then have 1/16 of the work and the kernel
-//   runs at the speed of its staging.
-template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false, bool BFM = false>
+// BFM = 8, 4 or 2 (bf16 maps whose tap columns are a multiple of that many pixels apart; 0: off):
+//   the tiles are kept in LDS as bf16 in the same [filter or channel][row][column] order, and one
+//   v_mfma_f32_32x32x16_bf16 contracts 16 consecutive pixels of a row, of which a lane supplies 8:
+//   one 16-byte LDS read when they are aligned to 8 pixels, else two 8-byte or four 4-byte reads.
+//   The matrix cores then have 1/16 of the work and the kernel runs at the speed of its staging.
+template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false, int BFM = 0>
 __global__ void __launch_bounds__(kThreads, (TPW <= 9 ? 2 : 1))
 conv_bwd_weight_mfma_kernel(BwParams p)
 {
@@ -871,7 +873,20 @@ conv_bwd_weight_mfma_kernel(BwParams p)
                     const bf16x8 A = *(const bf16x8 *)(ab + r * PW + 16 * q);
                     bf16x8 B[TPW];
 #pragma unroll
-                    for (int t = 0; t < TPW; ++t) B[t] = *(const bf16x8 *)(bb + boff[t] + r * p.xcols + 16 * q);
+                    for (int t = 0; t < TPW; ++t) {
+                        const unsigned short *src = bb + boff[t] + r * p.xcols + 16 * q;
+                        if (BFM == 8) {
+                            B[t] = *(const bf16x8 *)src;
+                        } else if (BFM == 4) {
+                            const u32x2 b0 = *(const u32x2 *)src, b1 = *(const u32x2 *)(src + 4);
+                            const u32x4 b = {b0[0], b0[1], b1[0], b1[1]};
+                            B[t] = __builtin_bit_cast(bf16x8, b);
+                        } else {
+                            const unsigned *s32 = (const unsigned *)src;
+                            const u32x4 b = {s32[0], s32[1], s32[2], s32[3]};
+                            B[t] = __builtin_bit_cast(bf16x8, b);
+                        }
+                    }
 #pragma unroll
                     for (int t = 0; t < TPW; ++t)
                         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B[t], acc[t], 0, 0, 0);
@@ -1015,7 +1030,7 @@ struct BwPlan {
     bool ok;
     int Kp, Cp, xrows, xcols, xstride, n_rowtile, n_coltile, S, n_fblk, n_cblk, tpw;
     bool rowsplit, packb;
-    bool bfm;            // bf16 tiles in LDS, bf16 matrix cores
+    int bfm;             // 8, 4, 2: bf16 tiles in LDS, bf16 matrix cores, tap columns aligned to that many pixels; 0: off
     int col_passes;      // > 1: one launch per tap column b (a kh x 1 kernel on x shifted by b*d columns)
     int n_part;          // partial blocks the reduce kernel adds up
     long n_ptile;
@@ -1030,11 +1045,14 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     if (taps > 52) return b;
     // few input channels: pack (channel, tap column) pairs into the 32 B-operand columns
     b.packb = allow_packb && s.C <= 4 && s.C * s.kw <= 32 && s.kh >= 2 && s.kh <= 7;
-    // bf16 matrix cores: every 16-byte LDS read of 8 pixels must be aligned, i.e. the tap columns a
-    // multiple of 8 pixels apart; kernels exist for 3 and 4 accumulator tiles per wave
-    b.bfm = in == DSK_BF16 && !b.packb && s.kw > 1 && s.d % 8 == 0 && taps > 8 && taps <= 16 && s.kh <= 5;
+    // bf16 matrix cores: a lane's 8 pixels are read from LDS in pieces as large as the spacing of the
+    // tap columns allows (odd spacings are left to the fp32 path); kernels exist for 3, 4 and 7
+    // accumulator tiles per wave
+    b.bfm = 0;
+    if (in == DSK_BF16 && !b.packb && s.kw > 1 && s.d % 2 == 0 && taps > 8 && taps <= 28 && s.kh <= 5)
+        b.bfm = s.d % 8 == 0 ? 8 : s.d % 4 == 0 ? 4 : 2;
     b.rowsplit = !b.packb && !b.bfm && (taps == 1 || taps == 9);
-    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.bfm ? (taps <= 12 ? 3 : 4)
+    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.bfm ? (taps <= 12 ? 3 : taps <= 16 ? 4 : 7)
           : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
     b.Kp = (s.K + 31) / 32 * 32;
     b.Cp = (s.C + 31) / 32 * 32;
@@ -1181,12 +1199,18 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     int rc = DSK_OK;
     for (int pass = 0; pass < b.col_passes; ++pass) {
         p.col_shift = pass * s.d;      // the partial blocks are reused: the passes run one after the other
-        if (b.bfm && b.tpw == 3)
-            conv_bwd_weight_mfma_kernel<bf16, 3, 8, false, true, false, true>
-                <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
-        else if (b.bfm)
-            conv_bwd_weight_mfma_kernel<bf16, 4, 8, false, true, false, true>
-                <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+#define DSK_BFM_LAUNCH(TPW, AL)                                                                        \
+    conv_bwd_weight_mfma_kernel<bf16, TPW, 8, false, true, false, AL><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p)
+        if (b.bfm == 8 && b.tpw == 3) DSK_BFM_LAUNCH(3, 8);
+        else if (b.bfm == 8 && b.tpw == 4) DSK_BFM_LAUNCH(4, 8);
+        else if (b.bfm == 8) DSK_BFM_LAUNCH(7, 8);
+        else if (b.bfm == 4 && b.tpw == 3) DSK_BFM_LAUNCH(3, 4);
+        else if (b.bfm == 4 && b.tpw == 4) DSK_BFM_LAUNCH(4, 4);
+        else if (b.bfm == 4) DSK_BFM_LAUNCH(7, 4);
+        else if (b.bfm == 2 && b.tpw == 3) DSK_BFM_LAUNCH(3, 2);
+        else if (b.bfm == 2 && b.tpw == 4) DSK_BFM_LAUNCH(4, 2);
+        else if (b.bfm == 2) DSK_BFM_LAUNCH(7, 2);
+#undef DSK_BFM_LAUNCH
         else if (b.packb && b.xrows <= 8) DSK_BW_LAUNCH(2, 8, false, true, true);
         else if (b.packb) DSK_BW_LAUNCH(2, 10, false, true, true);
         else if (b.rowsplit && b.tpw == 1 && b.xrows <= 4) DSK_BW_LAUNCH(1, 4, true, true, false);

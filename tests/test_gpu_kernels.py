@@ -168,6 +168,8 @@ BF16_CASES = [
     (1, 16, 30, 45, 10, 2, 4, 2),      # backward-data has 10 < 16 channels: fp32 matrix path
     (1, 48, 70, 110, 40, 3, 16, 0),    # 3x3 taps 16 apart: weight gradient on the bf16 matrix cores too
     (2, 32, 40, 64, 33, 3, 8, 1),
+    (1, 32, 60, 90, 40, 5, 4, 1),      # 25 taps 4 apart: a lane's 8 pixels come as two 8-byte LDS reads
+    (1, 20, 40, 70, 36, 3, 4, 2),
 ]
 
 

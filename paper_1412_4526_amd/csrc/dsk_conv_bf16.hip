@@ -19,6 +19,7 @@ static constexpr int kThreads = 256;
 static constexpr int kXcds = 8;
 static constexpr int TH = 8, TW = 64, CK = 16;
 static constexpr int kItems = 8;        // (pixel, channel half) items per thread per chunk, at most
+static constexpr int kItemsPair = 5;    // (pixel pair, channel half) items per thread per chunk, at most
 static constexpr int kWq = 8;           // 16-byte pieces of the chunk's weights per thread, at most
 static constexpr size_t kMaxLds = 64 * 1024;
 
@@ -34,7 +35,8 @@ struct GbParams {
     int N, Cin, Hin, Win, Fout, Hout, Wout;
     int kh, kw, d, off_h, off_w, act;
     int NC;              // chunks of 16 channels
-    int rows, cols, n_pix;   // LDS tile: TH+kh-1 by TW+(kw-1)*d pixels
+    int rows, cols, n_pix;   // LDS tile: TH+kh-1 by TW+(kw-1)*d pixels; n_pix: pixels (or pixel pairs) staged per channel half
+    int pp_row;          // pixel pairs per tile row (pair form)
     int n_items, n_wq;   // per thread and chunk: items, 16-byte weight pieces (LDS parts padded accordingly)
     int xs_bytes;
     int n_rowtile, n_coltile, n_fgrp;
@@ -65,12 +67,16 @@ gb_weight_prep_kernel(const float *__restrict__ w, bf16 *__restrict__ wt, int K,
     wt[idx] = f32_to_bf16(v);
 }
 
-template <typename TO, int WM>
+// PAIR (maps with an even number of columns): an item is (pixel PAIR, channel half).  Every row of
+// a plane then starts at an even element, so two neighbouring pixels starting at an even column
+// are one aligned 4-byte load: half as many loads and staging registers, and the two pixels are
+// separated when they are packed for LDS.
+template <typename TO, int WM, bool PAIR>
 __global__ void __launch_bounds__(kThreads, 2)
 gemm_conv_bf16_kernel(GbParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int TF = WM * 32;
+    constexpr int TF = WM * 32, NI = PAIR ? kItemsPair : kItems;
     unsigned char *xs = smem;                  // [rows*cols pixels][16 channels] bf16
     unsigned char *wsm = smem + p.xs_bytes;    // [taps][TF][16 channels] bf16
 
@@ -97,17 +103,34 @@ gemm_conv_bf16_kernel(GbParams p)
     // where channel 8*g of the chunk is read for that pixel, relative to the chunk's first
     // channel; pixels outside the map (and the padding of the item list) read offset 0, which
     // is a valid address, and bit i of `zero` turns them into zeros at the LDS write.
-    unsigned voff[kItems];
+    // PAIR: n_pix counts pixel pairs (pp_row per tile row); pair jp of a row is tile columns
+    // 2*jp - par and 2*jp + 1 - par, where par makes the first one an even map column; lpix[i] is
+    // the LDS pixel index of the first (the second follows it) and bits 8+i / 16+i of `zero`
+    // say that the first / second column lies outside the tile and is not written.
+    unsigned voff[NI];
+    int lpix[PAIR ? NI : 1];
     unsigned zero = 0;
+    const int par = PAIR ? (v0 - p.off_w) & 1 : 0;
 #pragma unroll
-    for (int i = 0; i < kItems; ++i) {
+    for (int i = 0; i < NI; ++i) {
         const int it = tid + i * kThreads;
         const int g = it >= p.n_pix ? 1 : 0, pi = it - g * p.n_pix;
-        const int r = pi / p.cols, c = pi - r * p.cols;
-        const int irow = u0 + r * p.d - p.off_h, icol = v0 + c - p.off_w;
-        const bool ok = it < 2 * p.n_pix && irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win;
-        voff[i] = ok ? (unsigned)(8 * g) * HW + (unsigned)(irow * p.Win + icol) : 0u;
-        zero |= ok ? 0u : 1u << i;
+        if (PAIR) {
+            const int r = pi / p.pp_row, c = 2 * (pi - r * p.pp_row) - par;
+            const int irow = u0 + r * p.d - p.off_h, icol = v0 + c - p.off_w;      // icol is even
+            const bool ok = it < 2 * p.n_pix && irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win;
+            voff[i] = ok ? (unsigned)(8 * g) * HW + (unsigned)(irow * p.Win + icol) : 0u;
+            lpix[i] = r * p.cols + c;
+            zero |= ok ? 0u : 1u << i;
+            zero |= it < 2 * p.n_pix && c >= 0 && c < p.cols ? 0u : 1u << (8 + i);
+            zero |= it < 2 * p.n_pix && c + 1 >= 0 && c + 1 < p.cols ? 0u : 1u << (16 + i);
+        } else {
+            const int r = pi / p.cols, c = pi - r * p.cols;
+            const int irow = u0 + r * p.d - p.off_h, icol = v0 + c - p.off_w;
+            const bool ok = it < 2 * p.n_pix && irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win;
+            voff[i] = ok ? (unsigned)(8 * g) * HW + (unsigned)(irow * p.Win + icol) : 0u;
+            zero |= ok ? 0u : 1u << i;
+        }
     }
 
     f32x16 acc[WM][4];
@@ -118,28 +141,30 @@ gemm_conv_bf16_kernel(GbParams p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
 
-    unsigned short xr[kItems][8];
+    unsigned xr[NI][8];      // one 2-byte value each (PAIR: two, of neighbouring pixels)
     u32x4 wv[kWq];
     // Every load is issued unconditionally: a load under a condition would be waited for on the spot.
     auto fetch = [&](int ch) __attribute__((always_inline)) {
         const int c0 = ch * CK;
         if (c0 + CK <= p.Cin) {
 #pragma unroll
-            for (int i = 0; i < kItems; ++i)
+            for (int i = 0; i < NI; ++i)
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
-                    xr[i][j] = __builtin_amdgcn_raw_buffer_load_b16(rx, (int)(voff[i] * 2u), (int)((unsigned)(c0 + j) * HW * 2u), 0);
+                    xr[i][j] = PAIR ? __builtin_amdgcn_raw_buffer_load_b32(rx, (int)(voff[i] * 2u), (int)((unsigned)(c0 + j) * HW * 2u), 0)
+                                    : __builtin_amdgcn_raw_buffer_load_b16(rx, (int)(voff[i] * 2u), (int)((unsigned)(c0 + j) * HW * 2u), 0);
         } else {
             // last chunk of a padded channel count: channels at or beyond Cin meet zero weights;
             // the chunk's first channel is read instead so that the address stays inside the tensor
 #pragma unroll
-            for (int i = 0; i < kItems; ++i) {
+            for (int i = 0; i < NI; ++i) {
                 const int g8 = tid + i * kThreads >= p.n_pix ? 8 : 0;
                 const unsigned pix = voff[i] - (unsigned)g8 * HW * ((zero >> i) & 1u ? 0u : 1u);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const unsigned off = c0 + g8 + j < p.Cin ? voff[i] + (unsigned)j * HW : pix;
-                    xr[i][j] = __builtin_amdgcn_raw_buffer_load_b16(rx, (int)(off * 2u), (int)((unsigned)c0 * HW * 2u), 0);
+                    xr[i][j] = PAIR ? __builtin_amdgcn_raw_buffer_load_b32(rx, (int)(off * 2u), (int)((unsigned)c0 * HW * 2u), 0)
+                                    : __builtin_amdgcn_raw_buffer_load_b16(rx, (int)(off * 2u), (int)((unsigned)c0 * HW * 2u), 0);
                 }
             }
         }
@@ -158,16 +183,35 @@ gemm_conv_bf16_kernel(GbParams p)
     fetch(0);
     for (int ch = 0; ch < p.NC; ++ch) {
         __syncthreads();      // every wave is done reading the previous chunk
+        // The loaded halves are packed here, not where they were fetched: packed early (which the
+        // compiler would do to halve the registers they occupy) every pair of loads is waited for
+        // on the spot, and a chunk then costs 32 memory round trips instead of one.
 #pragma unroll
-        for (int i = 0; i < kItems; ++i)
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(xr[i][j]));
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
             if (i < p.n_items) {
-                u32x4 v;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    v[j] = (zero >> i) & 1u ? 0u : (unsigned)xr[i][2 * j] | ((unsigned)xr[i][2 * j + 1] << 16);
                 const int it = tid + i * kThreads;
                 const int g = it >= p.n_pix ? 1 : 0;
-                if (it < 2 * p.n_pix) *(u32x4 *)(xs + (it - g * p.n_pix) * 32 + g * 16) = v;
+                const bool z = (zero >> i) & 1u;
+                if (PAIR) {
+                    u32x4 va, vb;      // the low halves belong to the first pixel, the high halves to the second
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const unsigned q0 = xr[i][2 * j], q1 = xr[i][2 * j + 1];
+                        va[j] = z ? 0u : (q0 & 0xffffu) | (q1 << 16);
+                        vb[j] = z ? 0u : (q0 >> 16) | (q1 & 0xffff0000u);
+                    }
+                    if (!((zero >> (8 + i)) & 1u)) *(u32x4 *)(xs + lpix[i] * 32 + g * 16) = va;
+                    if (!((zero >> (16 + i)) & 1u)) *(u32x4 *)(xs + (lpix[i] + 1) * 32 + g * 16) = vb;
+                } else {
+                    u32x4 v;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = z ? 0u : xr[i][2 * j] | (xr[i][2 * j + 1] << 16);
+                    if (it < 2 * p.n_pix) *(u32x4 *)(xs + (it - g * p.n_pix) * 32 + g * 16) = v;
+                }
             }
 #pragma unroll
         for (int q = 0; q < kWq; ++q)
@@ -225,13 +269,14 @@ gemm_conv_bf16_kernel(GbParams p)
 
 struct GbPlan {
     bool ok;
-    int WM, TF, NC, rows, cols, n_pix, n_items, n_wq, xs_bytes, n_fgrp, n_rowtile, n_coltile;
+    int WM, TF, NC, rows, cols, n_pix, pp_row, n_items, n_wq, xs_bytes, n_fgrp, n_rowtile, n_coltile;
+    bool pair;
     long tiles;
     size_t lds_bytes, wt_bytes;
 };
 
 // Cin / Fout: channel and output counts of the GEMM (swapped for backward-data)
-static GbPlan gb_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int kw, int d)
+static GbPlan gb_plan(int N, int Cin, int Win, int Fout, int Hout, int Wout, int kh, int kw, int d)
 {
     GbPlan g{};
     if (Cin < CK) return g;        // a first layer with 3 channels would be 13/16 padding
@@ -240,10 +285,17 @@ static GbPlan gb_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
     const long taps = (long)kh * kw;
     if (cols > 4096 || taps > 1024) return g;
     g.cols = (int)cols;
-    g.n_pix = g.rows * g.cols;
+    g.pair = Win % 2 == 0;
+    g.pp_row = g.cols / 2 + 1;
+    g.n_pix = g.pair ? g.rows * g.pp_row : g.rows * g.cols;
     g.n_items = (2 * g.n_pix + kThreads - 1) / kThreads;
+    if (g.pair && g.n_items > kItemsPair) {      // too many pairs for the registers set aside: single pixels
+        g.pair = false;
+        g.n_pix = g.rows * g.cols;
+        g.n_items = (2 * g.n_pix + kThreads - 1) / kThreads;
+    }
     if (g.n_items > kItems) return g;
-    g.xs_bytes = (g.n_pix * 32 + 255) & ~255;
+    g.xs_bytes = (g.rows * g.cols * 32 + 255) & ~255;
     for (int wm = 2; wm >= 1; --wm) {
         if (wm == 2 && Fout <= 32) continue;
         const long wbytes = taps * wm * 32 * CK * 2;
@@ -274,7 +326,7 @@ static int gb_run(const void *in, void *out, const float *w, const float *bias, 
                   int Fout, int Hout, int Wout, int kh, int kw, int d, int off, int act, int flip, int K, int C,
                   dsk_dtype tout, void *ws, hipStream_t st)
 {
-    const GbPlan g = gb_plan(N, Cin, Fout, Hout, Wout, kh, kw, d);
+    const GbPlan g = gb_plan(N, Cin, Win, Fout, Hout, Wout, kh, kw, d);
     if (!g.ok) return DSK_ESHAPE;
     const int taps = kh * kw;
     bf16 *wt = (bf16 *)ws;
@@ -288,28 +340,35 @@ static int gb_run(const void *in, void *out, const float *w, const float *bias, 
     p.N = N; p.Cin = Cin; p.Hin = Hin; p.Win = Win; p.Fout = Fout; p.Hout = Hout; p.Wout = Wout;
     p.kh = kh; p.kw = kw; p.d = d; p.off_h = off ? (kh - 1) * d : 0; p.off_w = off ? (kw - 1) * d : 0;
     p.act = act;
-    p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.n_pix = g.n_pix; p.n_items = g.n_items; p.n_wq = g.n_wq;
+    p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.n_pix = g.n_pix; p.pp_row = g.pp_row; p.n_items = g.n_items;
+    p.n_wq = g.n_wq;
     p.xs_bytes = g.xs_bytes;
     p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp;
     p.tiles = g.tiles;
     p.per_xcd = (g.tiles + kXcds - 1) / kXcds;
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;
     const unsigned grid = (unsigned)(p.per_xcd * kXcds);
+#define DSK_GB_LAUNCH(TO, WM, PAIR) gemm_conv_bf16_kernel<TO, WM, PAIR><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p)
     if (tout == DSK_BF16) {
-        if (g.WM == 2) gemm_conv_bf16_kernel<bf16, 2><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
-        else gemm_conv_bf16_kernel<bf16, 1><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        if (g.WM == 2 && g.pair) DSK_GB_LAUNCH(bf16, 2, true);
+        else if (g.WM == 2) DSK_GB_LAUNCH(bf16, 2, false);
+        else if (g.pair) DSK_GB_LAUNCH(bf16, 1, true);
+        else DSK_GB_LAUNCH(bf16, 1, false);
     } else {
-        if (g.WM == 2) gemm_conv_bf16_kernel<float, 2><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
-        else gemm_conv_bf16_kernel<float, 1><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        if (g.WM == 2 && g.pair) DSK_GB_LAUNCH(float, 2, true);
+        else if (g.WM == 2) DSK_GB_LAUNCH(float, 2, false);
+        else if (g.pair) DSK_GB_LAUNCH(float, 1, true);
+        else DSK_GB_LAUNCH(float, 1, false);
     }
+#undef DSK_GB_LAUNCH
     return check_launch();
 }
 
 // ---- entry points for the dispatcher (bf16 input maps only)
 size_t conv_bf16_ws_bytes(int which, const ConvShape &s)
 {
-    const GbPlan g = which == DSK_WS_CONV_FWD ? gb_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d)
-                                              : gb_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d);
+    const GbPlan g = which == DSK_WS_CONV_FWD ? gb_plan(s.N, s.C, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d)
+                                              : gb_plan(s.N, s.K, s.Wo, s.C, s.H, s.W, s.kh, s.kw, s.d);
     return g.ok ? g.wt_bytes : 0;
 }
 
@@ -319,8 +378,8 @@ bool conv_bf16_supported(int which, const ConvShape &s)
         (long)s.K * s.Ho * s.Wo >= (1L << 30))
         return false;
     if (s.kh == 1 && s.kw == 1) return false;      // 1x1 layers have their own kernel
-    if (which == DSK_WS_CONV_FWD) return gb_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
-    if (which == DSK_WS_CONV_BWD_DATA) return gb_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
+    if (which == DSK_WS_CONV_FWD) return gb_plan(s.N, s.C, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
+    if (which == DSK_WS_CONV_BWD_DATA) return gb_plan(s.N, s.K, s.Wo, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
     return false;
 }
 

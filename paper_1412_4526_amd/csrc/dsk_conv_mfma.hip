@@ -678,6 +678,27 @@ static constexpr int PW = 32;   // pixel-tile columns
 static constexpr int DY_STRIDE = PH * PW + 1;   // odd: lanes = filters read conflict-free
 static constexpr int DYB = PH * PW + 8;         // bf16 tiles: 272 bytes per filter
 
+// Loads for the tiles of the weight gradient.  RAW (bf16 tiles in LDS): the 16 bits are kept as
+// they are, in the low half of the register, instead of being widened to fp32 and rounded back.
+template <bool RAW>
+__device__ inline float bw_ld(BufRsrc r, const float *p, unsigned lane_off, unsigned uniform_off)
+{
+    return buf_ld(r, p, lane_off, uniform_off);
+}
+template <bool RAW>
+__device__ inline float bw_ld(BufRsrc r, const bf16 *p, unsigned lane_off, unsigned uniform_off)
+{
+    if (!RAW) return buf_ld(r, p, lane_off, uniform_off);
+    return __builtin_bit_cast(float, (unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
+                                         r, (int)(lane_off * 2u), (int)(uniform_off * 2u), 0));
+}
+template <bool RAW> __device__ inline float bw_ld(const float *p, long i) { return p[i]; }
+template <bool RAW> __device__ inline float bw_ld(const bf16 *p, long i)
+{
+    return RAW ? __builtin_bit_cast(float, (unsigned)p[i].v) : bf16_to_f32(p[i]);
+}
+__device__ inline unsigned short bw_raw16(float v) { return (unsigned short)__builtin_bit_cast(unsigned, v); }
+
 struct BwParams {
     const void *x, *dy;
     float *part;         // [split][taps][Kp][Cp]
@@ -801,7 +822,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int seg = wave * 2 + 8 * i;
-                dr[i] = buf_ld(rd, dyt, dlane_off, (unsigned)(seg >> 2) * HoWo + (unsigned)(seg & 3) * dWo);
+                dr[i] = bw_ld<BFM != 0>(rd, dyt, dlane_off, (unsigned)(seg >> 2) * HoWo + (unsigned)(seg & 3) * dWo);
             }
             const BufRsrc rx = buf_rsrc(xt, x_end);
 #pragma unroll
@@ -809,7 +830,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
                 for (int r = 0; r < XR; ++r) {
                     const int rr = r < p.xrows ? r : 0;      // rows beyond the tile are not staged
-                    xr[ci][r] = buf_ld(rx, xt, xlane_off, (unsigned)(wave + 4 * ci) * HW + (unsigned)rr * dW);
+                    xr[ci][r] = bw_ld<BFM != 0>(rx, xt, xlane_off, (unsigned)(wave + 4 * ci) * HW + (unsigned)rr * dW);
                 }
             }
             return;
@@ -821,7 +842,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             const bool ok_s = f < nf_valid && r < st_nr_dy;   // uniform
             const TI *base = ok_s ? dyt + ((unsigned)f * HoWo + (unsigned)r * dWo) : dyt;
             const bool ok = ok_s && st_dcol_ok && r + hi < st_nr_dy;
-            dr[i] = ldf(base, (long)(ok ? (unsigned)hi * dWo + (unsigned)lo : 0u));
+            dr[i] = bw_ld<BFM != 0>(base, (long)(ok ? (unsigned)hi * dWo + (unsigned)lo : 0u));
         }
 #pragma unroll
         for (int ci = 0; ci < NCI; ++ci) {
@@ -830,7 +851,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             for (int r = 0; r < XR; ++r) {
                 const bool ok_s = c < nc_valid && r < st_nr_x;              // uniform
                 const TI *base = ok_s ? xt + ((unsigned)c * HW + (unsigned)r * dW) : xt;
-                xr[ci][r] = ldf(base, (long)xlane_off);
+                xr[ci][r] = bw_ld<BFM != 0>(base, (long)xlane_off);
             }
         }
     };
@@ -845,7 +866,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             const int seg = wave * 2 + hi + 8 * i;
             const bool ok = st_dcol_ok && (seg >> 2) < nf_valid && (seg & 3) < st_nr_dy;
             const float v = ok ? dr[i] : 0.f;
-            if (BFM) dyb[(seg >> 2) * DYB + (seg & 3) * PW + lo] = f32_to_bf16(v).v;      // exact: v came from bf16
+            if (BFM) dyb[(seg >> 2) * DYB + (seg & 3) * PW + lo] = bw_raw16(v);
             else dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
         }
         if (lane < p.xcols) {
@@ -856,7 +877,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
                     if (r < p.xrows) {
                         const bool ok = st_col_ok && wave + 4 * ci < nc_valid && r < st_nr_x;
                         const float v = ok ? xr[ci][r] : 0.f;
-                        if (BFM) xb16[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = f32_to_bf16(v).v;
+                        if (BFM) xb16[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = bw_raw16(v);
                         else xs[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = v;
                     }
         }

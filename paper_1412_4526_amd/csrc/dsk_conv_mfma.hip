@@ -783,8 +783,13 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-    float dr[16];          // dy tile share: (filter, row) segments wave*2+hi+8i, column lo
-    float xr[NCI][XR];     // x tile share: channels wave+4*ci, rows r, column lane
+    float dr[BFM ? 1 : 16];              // dy tile share: (filter, row) segments wave*2+hi+8i, column lo
+    float xr[BFM ? 1 : NCI][BFM ? 1 : XR];   // x tile share: channels wave+4*ci, rows r, column lane
+    // BFM: the maps have an even number of columns, so two neighbouring pixels are one aligned
+    // 4-byte load and one 4-byte LDS write.  dy: filter wave+4i, row lane/16, pixel pair lane%16;
+    // x: channel wave+4*ci, row 2k + lane/32, pixel pair lane%32.
+    unsigned drp[BFM ? 8 : 1];
+    unsigned xrp[BFM ? NCI : 1][BFM ? XR / 2 : 1];
 
     // Every tile starts inside both maps (the host enumerates only such tiles), so the tile's
     // base is always a valid address: loads that fall outside the maps are redirected there and
@@ -806,6 +811,36 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         const int v0 = ct * PW;
         const TI *dyt = dy + (((long)n * p.K + fb * 32) * p.Ho + u0) * p.Wo + v0;
         const TI *xt = x + (((long)n * p.C + cb * 32) * p.H + u0) * p.W + v0 + p.col_shift;
+        if constexpr (BFM != 0) {
+            st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;
+            st_nr_x = (p.H - u0 + p.d - 1) / p.d;
+            st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
+            const int rl = lane >> 4, jl = lane & 15, xl = lane >> 5, pl = lane & 31;
+            st_dcol_ok = v0 + 2 * jl < p.Wo;
+            st_col_ok = 2 * pl < p.xcols && v0 + 2 * pl + p.col_shift < p.W;
+            // offsets in elements; rows, filters and channels that do not exist are read from the
+            // tile's first element instead (a valid address) and become zeros at the LDS write
+            const unsigned dlo = st_dcol_ok && rl < st_nr_dy ? (unsigned)rl * dWo + 2u * jl : 0u;
+            const BufRsrc rd = buf_rsrc(dyt, dy_end);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int f = wave + 4 * i;
+                const unsigned so = f < nf_valid ? (unsigned)f * HoWo : 0u;
+                drp[i] = __builtin_amdgcn_raw_buffer_load_b32(rd, (int)(dlo * 2u), (int)(so * 2u), 0);
+            }
+            const BufRsrc rx = buf_rsrc(xt, x_end);
+#pragma unroll
+            for (int ci = 0; ci < NCI; ++ci) {
+                const int c = wave + 4 * ci;
+#pragma unroll
+                for (int k = 0; k < XR / 2; ++k) {
+                    const unsigned so = c < nc_valid && 2 * k < st_nr_x ? (unsigned)c * HW + (unsigned)(2 * k) * dW : 0u;
+                    const unsigned xo = st_col_ok && 2 * k + xl < st_nr_x ? (unsigned)xl * dW + 2u * pl : 0u;
+                    xrp[ci][k] = __builtin_amdgcn_raw_buffer_load_b32(rx, (int)(xo * 2u), (int)(so * 2u), 0);
+                }
+            }
+            return;
+        }
         // dy: segment i of this wave is filter f_i, rows r_i (lanes 0-31) and r_i+1 (lanes 32-63)
         st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;           // dy rows u0 + r*d that exist (>= 1)
         st_dcol_ok = v0 + lo < p.Wo;
@@ -861,6 +896,27 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     while (pt < p.n_ptile) {
         if (!PREFETCH) load_tile(pt);
         __syncthreads();        // every wave is done with the previous tile
+        if constexpr (BFM != 0) {
+            const int rl = lane >> 4, jl = lane & 15, xl = lane >> 5, pl = lane & 31;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int f = wave + 4 * i;
+                const bool ok = st_dcol_ok && f < nf_valid && rl < st_nr_dy;
+                *(unsigned *)(dyb + f * DYB + rl * PW + 2 * jl) = ok ? drp[i] : 0u;
+            }
+            if (2 * pl < p.xcols) {
+#pragma unroll
+                for (int ci = 0; ci < NCI; ++ci)
+#pragma unroll
+                    for (int k = 0; k < XR / 2; ++k) {
+                        const int r = 2 * k + xl;
+                        if (r < p.xrows) {
+                            const bool ok = st_col_ok && wave + 4 * ci < nc_valid && r < st_nr_x;
+                            *(unsigned *)(xb16 + (wave + 4 * ci) * p.xstride + r * p.xcols + 2 * pl) = ok ? xrp[ci][k] : 0u;
+                        }
+                    }
+            }
+        } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int seg = wave * 2 + hi + 8 * i;
@@ -880,6 +936,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
                         if (BFM) xb16[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = bw_raw16(v);
                         else xs[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = v;
                     }
+        }
         }
         __syncthreads();
         if (PREFETCH && pt + p.S < p.n_ptile) load_tile(pt + p.S);      // in flight while the matrix cores run
@@ -1067,10 +1124,10 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     // few input channels: pack (channel, tap column) pairs into the 32 B-operand columns
     b.packb = allow_packb && s.C <= 4 && s.C * s.kw <= 32 && s.kh >= 2 && s.kh <= 7;
     // bf16 matrix cores: a lane's 8 pixels are read from LDS in pieces as large as the spacing of the
-    // tap columns allows (odd spacings are left to the fp32 path); kernels exist for 3, 4 and 7
-    // accumulator tiles per wave
+    // tap columns allows (odd spacings and maps of odd width, whose pixel pairs are not aligned
+    // 4-byte words, are left to the fp32 path); kernels exist for 3, 4 and 7 accumulator tiles per wave
     b.bfm = 0;
-    if (in == DSK_BF16 && !b.packb && s.kw > 1 && s.d % 2 == 0 && taps > 8 && taps <= 28 && s.kh <= 5)
+    if (in == DSK_BF16 && !b.packb && s.kw > 1 && s.d % 2 == 0 && s.W % 2 == 0 && taps > 8 && taps <= 28 && s.kh <= 5)
         b.bfm = s.d % 8 == 0 ? 8 : s.d % 4 == 0 ? 4 : 2;
     b.rowsplit = !b.packb && !b.bfm && (taps == 1 || taps == 9);
     b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.bfm ? (taps <= 12 ? 3 : taps <= 16 ? 4 : 7)

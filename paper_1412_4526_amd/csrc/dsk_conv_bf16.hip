@@ -19,7 +19,7 @@ static constexpr int kThreads = 256;
 static constexpr int kXcds = 8;
 static constexpr int TH = 8, TW = 64, CK = 16;
 static constexpr int kItems = 8;        // (pixel, channel half) items per thread per chunk, at most
-static constexpr int kItemsPair = 5;    // (pixel pair, channel half) items per thread per chunk, at most
+static constexpr int kItemsPair = 4;    // (pixel pair, channel half) items per thread per chunk, at most
 static constexpr int kWq = 8;           // 16-byte pieces of the chunk's weights per thread, at most
 static constexpr size_t kMaxLds = 64 * 1024;
 

@@ -1104,6 +1104,146 @@ bias_reduce_kernel(const float *__restrict__ part, float *__restrict__ db, int K
     db[f] = acc;
 }
 
+// ============================================================================
+// Weight gradient of a 1x1 kernel: dw[f][c] = sum over images and pixels q of dy[f][q] * x[c][q].
+// Both maps should come from HBM once: a workgroup owns up to 64 filters x 256 channels of dw
+// (16 accumulator tiles, four per wave) and walks over a share of the 32-pixel tiles of the
+// flat pixel index; A = dy (lane = filter), B = x (lane = channel), k = pixel pair, both
+// transposed through LDS (row pitch 33: conflict-free).  The next tile is fetched into
+// registers meanwhile.  Partial blocks [share][Kp][Cp] are summed by bw_reduce_kernel.
+// ============================================================================
+static constexpr int kPbQ = 32;          // pixels per tile
+static constexpr int kPbPitch = kPbQ + 1;
+
+struct PbParams {
+    const void *x, *dy;
+    float *part;         // [S][Kp][Cp]
+    int N, C, K, Kp, Cp, S, n_cg;
+    long HW, n_tile;     // pixels per plane; N * ceil(HW / 32)
+};
+
+template <typename TI, int FB>
+__global__ void __launch_bounds__(kThreads, 2)
+pw_bwd_weight_kernel(PbParams p)
+{
+    __shared__ float dys[FB * 32 * kPbPitch];
+    __shared__ float xs[256 * kPbPitch];
+    const int tid = threadIdx.x, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cg = blockIdx.x % p.n_cg, s = blockIdx.x / p.n_cg;
+    const int c_base = cg * 256;
+    const TI *x = (const TI *)p.x, *dy = (const TI *)p.dy;
+    const unsigned HW = (unsigned)p.HW;
+    const long per_img = (p.HW + kPbQ - 1) / kPbQ;
+    const TI *x_end = x + (long)p.N * p.C * p.HW, *dy_end = dy + (long)p.N * p.K * p.HW;
+
+    f32x16 acc[FB][2];
+#pragma unroll
+    for (int a = 0; a < FB; ++a)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][j][i] = 0.f;
+
+    // staging share of a thread: pixel lo of rows 2*wave + hi + 8*i (x: 32 channel rows, dy: 4*FB filter rows)
+    float xr[32], dr[4 * FB];
+    bool st_q_ok = false;
+    auto load_tile = [&](long t) __attribute__((always_inline)) {
+        const int n = (int)(t / per_img);
+        const unsigned q0 = (unsigned)(t - n * per_img) * kPbQ;
+        st_q_ok = q0 + lo < HW;
+        const TI *xn = x + ((long)n * p.C + c_base) * p.HW, *dn = dy + (long)n * p.K * p.HW;
+        const BufRsrc rx = buf_rsrc(xn, x_end), rd = buf_rsrc(dn, dy_end);
+        // rows that do not exist are read from row 0 (a valid address) and zeroed at the LDS write
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            const int c = 2 * wave + 8 * i;              // lanes 32..63 take c + 1
+            const unsigned lane_off = st_q_ok && c_base + c + hi < p.C ? (unsigned)hi * HW + q0 + lo : 0u;
+            xr[i] = buf_ld(rx, xn, lane_off, c_base + c < p.C ? (unsigned)c * HW : 0u);
+        }
+#pragma unroll
+        for (int i = 0; i < 4 * FB; ++i) {
+            const int f = 2 * wave + 8 * i;
+            const unsigned lane_off = st_q_ok && f + hi < p.K ? (unsigned)hi * HW + q0 + lo : 0u;
+            dr[i] = buf_ld(rd, dn, lane_off, f < p.K ? (unsigned)f * HW : 0u);
+        }
+    };
+
+    long t = s;
+    if (t < p.n_tile) load_tile(t);
+    while (t < p.n_tile) {
+        __syncthreads();        // every wave is done with the previous tile
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            const int c = 2 * wave + hi + 8 * i;
+            xs[c * kPbPitch + lo] = st_q_ok && c_base + c < p.C ? xr[i] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < 4 * FB; ++i) {
+            const int f = 2 * wave + hi + 8 * i;
+            dys[f * kPbPitch + lo] = st_q_ok && f < p.K ? dr[i] : 0.f;
+        }
+        __syncthreads();
+        t += p.S;
+        // the next tile, or the last one again (a load under a condition would be waited for at once)
+        load_tile(t < p.n_tile ? t : t - p.S);
+        const float *ab = dys + lo * kPbPitch + hi;
+        const float *bb = xs + (wave * 64 + lo) * kPbPitch + hi;
+#pragma unroll 4
+        for (int q = 0; q < kPbQ / 2; ++q) {
+            float A[FB], B[2];
+#pragma unroll
+            for (int a = 0; a < FB; ++a) A[a] = ab[a * 32 * kPbPitch + 2 * q];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) B[j] = bb[j * 32 * kPbPitch + 2 * q];
+#pragma unroll
+            for (int a = 0; a < FB; ++a)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[a][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[a], B[j], acc[a][j], 0, 0, 0);
+        }
+    }
+
+    float *part = p.part + (long)s * p.Kp * p.Cp;
+#pragma unroll
+    for (int a = 0; a < FB; ++a)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int c = c_base + (2 * wave + j) * 32 + lo;
+            if (c >= p.Cp) continue;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int f = a * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
+                part[(long)f * p.Cp + c] = acc[a][j][i];
+            }
+        }
+}
+
+struct PbPlan {
+    bool ok;
+    int Kp, Cp, FB, n_cg, S;
+    long n_tile;
+    size_t part_bytes;
+};
+
+static PbPlan pb_plan(const ConvShape &s)
+{
+    PbPlan b{};
+    if (s.kh != 1 || s.kw != 1 || s.K > 64 || (long)s.H * s.W >= (1L << 28)) return b;
+    b.Kp = (s.K + 31) / 32 * 32;
+    b.Cp = (s.C + 31) / 32 * 32;
+    b.FB = b.Kp / 32;
+    b.n_cg = (s.C + 255) / 256;
+    b.n_tile = (long)s.N * (((long)s.H * s.W + kPbQ - 1) / kPbQ);
+    long S = 512 / b.n_cg;
+    if (S > b.n_tile / 4) S = b.n_tile / 4;
+    if (S < 1) S = 1;
+    b.S = (int)S;
+    b.part_bytes = 4 * ((size_t)b.S * b.Kp * b.Cp + (size_t)s.K * kBiasSplit);
+    b.ok = true;
+    return b;
+}
+
 struct BwPlan {
     bool ok;
     int Kp, Cp, xrows, xcols, xstride, n_rowtile, n_coltile, S, n_fblk, n_cblk, tpw;
@@ -1207,6 +1347,8 @@ size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
         return g.ok ? g.wt_bytes + g.partial_bytes : 0;
     }
     if (which == DSK_WS_CONV_BWD_WEIGHT) {
+        const PbPlan pb = pb_plan(s);
+        if (pb.ok) return pb.part_bytes;
         const BwPlan b = bw_plan(s, in);
         return b.ok ? b.part_bytes : 0;
     }
@@ -1225,7 +1367,7 @@ bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype 
         return pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw).ok || gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
     if (which == DSK_WS_CONV_BWD_DATA)
         return pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw).ok || gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
-    if (which == DSK_WS_CONV_BWD_WEIGHT) return bw_plan(s, in).ok;
+    if (which == DSK_WS_CONV_BWD_WEIGHT) return pb_plan(s).ok || bw_plan(s, in).ok;
     return false;
 }
 
@@ -1250,6 +1392,33 @@ int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const Co
 int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
                                 dsk_dtype in, void *ws, hipStream_t st)
 {
+    if (const PbPlan pb = pb_plan(s); pb.ok) {
+        PbParams q{};
+        q.x = x; q.dy = dy; q.part = (float *)ws;
+        q.N = s.N; q.C = s.C; q.K = s.K; q.Kp = pb.Kp; q.Cp = pb.Cp; q.S = pb.S; q.n_cg = pb.n_cg;
+        q.HW = (long)s.H * s.W; q.n_tile = pb.n_tile;
+        const unsigned grid = (unsigned)(pb.S * pb.n_cg);
+        if (in == DSK_F32 && pb.FB == 2) pw_bwd_weight_kernel<float, 2><<<dim3(grid), dim3(kThreads), 0, st>>>(q);
+        else if (in == DSK_F32) pw_bwd_weight_kernel<float, 1><<<dim3(grid), dim3(kThreads), 0, st>>>(q);
+        else if (pb.FB == 2) pw_bwd_weight_kernel<bf16, 2><<<dim3(grid), dim3(kThreads), 0, st>>>(q);
+        else pw_bwd_weight_kernel<bf16, 1><<<dim3(grid), dim3(kThreads), 0, st>>>(q);
+        int rc = check_launch();
+        if (rc != DSK_OK) return rc;
+        const long total = (long)s.K * s.C;
+        bw_reduce_kernel<<<dim3((unsigned)((total + kRedOut - 1) / kRedOut)), dim3(kThreads), 0, st>>>(
+            (const float *)ws, dw, s.K, s.C, 1, pb.Kp, pb.Cp, pb.S, 1, 1, 0);
+        rc = check_launch();
+        if (rc != DSK_OK || !db) return rc;
+        float *bpart = (float *)ws + (size_t)pb.S * pb.Kp * pb.Cp;
+        if (in == DSK_F32)
+            bias_partial_kernel<float><<<dim3(s.K * kBiasSplit), dim3(kThreads), 0, st>>>((const float *)dy, bpart, s.N,
+                                                                                        s.K, (long)s.Ho * s.Wo);
+        else
+            bias_partial_kernel<bf16><<<dim3(s.K * kBiasSplit), dim3(kThreads), 0, st>>>((const bf16 *)dy, bpart, s.N,
+                                                                                       s.K, (long)s.Ho * s.Wo);
+        bias_reduce_kernel<<<dim3((s.K + kThreads - 1) / kThreads), dim3(kThreads), 0, st>>>(bpart, db, s.K);
+        return check_launch();
+    }
     const BwPlan b = bw_plan(s, in);
     if (!b.ok) return DSK_ESHAPE;
     const int kw_pass = b.col_passes > 1 ? 1 : s.kw;      // tap columns one launch covers

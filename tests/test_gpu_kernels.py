@@ -40,6 +40,7 @@ CONV_CASES = [
     (1, 4, 90, 100, 9, 6, 12, 2),      # 6x6 taps 12 apart, four input channels
     (1, 20, 50, 61, 150, 1, 1, 1),     # 1x1 with three filter groups; pixel count not a multiple of 128
     (3, 70, 9, 13, 3, 1, 2, 0),        # 1x1, planes smaller than one wave's 128 pixels
+    (1, 300, 20, 33, 2, 1, 1, 0),      # 1x1, more than 256 channels, two filters
 ]
 
 

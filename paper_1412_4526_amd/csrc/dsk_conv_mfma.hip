@@ -728,13 +728,17 @@ struct BwParams {
 //   v_mfma_f32_32x32x16_bf16 contracts 16 consecutive pixels of a row, of which a lane supplies 8:
 //   one 16-byte LDS read when they are aligned to 8 pixels, else two 8-byte or four 4-byte reads.
 //   The matrix cores then have 1/16 of the work and the kernel runs at the speed of its staging.
-template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false, int BFM = 0>
+// FB = 2 (3x3 kernels in fp32): the workgroup owns TWO 32-filter blocks; waves 0/2 take the first
+//   and waves 1/3 the second, and the two waves of a block divide the taps.  The x tile is then
+//   staged once per 64 filters, and a staged tile feeds 2.2 times as many matrix instructions
+//   as when every wave takes all nine taps of one tile row.
+template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false, int BFM = 0, int FB = 1>
 __global__ void __launch_bounds__(kThreads, (TPW <= 9 ? 2 : 1))
 conv_bwd_weight_mfma_kernel(BwParams p)
 {
     extern __shared__ __align__(16) float smem[];
-    float *dys = smem;                       // [32 filters][DY_STRIDE]
-    float *xs = smem + 32 * DY_STRIDE;       // [32 channels][xstride]
+    float *dys = smem;                       // [32 * FB filters][DY_STRIDE]
+    float *xs = smem + FB * 32 * DY_STRIDE;  // [32 channels][xstride]
     // the same two tiles as bf16: row pitch of the dy tile DYB, of an x channel p.xstride (both
     // multiples of 8 elements and an odd number of 16-byte units, which spreads lanes over the banks)
     unsigned short *dyb = (unsigned short *)smem;
@@ -753,9 +757,12 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     const int per_xcd = (nblk + kXcds - 1) / kXcds;
     int b = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
     if (b >= nblk) return;
-    const int fb = b % p.n_fblk; b /= p.n_fblk;
+    const int fb = b % p.n_fblk; b /= p.n_fblk;      // n_fblk counts groups of FB filter blocks
     const int cb = b % p.n_cblk;
     const int s = b / p.n_cblk;
+    const int f_base = fb * 32 * FB;
+    const int my_fb = FB == 2 ? wave & 1 : 0;                                   // this wave's block of the group
+    const int tap0 = FB == 2 ? wave >> 1 : wave, tap_step = FB == 2 ? 2 : 4;    // its taps: tap0, tap0 + tap_step, ...
 
     const TI *x = (const TI *)p.x;
     const TI *dy = (const TI *)p.dy;
@@ -765,7 +772,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     int boff[TPW];
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
-        int tap = ROWSPLIT ? t : wave + 4 * t;
+        int tap = ROWSPLIT ? t : tap0 + tap_step * t;
         tap = tap < taps ? tap : 0;
         const int a = PACKB ? tap : tap / p.kw;
         boff[t] = a * p.xcols + (PACKB ? 0 : (tap - a * p.kw) * p.d);
@@ -783,7 +790,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-    float dr[BFM ? 1 : 16];              // dy tile share: (filter, row) segments wave*2+hi+8i, column lo
+    float dr[BFM ? 1 : 16 * FB];         // dy tile share: (filter, row) segments wave*2+hi+8i, column lo
     float xr[BFM ? 1 : NCI][BFM ? 1 : XR];   // x tile share: channels wave+4*ci, rows r, column lane
     // BFM: the maps have an even number of columns, so two neighbouring pixels are one aligned
     // 4-byte load and one 4-byte LDS write.  dy: filter wave+4i, row lane/16, pixel pair lane%16;
@@ -798,8 +805,8 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     // is a wave-uniform base plus one per-lane offset shared by all loads of the tile.
     const unsigned HoWo = (unsigned)(p.Ho * p.Wo), dWo = (unsigned)(p.d * p.Wo);
     const unsigned HW = (unsigned)(p.H * p.W), dW = (unsigned)(p.d * p.W);
-    const int nf_valid = p.K - fb * 32, nc_valid = p.C - cb * 32;
-    const bool full_blocks = !PACKB && nf_valid >= 32 && nc_valid >= 32;
+    const int nf_valid = p.K - f_base, nc_valid = p.C - cb * 32;
+    const bool full_blocks = !PACKB && nf_valid >= 32 * FB && nc_valid >= 32;
     const TI *dy_end = dy + (long)p.N * p.K * HoWo, *x_end = x + (long)p.N * p.C * HW;
     int st_nr_dy = 0, st_nr_x = 0;             // rows of the staged tile that exist
     bool st_dcol_ok = false, st_col_ok = false; // this lane's column exists
@@ -809,7 +816,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         const int n = (int)(pt / ((long)p.n_coltile * p.n_rowtile));
         const int u0 = (rt / p.d) * p.d * PH + (rt % p.d);
         const int v0 = ct * PW;
-        const TI *dyt = dy + (((long)n * p.K + fb * 32) * p.Ho + u0) * p.Wo + v0;
+        const TI *dyt = dy + (((long)n * p.K + f_base) * p.Ho + u0) * p.Wo + v0;
         const TI *xt = x + (((long)n * p.C + cb * 32) * p.H + u0) * p.W + v0 + p.col_shift;
         if constexpr (BFM != 0) {
             st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;
@@ -855,7 +862,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             const unsigned dlane_off = st_dcol_ok ? (unsigned)hi * dWo + (unsigned)lo : 0u;
             const BufRsrc rd = buf_rsrc(dyt, dy_end);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
+            for (int i = 0; i < 16 * FB; ++i) {
                 const int seg = wave * 2 + 8 * i;
                 dr[i] = bw_ld<BFM != 0>(rd, dyt, dlane_off, (unsigned)(seg >> 2) * HoWo + (unsigned)(seg & 3) * dWo);
             }
@@ -871,7 +878,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             return;
         }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < 16 * FB; ++i) {
             const int seg = wave * 2 + 8 * i;              // even: the lower half's segment
             const int f = seg >> 2, r = seg & 3;
             const bool ok_s = f < nf_valid && r < st_nr_dy;   // uniform
@@ -918,7 +925,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             }
         } else {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < 16 * FB; ++i) {
             const int seg = wave * 2 + hi + 8 * i;
             const bool ok = st_dcol_ok && (seg >> 2) < nf_valid && (seg & 3) < st_nr_dy;
             const float v = ok ? dr[i] : 0.f;
@@ -973,7 +980,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             continue;
         }
         // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
-        const float *ab = dys + lo * DY_STRIDE + hi;
+        const float *ab = dys + (my_fb * 32 + lo) * DY_STRIDE + hi;
         const float *bb = xs + blane + hi;
         for (int r = ROWSPLIT ? wave : 0; r < (ROWSPLIT ? wave + 1 : PH); ++r) {
 #pragma unroll 4
@@ -994,11 +1001,11 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     float *part = p.part + split * p.Kp * p.Cp * taps;
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
-        const int tap = ROWSPLIT ? t : wave + 4 * t;
-        if (tap >= taps) continue;
+        const int tap = ROWSPLIT ? t : tap0 + tap_step * t;
+        if (tap >= taps || f_base + my_fb * 32 >= p.Kp) continue;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int f = fb * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
+            const int f = f_base + my_fb * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
             const int c = cb * 32 + lo;
             part[((long)tap * p.Kp + f) * p.Cp + c] = acc[t][i];      // 32 consecutive channels per store
         }
@@ -1248,6 +1255,7 @@ struct BwPlan {
     bool ok;
     int Kp, Cp, xrows, xcols, xstride, n_rowtile, n_coltile, S, n_fblk, n_cblk, tpw;
     bool rowsplit, packb;
+    bool fb2;            // two filter blocks per workgroup
     int bfm;             // 8, 4, 2: bf16 tiles in LDS, bf16 matrix cores, tap columns aligned to that many pixels; 0: off
     int col_passes;      // > 1: one launch per tap column b (a kh x 1 kernel on x shifted by b*d columns)
     int n_part;          // partial blocks the reduce kernel adds up
@@ -1269,8 +1277,9 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     b.bfm = 0;
     if (in == DSK_BF16 && !b.packb && s.kw > 1 && s.d % 2 == 0 && s.W % 2 == 0 && taps > 8 && taps <= 28 && s.kh <= 5)
         b.bfm = s.d % 8 == 0 ? 8 : s.d % 4 == 0 ? 4 : 2;
-    b.rowsplit = !b.packb && !b.bfm && (taps == 1 || taps == 9);
-    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.bfm ? (taps <= 12 ? 3 : taps <= 16 ? 4 : 7)
+    b.fb2 = !b.packb && !b.bfm && taps == 9 && s.K > 32;
+    b.rowsplit = !b.packb && !b.bfm && !b.fb2 && (taps == 1 || taps == 9);
+    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.fb2 ? 5 : b.bfm ? (taps <= 12 ? 3 : taps <= 16 ? 4 : 7)
           : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
     b.Kp = (s.K + 31) / 32 * 32;
     b.Cp = (s.C + 31) / 32 * 32;
@@ -1289,6 +1298,16 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
         b.xstride = 8 * (((b.xrows * b.xcols + 7) / 8) | 1);
         b.lds_bytes = 2 * ((size_t)32 * DYB + (size_t)32 * b.xstride);
     }
+    if (b.fb2) {
+        const size_t two = 4 * ((size_t)64 * DY_STRIDE + (size_t)32 * b.xstride);
+        if (two <= kMaxLdsBw) {
+            b.lds_bytes = two;
+        } else {      // wide tap spacing: back to one block per workgroup, every wave all nine taps of a row
+            b.fb2 = false;
+            b.rowsplit = true;
+            b.tpw = (int)taps;
+        }
+    }
     if (b.lds_bytes > kMaxLdsBw) return b;
     // residue classes of the last row block that start beyond the map hold no pixel: skip them
     {
@@ -1298,7 +1317,7 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     }
     b.n_coltile = (s.Wo + PW - 1) / PW;
     b.n_ptile = (long)s.N * b.n_rowtile * b.n_coltile;
-    const long blocks = (long)b.n_fblk * b.n_cblk;
+    const long blocks = (long)(b.fb2 ? (b.n_fblk + 1) / 2 : b.n_fblk) * b.n_cblk;
     long S = 2048 / blocks;
     if (S > 256) S = 256;
     if (S > b.n_ptile / 4) S = b.n_ptile / 4;
@@ -1429,8 +1448,8 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     p.kh = s.kh; p.kw = kw_pass; p.d = s.d;
     p.Kp = b.Kp; p.Cp = b.Cp; p.xrows = b.xrows; p.xcols = b.xcols; p.xstride = b.xstride;
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
-    p.n_fblk = b.n_fblk; p.n_cblk = b.n_cblk;
-    const unsigned grid = (unsigned)(((long)b.n_fblk * b.n_cblk * b.S + kXcds - 1) / kXcds * kXcds);
+    p.n_fblk = b.fb2 ? (b.n_fblk + 1) / 2 : b.n_fblk; p.n_cblk = b.n_cblk;
+    const unsigned grid = (unsigned)(((long)p.n_fblk * b.n_cblk * b.S + kXcds - 1) / kXcds * kXcds);
 #define DSK_BW_LAUNCH(TPW, XR, RS, PF, PB)                                                                 \
     do {                                                                                               \
         if (in == DSK_F32) {                                                                           \
@@ -1458,6 +1477,17 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
         else if (b.bfm == 2 && b.tpw == 4) DSK_BFM_LAUNCH(4, 2);
         else if (b.bfm == 2) DSK_BFM_LAUNCH(7, 2);
 #undef DSK_BFM_LAUNCH
+        else if (b.fb2) {
+            if (in == DSK_F32) {
+                allow_lds(conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 0, 2>, b.lds_bytes);
+                conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 0, 2>
+                    <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+            } else {
+                allow_lds(conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 0, 2>, b.lds_bytes);
+                conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 0, 2>
+                    <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+            }
+        }
         else if (b.packb && b.xrows <= 8) DSK_BW_LAUNCH(2, 8, false, true, true);
         else if (b.packb) DSK_BW_LAUNCH(2, 10, false, true, true);
         else if (b.rowsplit && b.tpw == 1 && b.xrows <= 4) DSK_BW_LAUNCH(1, 4, true, true, false);

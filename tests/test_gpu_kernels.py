@@ -41,6 +41,7 @@ CONV_CASES = [
     (1, 20, 50, 61, 150, 1, 1, 1),     # 1x1 with three filter groups; pixel count not a multiple of 128
     (3, 70, 9, 13, 3, 1, 2, 0),        # 1x1, planes smaller than one wave's 128 pixels
     (1, 300, 20, 33, 2, 1, 1, 0),      # 1x1, more than 256 channels, two filters
+    (1, 40, 50, 70, 72, 3, 4, 1),      # 3x3 with three 32-filter blocks: two blocks per workgroup, one group half empty
 ]
 
 

@@ -728,7 +728,7 @@ struct BwParams {
 //   v_mfma_f32_32x32x16_bf16 contracts 16 consecutive pixels of a row, of which a lane supplies 8:
 //   one 16-byte LDS read when they are aligned to 8 pixels, else two 8-byte or four 4-byte reads.
 //   The matrix cores then have 1/16 of the work and the kernel runs at the speed of its staging.
-// FB = 2 (3x3 kernels in fp32): the workgroup owns TWO 32-filter blocks; waves 0/2 take the first
+// FB = 2 (3x3 kernels): the workgroup owns TWO 32-filter blocks; waves 0/2 take the first
 //   and waves 1/3 the second, and the two waves of a block divide the taps.  The x tile is then
 //   staged once per 64 filters, and a staged tile feeds 2.2 times as many matrix instructions
 //   as when every wave takes all nine taps of one tile row.
@@ -742,7 +742,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     // the same two tiles as bf16: row pitch of the dy tile DYB, of an x channel p.xstride (both
     // multiples of 8 elements and an odd number of 16-byte units, which spreads lanes over the banks)
     unsigned short *dyb = (unsigned short *)smem;
-    unsigned short *xb16 = (unsigned short *)smem + 32 * DYB;
+    unsigned short *xb16 = (unsigned short *)smem + FB * 32 * DYB;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -795,7 +795,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     // BFM: the maps have an even number of columns, so two neighbouring pixels are one aligned
     // 4-byte load and one 4-byte LDS write.  dy: filter wave+4i, row lane/16, pixel pair lane%16;
     // x: channel wave+4*ci, row 2k + lane/32, pixel pair lane%32.
-    unsigned drp[BFM ? 8 : 1];
+    unsigned drp[BFM ? 8 * FB : 1];
     unsigned xrp[BFM ? NCI : 1][BFM ? XR / 2 : 1];
 
     // Every tile starts inside both maps (the host enumerates only such tiles), so the tile's
@@ -830,7 +830,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             const unsigned dlo = st_dcol_ok && rl < st_nr_dy ? (unsigned)rl * dWo + 2u * jl : 0u;
             const BufRsrc rd = buf_rsrc(dyt, dy_end);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < 8 * FB; ++i) {
                 const int f = wave + 4 * i;
                 const unsigned so = f < nf_valid ? (unsigned)f * HoWo : 0u;
                 drp[i] = __builtin_amdgcn_raw_buffer_load_b32(rd, (int)(dlo * 2u), (int)(so * 2u), 0);
@@ -906,7 +906,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         if constexpr (BFM != 0) {
             const int rl = lane >> 4, jl = lane & 15, xl = lane >> 5, pl = lane & 31;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < 8 * FB; ++i) {
                 const int f = wave + 4 * i;
                 const bool ok = st_dcol_ok && f < nf_valid && rl < st_nr_dy;
                 *(unsigned *)(dyb + f * DYB + rl * PW + 2 * jl) = ok ? drp[i] : 0u;
@@ -950,7 +950,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         pt += p.S;
         if (BFM) {
             // ---- bf16 matrix cores: k index = 16 consecutive pixels of a row, 8 per lane
-            const unsigned short *ab = dyb + lo * DYB + 8 * hi;
+            const unsigned short *ab = dyb + (my_fb * 32 + lo) * DYB + 8 * hi;
             const unsigned short *bb = xb16 + blane + 8 * hi;
             for (int r = ROWSPLIT ? wave : 0; r < (ROWSPLIT ? wave + 1 : PH); ++r) {
 #pragma unroll
@@ -1277,7 +1277,7 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     b.bfm = 0;
     if (in == DSK_BF16 && !b.packb && s.kw > 1 && s.d % 2 == 0 && s.W % 2 == 0 && taps > 8 && taps <= 28 && s.kh <= 5)
         b.bfm = s.d % 8 == 0 ? 8 : s.d % 4 == 0 ? 4 : 2;
-    b.fb2 = !b.packb && !b.bfm && taps == 9 && s.K > 32;
+    b.fb2 = !b.packb && taps == 9 && s.K > 32;
     b.rowsplit = !b.packb && !b.bfm && !b.fb2 && (taps == 1 || taps == 9);
     b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.fb2 ? 5 : b.bfm ? (taps <= 12 ? 3 : taps <= 16 ? 4 : 7)
           : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
@@ -1299,9 +1299,13 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
         b.lds_bytes = 2 * ((size_t)32 * DYB + (size_t)32 * b.xstride);
     }
     if (b.fb2) {
-        const size_t two = 4 * ((size_t)64 * DY_STRIDE + (size_t)32 * b.xstride);
+        const size_t two = b.bfm ? 2 * ((size_t)64 * DYB + (size_t)32 * b.xstride)
+                                 : 4 * ((size_t)64 * DY_STRIDE + (size_t)32 * b.xstride);
         if (two <= kMaxLdsBw) {
             b.lds_bytes = two;
+        } else if (b.bfm) {
+            b.fb2 = false;
+            b.tpw = 3;
         } else {      // wide tap spacing: back to one block per workgroup, every wave all nine taps of a row
             b.fb2 = false;
             b.rowsplit = true;
@@ -1467,7 +1471,18 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
         p.col_shift = pass * s.d;      // the partial blocks are reused: the passes run one after the other
 #define DSK_BFM_LAUNCH(TPW, AL)                                                                        \
     conv_bwd_weight_mfma_kernel<bf16, TPW, 8, false, true, false, AL><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p)
-        if (b.bfm == 8 && b.tpw == 3) DSK_BFM_LAUNCH(3, 8);
+        if (b.bfm && b.fb2) {
+            allow_lds(conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 8, 2>, b.lds_bytes);
+            allow_lds(conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 4, 2>, b.lds_bytes);
+            allow_lds(conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 2, 2>, b.lds_bytes);
+            if (b.bfm == 8)
+                conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 8, 2><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+            else if (b.bfm == 4)
+                conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 4, 2><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+            else
+                conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 2, 2><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+        }
+        else if (b.bfm == 8 && b.tpw == 3) DSK_BFM_LAUNCH(3, 8);
         else if (b.bfm == 8 && b.tpw == 4) DSK_BFM_LAUNCH(4, 8);
         else if (b.bfm == 8) DSK_BFM_LAUNCH(7, 8);
         else if (b.bfm == 4 && b.tpw == 3) DSK_BFM_LAUNCH(3, 4);

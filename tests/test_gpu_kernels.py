@@ -172,6 +172,7 @@ BF16_CASES = [
     (2, 32, 40, 64, 33, 3, 8, 1),
     (1, 32, 60, 90, 40, 5, 4, 1),      # 25 taps 4 apart: a lane's 8 pixels come as two 8-byte LDS reads
     (1, 20, 40, 70, 36, 3, 4, 2),
+    (1, 32, 44, 60, 72, 3, 2, 1),      # three filter blocks, two per workgroup; 4-byte LDS reads
 ]
 
 

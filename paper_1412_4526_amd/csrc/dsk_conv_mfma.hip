@@ -1277,9 +1277,9 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     b.bfm = 0;
     if (in == DSK_BF16 && !b.packb && s.kw > 1 && s.d % 2 == 0 && s.W % 2 == 0 && taps > 8 && taps <= 28 && s.kh <= 5)
         b.bfm = s.d % 8 == 0 ? 8 : s.d % 4 == 0 ? 4 : 2;
-    b.fb2 = !b.packb && taps == 9 && s.K > 32;
+    b.fb2 = !b.packb && (taps == 9 || (b.bfm && taps == 16)) && s.K > 32;
     b.rowsplit = !b.packb && !b.bfm && !b.fb2 && (taps == 1 || taps == 9);
-    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.fb2 ? 5 : b.bfm ? (taps <= 12 ? 3 : taps <= 16 ? 4 : 7)
+    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.fb2 ? (taps == 9 ? 5 : 8) : b.bfm ? (taps <= 12 ? 3 : taps <= 16 ? 4 : 7)
           : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
     b.Kp = (s.K + 31) / 32 * 32;
     b.Cp = (s.C + 31) / 32 * 32;
@@ -1305,7 +1305,7 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
             b.lds_bytes = two;
         } else if (b.bfm) {
             b.fb2 = false;
-            b.tpw = 3;
+            b.tpw = taps == 9 ? 3 : 4;
         } else {      // wide tap spacing: back to one block per workgroup, every wave all nine taps of a row
             b.fb2 = false;
             b.rowsplit = true;
@@ -1471,17 +1471,19 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
         p.col_shift = pass * s.d;      // the partial blocks are reused: the passes run one after the other
 #define DSK_BFM_LAUNCH(TPW, AL)                                                                        \
     conv_bwd_weight_mfma_kernel<bf16, TPW, 8, false, true, false, AL><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p)
-        if (b.bfm && b.fb2) {
-            allow_lds(conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 8, 2>, b.lds_bytes);
-            allow_lds(conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 4, 2>, b.lds_bytes);
-            allow_lds(conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 2, 2>, b.lds_bytes);
-            if (b.bfm == 8)
-                conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 8, 2><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
-            else if (b.bfm == 4)
-                conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 4, 2><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
-            else
-                conv_bwd_weight_mfma_kernel<bf16, 5, 6, false, true, false, 2, 2><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
-        }
+#define DSK_BFM2_LAUNCH(TPW, XR, AL, PF)                                                                  \
+    do {                                                                                               \
+        allow_lds(conv_bwd_weight_mfma_kernel<bf16, TPW, XR, false, PF, false, AL, 2>, b.lds_bytes);     \
+        conv_bwd_weight_mfma_kernel<bf16, TPW, XR, false, PF, false, AL, 2>                              \
+            <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                      \
+    } while (0)
+        if (b.bfm == 8 && b.fb2 && b.tpw == 5) DSK_BFM2_LAUNCH(5, 6, 8, true);
+        else if (b.bfm == 4 && b.fb2 && b.tpw == 5) DSK_BFM2_LAUNCH(5, 6, 4, true);
+        else if (b.bfm == 2 && b.fb2 && b.tpw == 5) DSK_BFM2_LAUNCH(5, 6, 2, true);
+        else if (b.bfm == 8 && b.fb2) DSK_BFM2_LAUNCH(8, 8, 8, false);
+        else if (b.bfm == 4 && b.fb2) DSK_BFM2_LAUNCH(8, 8, 4, false);
+        else if (b.bfm == 2 && b.fb2) DSK_BFM2_LAUNCH(8, 8, 2, false);
+#undef DSK_BFM2_LAUNCH
         else if (b.bfm == 8 && b.tpw == 3) DSK_BFM_LAUNCH(3, 8);
         else if (b.bfm == 8 && b.tpw == 4) DSK_BFM_LAUNCH(4, 8);
         else if (b.bfm == 8) DSK_BFM_LAUNCH(7, 8);

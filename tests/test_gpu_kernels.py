@@ -222,6 +222,8 @@ POOL_CASES = [
     (1, 2, 9, 9, 2, 8),   # d larger than the output
     (1, 3, 100, 300, 8, 1), (1, 2, 90, 70, 8, 2), (2, 2, 50, 280, 4, 2),   # 8x8 and 4x4 windows over several tiles
     (1, 2, 40, 50, 5, 2), (1, 2, 30, 30, 6, 1),                            # window sizes without a tiled kernel
+    (1, 2, 24, 770, 2, 2), (1, 1, 20, 1026, 2, 2), (1, 2, 40, 600, 3, 2),  # pixel pairs; 128, 256 and 64 threads along a row
+    (1, 2, 30, 51, 8, 1), (2, 2, 33, 47, 8, 1), (1, 3, 21, 43, 4, 1), (1, 2, 26, 45, 4, 1), (1, 1, 70, 1063, 8, 1),  # d = 1: four pixels per thread
 ]
 
 
@@ -265,8 +267,11 @@ def test_avgpool_fwd_bwd(case):
     assert_close(dx, oracle_pool_bwd(x, k, d, False, dy), "avgpool dx")
 
 
-def test_pool_bf16():
-    N, C, H, W, k, d = 1, 4, 40, 150, 2, 2
+@pytest.mark.parametrize("case", [(1, 4, 40, 150, 2, 2), (1, 3, 30, 77, 2, 1), (1, 2, 40, 280, 3, 4), (1, 2, 50, 140, 8, 2),
+                                  (2, 2, 36, 90, 4, 2)], ids=lambda c: "N%dC%dH%dW%dk%dd%d" % c)
+def test_pool_bf16(case):
+    N, C, H, W, k, d = case
+    _say("pool bf16", case)
     rng = np.random.default_rng(3)
     x = bf16_round(rng.uniform(-1, 1, (N, C, H, W)))
     ry, ram = oracle_pool_fwd(x, k, d, True)
@@ -276,6 +281,13 @@ def test_pool_bf16():
     assert np.array_equal(to_np(y), ry) and np.array_equal(am.cpu().numpy().astype(np.int32), ram)
     ya = dsk.dsk_avgpool_fwd(_t(x, torch.bfloat16), k, d)
     assert_close(ya, oracle_pool_fwd(x, k, d, False)[0], "bf16 avgpool", bf16=True)
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    dy = bf16_round(rng.standard_normal((N, C, Ho, Wo)))
+    dx = dsk.dsk_maxpool_bwd(_t(dy, torch.bfloat16), am, k, d, H, W)
+    assert dx.dtype == torch.bfloat16
+    assert_close(dx, oracle_pool_bwd(x, k, d, True, dy), "bf16 maxpool dx", bf16=True)
+    dxa = dsk.dsk_avgpool_bwd(_t(dy, torch.bfloat16), k, d, H, W)
+    assert_close(dxa, oracle_pool_bwd(x, k, d, False, dy), "bf16 avgpool dx", bf16=True)
 
 
 @pytest.mark.parametrize("shape", [(1, 10, 40, 40), (2, 33, 37, 61), (1, 2, 50, 9), (3, 1, 5, 7)],

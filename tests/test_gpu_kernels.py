@@ -330,6 +330,34 @@ def test_pad_image_and_act_bwd():
         assert_close(gt, ref, "act_bwd %d" % act)
 
 
+@pytest.mark.parametrize("shape", [(2, 5, 12, 20), (1, 3, 9, 7), (1, 40, 64, 96), (2, 4, 50, 66)],
+                         ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_act_bwd_bias(shape, dt):
+    """Non-linearity backward fused with the bias gradient; planes that are and are not multiples of 4."""
+    _say("act_bwd_bias", shape, dt)
+    rng = np.random.default_rng(11)
+    y = rng.uniform(-1, 1, shape).astype(np.float32)
+    y[rng.random(shape) < 0.3] = 0.0
+    g = rng.standard_normal(shape).astype(np.float32)
+    bf = dt == torch.bfloat16
+    if bf:
+        y, g = bf16_round(y), bf16_round(g)
+    for act in (1, 2, 0):
+        f = (y > 0) if act == 1 else (1 - y.astype(np.float64) ** 2) if act == 2 else 1.0
+        ref = g * f
+        if bf:
+            ref = bf16_round(ref).astype(np.float64)      # the bias gradient sums what is stored
+        gt = _t(g.copy(), dt)
+        db = dsk.dsk_act_bwd_bias(_t(y, dt), gt, act)
+        torch.cuda.synchronize()
+        assert_close(gt, ref, "act_bwd_bias dy act %d" % act, bf16=bf)
+        assert_close(db, to_np(gt).sum(axis=(0, 2, 3)), "act_bwd_bias db act %d" % act)
+        gt2 = _t(g.copy(), dt)
+        dsk.dsk_act_bwd(_t(y, dt), gt2, act)
+        assert torch.equal(gt, gt2)
+
+
 def test_launch_errors_are_reported_not_raised_as_faults():
     """Shapes the kernels cannot take are refused with a status before any launch."""
     x = torch.zeros((1, 2, 8, 8), device=DEV)

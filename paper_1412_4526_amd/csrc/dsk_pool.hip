@@ -49,7 +49,8 @@ __device__ inline bool pool_decode(const PoolShape &s, int &plane, int &r0, int 
     b /= s.col_blocks;
     const int rb = (int)(b % s.row_blocks);
     plane = (int)(b / s.row_blocks);
-    const int rg = rb * (kPoolThreads >> s.cl_log2) + ((int)threadIdx.x >> s.cl_log2);   // uniform over a wave
+    // (a run is at least one wave long: the row group is uniform over a wave, and the compiler has to know)
+    const int rg = rb * (kPoolThreads >> s.cl_log2) + __builtin_amdgcn_readfirstlane((int)threadIdx.x >> s.cl_log2);
     const int grp = rg / s.d, res = rg % s.d;
     r0 = grp * s.d * R + res;
     col = ((cb << s.cl_log2) + ((int)threadIdx.x & ((1 << s.cl_log2) - 1))) * V;
@@ -438,6 +439,11 @@ __device__ __attribute__((always_inline)) inline void pool_span_bwd_row(const Po
 #pragma unroll
             for (int b = 0; b < K; ++b) acc[r][j] += !IS_MAX || tap[KP + j - b] == a * K + b ? gm[KP + j - b] : 0.f;
     }
+    // a row is finished before the next one starts: interleaved, the rows need every register of the SIMD
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < V; ++j) asm volatile("" : "+v"(acc[r][j]));
 }
 
 template <int K, int R, bool IS_MAX, int... Ts>
@@ -676,7 +682,7 @@ static int pool_fwd_dispatch(const void *x, void *y, uint8_t *am, int N, int C, 
                              hipStream_t st)
 {
     if (pool_span_ok(N, C, H, W, k, d, sizeof(T))) return pool_span_fwd<IS_MAX>(x, y, am, N, C, H, W, k, st);
-    // pairs pay where the instruction count binds: 2-byte pixels (fp32 kernels are HBM-bound either way)
+    // pairs pay where the instruction count binds: 2-byte pixels (fp32 kernels run as fast with one pixel per thread)
     return pool_pairs(W, d) && sizeof(T) == 2 ? pool_fwd_dispatch<T, IS_MAX, 2>(x, y, am, N, C, H, W, k, d, st)
                             : pool_fwd_dispatch<T, IS_MAX, 1>(x, y, am, N, C, H, W, k, d, st);
 }

@@ -173,6 +173,8 @@ BF16_CASES = [
     (1, 32, 60, 90, 40, 5, 4, 1),      # 25 taps 4 apart: a lane's 8 pixels come as two 8-byte LDS reads
     (1, 20, 40, 70, 36, 3, 4, 2),
     (1, 32, 44, 60, 72, 3, 2, 1),      # three filter blocks, two per workgroup; 4-byte LDS reads
+    (1, 16, 60, 110, 40, 3, 18, 0),    # tile too large for four-pixel items: pixel pairs
+    (1, 16, 30, 66, 33, 3, 1, 1),      # 66-column tiles: the last group of four is half outside
 ]
 
 

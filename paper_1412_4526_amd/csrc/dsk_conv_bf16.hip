@@ -40,6 +40,7 @@ struct GbParams {
     int n_items, n_wq;   // per thread and chunk: items, 16-byte weight pieces (LDS parts padded accordingly)
     int xs_bytes;
     int n_rowtile, n_coltile, n_fgrp;
+    int nrb, full_cls;   // row blocks of d*TH rows; residue classes that have a tile in the last one (the others: nrb-1 tiles)
     long tiles, per_xcd;
 };
 
@@ -91,7 +92,17 @@ gemm_conv_bf16_kernel(GbParams p)
     const int ct = (int)(tile % p.n_coltile); tile /= p.n_coltile;
     const int rt = (int)(tile % p.n_rowtile);
     const int n = (int)(tile / p.n_rowtile);
-    const int u0 = (rt / p.d) * p.d * TH + (rt % p.d);
+    // row tiles are numbered class by class, down the map within a class: tiles that follow each other
+    // (one XCD, the same time) share input rows; different residue classes share none
+    const int nf = p.full_cls * p.nrb;
+    int cls, rb;
+    if (rt < nf) {
+        cls = rt / p.nrb; rb = rt - cls * p.nrb;
+    } else {
+        const int q = (rt - nf) / (p.nrb - 1);
+        cls = p.full_cls + q; rb = rt - nf - q * (p.nrb - 1);
+    }
+    const int u0 = rb * p.d * TH + cls;
     const int v0 = ct * TW;
 
     const unsigned HW = (unsigned)(p.Hin * p.Win);
@@ -269,7 +280,7 @@ gemm_conv_bf16_kernel(GbParams p)
 
 struct GbPlan {
     bool ok;
-    int WM, TF, NC, rows, cols, n_pix, pp_row, n_items, n_wq, xs_bytes, n_fgrp, n_rowtile, n_coltile;
+    int WM, TF, NC, rows, cols, n_pix, pp_row, n_items, n_wq, xs_bytes, n_fgrp, n_rowtile, n_coltile, nrb, full_cls;
     bool pair;
     long tiles;
     size_t lds_bytes, wt_bytes;
@@ -315,6 +326,8 @@ static GbPlan gb_plan(int N, int Cin, int Win, int Fout, int Hout, int Wout, int
         const int nrb = (Hout + d * TH - 1) / (d * TH);
         const int last = Hout - (nrb - 1) * d * TH;
         g.n_rowtile = (nrb - 1) * d + (last < d ? last : d);
+        g.nrb = nrb;
+        g.full_cls = last < d ? last : d;
     }
     g.n_coltile = (Wout + TW - 1) / TW;
     g.tiles = (long)N * g.n_rowtile * g.n_coltile * g.n_fgrp;
@@ -343,7 +356,7 @@ static int gb_run(const void *in, void *out, const float *w, const float *bias, 
     p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.n_pix = g.n_pix; p.pp_row = g.pp_row; p.n_items = g.n_items;
     p.n_wq = g.n_wq;
     p.xs_bytes = g.xs_bytes;
-    p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp;
+    p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp; p.nrb = g.nrb; p.full_cls = g.full_cls;
     p.tiles = g.tiles;
     p.per_xcd = (g.tiles + kXcds - 1) / kXcds;
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;

@@ -59,6 +59,7 @@ struct GcParams {
     int xs_floats;       // Cc*chan_stride rounded up to a multiple of 256
     int n_xi, n_wi;      // per thread and chunk: input-tile floats, weight float4s (both LDS parts padded)
     int n_rowtile, n_coltile, n_fgrp;
+    int nrb, full_cls;   // row blocks of d*TH rows; residue classes that have a tile in the last one (the others: nrb-1 tiles)
     long tiles;          // N * n_rowtile * n_coltile * n_fgrp output tiles
     int rounds;          // persistent workgroups: whole tiles each of them takes first
     int rem_units;       // (tiles - rounds * n_wg) * NC: chunks of the tiles left after that
@@ -96,7 +97,18 @@ __device__ inline void gc_decode_tile(const GcParams &p, long tile, int &fg, int
     const int ct = (int)(tile % p.n_coltile); tile /= p.n_coltile;
     const int rt = (int)(tile % p.n_rowtile);
     n = (int)(tile / p.n_rowtile);
-    u0 = (rt / p.d) * p.d * TH + (rt % p.d);
+    // Row tiles are numbered class by class, down the map within a class: tiles that follow each other
+    // (and run on one XCD at the same time) then share input rows and columns.  Numbered row block by
+    // row block, neighbours would be different residue classes, which share no input row.
+    const int nf = p.full_cls * p.nrb;
+    int cls, rb;
+    if (rt < nf) {
+        cls = rt / p.nrb; rb = rt - cls * p.nrb;
+    } else {
+        const int q = (rt - nf) / (p.nrb - 1);
+        cls = p.full_cls + q; rb = rt - nf - q * (p.nrb - 1);
+    }
+    u0 = rb * p.d * TH + cls;
     v0 = ct * TW;
 }
 
@@ -377,7 +389,7 @@ static constexpr long kSlots = 512;   // workgroups resident at once: 2 per CU, 
 
 struct GcPlan {
     bool ok, split;      // split: persistent workgroups with split tiles
-    int TF, WM, Cc, Cpad, NC, rows, cols, chan_stride, xs_floats, n_xi, n_wi, n_fgrp, n_rowtile, n_coltile;
+    int TF, WM, Cc, Cpad, NC, rows, cols, chan_stride, xs_floats, n_xi, n_wi, n_fgrp, n_rowtile, n_coltile, nrb, full_cls;
     int XI;              // kXI or kXIBig: which set of kernels
     long tiles, n_wg;
     int rounds, rem_units;
@@ -426,6 +438,8 @@ static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
         const int nrb = (Hout + d * TH - 1) / (d * TH);
         const int last = Hout - (nrb - 1) * d * TH;
         g.n_rowtile = (nrb - 1) * d + (last < d ? last : d);
+        g.nrb = nrb;
+        g.full_cls = last < d ? last : d;
     }
     g.n_coltile = (Wout + TW - 1) / TW;
     g.tiles = (long)N * g.n_rowtile * g.n_coltile * g.n_fgrp;
@@ -496,7 +510,7 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     p.act = act;
     p.Cpad = g.Cpad; p.Cc = g.Cc; p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.chan_stride = g.chan_stride;
     p.xs_floats = g.xs_floats; p.n_xi = g.n_xi; p.n_wi = g.n_wi;
-    p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp;
+    p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp; p.nrb = g.nrb; p.full_cls = g.full_cls;
     p.tiles = g.tiles; p.rounds = g.rounds; p.rem_units = g.rem_units; p.n_wg = g.n_wg;
     p.per_xcd = (p.n_wg + kXcds - 1) / kXcds;
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;

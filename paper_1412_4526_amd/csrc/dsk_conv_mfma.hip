@@ -56,6 +56,7 @@ struct GcParams {
     int Cpad, Cc, NC;    // padded channel count, channels per LDS chunk (even), chunks per tile
     int rows, cols;      // LDS tile: TH+kh-1 by TW+(kw-1)*d
     int chan_stride;     // rows*cols
+    unsigned m_cs, m_cols;   // 2^32 / chan_stride + 1 and 2^32 / cols + 1: e / x = mulhi(e, m) for the small e of the tile index
     int xs_floats;       // Cc*chan_stride rounded up to a multiple of 256
     int n_xi, n_wi;      // per thread and chunk: input-tile floats, weight float4s (both LDS parts padded)
     int n_rowtile, n_coltile, n_fgrp;
@@ -228,8 +229,9 @@ gemm_conv_kernel(GcParams p)
 #pragma unroll
             for (int i = 0; i < XI; ++i) {
                 const int e = tid + i * kThreads;
-                const int c = e / p.chan_stride, rem = e - c * p.chan_stride;
-                const int r = rem / p.cols, col = rem - r * p.cols;
+                // (exact: e * chan_stride and rem * cols stay below 2^32; a division costs some 40 instructions)
+                const int c = (int)__umulhi((unsigned)e, p.m_cs), rem = e - c * p.chan_stride;
+                const int r = (int)__umulhi((unsigned)rem, p.m_cols), col = rem - r * p.cols;
                 const int irow = row0 + r * p.d, icol = col0 + col;
                 const bool ok = e < n_x && irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win;
                 voff[i] = ok ? (unsigned)c * HW + (unsigned)(irow * p.Win + icol) : 0u;
@@ -261,8 +263,8 @@ gemm_conv_kernel(GcParams p)
 #pragma unroll
                 for (int i = 0; i < XI; ++i) {
                     unsigned v = voff[i];
-                    const unsigned cl = v / HW;
-                    v -= c0 + (int)cl >= p.Cin ? cl * HW : 0u;
+                    const unsigned cl = __umulhi((unsigned)(tid + i * kThreads), p.m_cs);      // the element's channel
+                    v -= !((zero >> i) & 1u) && c0 + (int)cl >= p.Cin ? cl * HW : 0u;
                     xv[i] = buf_ld(rx, src, v, 0u);
                 }
             }
@@ -447,8 +449,15 @@ static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
     // one-tile-per-workgroup launch leaves S - (T mod S) slots idle.  When that costs more than
     // a few per cent, S persistent workgroups take T/S whole tiles each and share the channel
     // chunks of the remaining T mod S tiles evenly.
+    // The same machinery fills the chip when there are fewer tiles than slots (small maps): with no whole
+    // round, the S workgroups share the channel chunks of ALL tiles (a share is then shorter than a tile,
+    // so it still meets two tiles at most).
     // (NC <= 4096 keeps the 32-bit chunk arithmetic of the kernels exact)
-    g.split = g.tiles > kSlots && g.tiles < 12 * kSlots && g.tiles % kSlots != 0 && g.NC <= 4096 && g.XI == kXI;
+    const bool tail = g.tiles > kSlots && g.tiles < 12 * kSlots && g.tiles % kSlots != 0;
+    // (tiles of at least four chunks: a piece costs a 64-128 KB round trip through the workspace, which two
+    // chunks of a 3-channel layer do not repay)
+    const bool few = g.tiles <= kSlots * 3 / 4 && g.NC >= 4 && g.tiles * g.NC >= kSlots / 2;
+    g.split = (tail || few) && g.NC <= 4096 && g.XI == kXI;
     if (g.split) {
         g.n_wg = kSlots;
         g.rounds = (int)(g.tiles / g.n_wg);
@@ -511,6 +520,8 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     p.Cpad = g.Cpad; p.Cc = g.Cc; p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.chan_stride = g.chan_stride;
     p.xs_floats = g.xs_floats; p.n_xi = g.n_xi; p.n_wi = g.n_wi;
     p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp; p.nrb = g.nrb; p.full_cls = g.full_cls;
+    p.m_cs = (unsigned)((1ull << 32) / (unsigned)g.chan_stride + 1);
+    p.m_cols = (unsigned)((1ull << 32) / (unsigned)g.cols + 1);
     p.tiles = g.tiles; p.rounds = g.rounds; p.rem_units = g.rem_units; p.n_wg = g.n_wg;
     p.per_xcd = (p.n_wg + kXcds - 1) / kXcds;
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;

@@ -110,6 +110,9 @@ SPLIT_CASES = [
     (1, 24, 826, 322, 32, 3, 1, 1),    # fwd: 515 tiles, 3 left over, fewer chunks than workgroups
     (2, 16, 300, 400, 40, 3, 2, 1),    # fwd: 532 tiles of 2 chunks
     (1, 24, 500, 700, 16, 3, 1, 0),    # fwd: 693 tiles of 3 chunks, 181 left over
+    (1, 48, 200, 200, 40, 3, 2, 1),    # fewer tiles than workgroups (104 of 6 chunks): every tile is shared
+    (2, 20, 90, 150, 70, 4, 4, 1),     # the same with two filter groups and a ragged last chunk
+    (1, 32, 120, 260, 33, 2, 1, 0),    # 4 chunks per tile
 ]
 
 

@@ -385,7 +385,7 @@ gc_fixup_kernel(GcParams p)
 }
 
 static constexpr int kXI = 16;   // input-tile elements per thread per chunk, at most
-static constexpr int kXIBig = 24;   // the same for tiles with a large halo (second set of kernels, never split)
+static constexpr int kXIBig = 24;   // the same for tiles with a large halo (second set of kernels)
 static constexpr int kWI = 8;    // weight float4s per thread per chunk, at most
 static constexpr long kSlots = 512;   // workgroups resident at once: 2 per CU, 256 CUs
 
@@ -457,7 +457,7 @@ static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
     // (tiles of at least four chunks: a piece costs a 64-128 KB round trip through the workspace, which two
     // chunks of a 3-channel layer do not repay)
     const bool few = g.tiles <= kSlots * 3 / 4 && g.NC >= 4 && g.tiles * g.NC >= kSlots / 2;
-    g.split = (tail || few) && g.NC <= 4096 && g.XI == kXI;
+    g.split = (tail || few) && g.NC <= 4096;
     if (g.split) {
         g.n_wg = kSlots;
         g.rounds = (int)(g.tiles / g.n_wg);
@@ -477,8 +477,12 @@ template <typename TI, typename TO>
 static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
 {
     const unsigned grid = (unsigned)(p.per_xcd * kXcds);
-    if (g.XI == kXIBig && g.WM == 2)
+    if (g.XI == kXIBig && g.WM == 2 && g.split)
+        gemm_conv_kernel<TI, TO, 2, kXIBig, kWI, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    else if (g.XI == kXIBig && g.WM == 2)
         gemm_conv_kernel<TI, TO, 2, kXIBig, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    else if (g.XI == kXIBig && g.split)
+        gemm_conv_kernel<TI, TO, 1, kXIBig, kWI, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.XI == kXIBig)
         gemm_conv_kernel<TI, TO, 1, kXIBig, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.WM == 2 && g.split)

@@ -113,6 +113,8 @@ SPLIT_CASES = [
     (1, 48, 200, 200, 40, 3, 2, 1),    # fewer tiles than workgroups (104 of 6 chunks): every tile is shared
     (2, 20, 90, 150, 70, 4, 4, 1),     # the same with two filter groups and a ragged last chunk
     (1, 32, 120, 260, 33, 2, 1, 0),    # 4 chunks per tile
+    (1, 20, 300, 300, 32, 7, 16, 0),   # large-halo kernels (two channels per chunk), 32-filter tiles
+    (1, 16, 280, 280, 48, 7, 16, 1),   # ... and 64-filter tiles
 ]
 
 

@@ -732,7 +732,8 @@ struct BwParams {
     const void *x, *dy;
     float *part;         // [split][taps][Kp][Cp]
     int N, C, H, W, K, Ho, Wo, kh, kw, d;
-    int col_shift;       // x is read this many columns to the right (one tap column of a wide kernel at a time)
+    int n_pass;          // > 1: a wide kernel is taken one tap column at a time; pass b reads x b*d columns to the right
+    long pass_stride;    // floats of `part` per pass
     int Kp, Cp;          // padded to 32
     int xrows, xcols, xstride;   // x tile: PH+kh-1 by PW+(kw-1)*d, channel stride odd
     int n_rowtile, n_coltile;    // pixel tiles per image
@@ -782,13 +783,16 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     // All (filter block, channel block) workgroups of one pixel share are neighbours in the
     // logical order and, through the XCD-aware mapping, run on the same XCD at the same time:
     // the x tiles are then fetched from HBM once, not once per filter block (and dy likewise).
-    const int nblk = p.n_fblk * p.n_cblk * p.S;
+    // The tap-column passes of one pixel share are neighbours too: their x tiles overlap.
+    const int nblk = p.n_fblk * p.n_cblk * p.S * p.n_pass;
     const int per_xcd = (nblk + kXcds - 1) / kXcds;
     int b = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
     if (b >= nblk) return;
     const int fb = b % p.n_fblk; b /= p.n_fblk;      // n_fblk counts groups of FB filter blocks
-    const int cb = b % p.n_cblk;
-    const int s = b / p.n_cblk;
+    const int cb = b % p.n_cblk; b /= p.n_cblk;
+    const int pass = b % p.n_pass;
+    const int s = b / p.n_pass;
+    const int col_shift = pass * p.d;
     const int f_base = fb * 32 * FB;
     const int my_fb = FB == 2 ? wave & 1 : 0;                                   // this wave's block of the group
     const int tap0 = FB == 2 ? wave >> 1 : wave, tap_step = FB == 2 ? 2 : 4;    // its taps: tap0, tap0 + tap_step, ...
@@ -846,14 +850,14 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         const int u0 = (rt / p.d) * p.d * PH + (rt % p.d);
         const int v0 = ct * PW;
         const TI *dyt = dy + (((long)n * p.K + f_base) * p.Ho + u0) * p.Wo + v0;
-        const TI *xt = x + (((long)n * p.C + cb * 32) * p.H + u0) * p.W + v0 + p.col_shift;
+        const TI *xt = x + (((long)n * p.C + cb * 32) * p.H + u0) * p.W + v0 + col_shift;
         if constexpr (BFM != 0) {
             st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;
             st_nr_x = (p.H - u0 + p.d - 1) / p.d;
             st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
             const int rl = lane >> 4, jl = lane & 15, xl = lane >> 5, pl = lane & 31;
             st_dcol_ok = v0 + 2 * jl < p.Wo;
-            st_col_ok = 2 * pl < p.xcols && v0 + 2 * pl + p.col_shift < p.W;
+            st_col_ok = 2 * pl < p.xcols && v0 + 2 * pl + col_shift < p.W;
             // offsets in elements; rows, filters and channels that do not exist are read from the
             // tile's first element instead (a valid address) and become zeros at the LDS write
             const unsigned dlo = st_dcol_ok && rl < st_nr_dy ? (unsigned)rl * dWo + 2u * jl : 0u;
@@ -880,7 +884,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         // dy: segment i of this wave is filter f_i, rows r_i (lanes 0-31) and r_i+1 (lanes 32-63)
         st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;           // dy rows u0 + r*d that exist (>= 1)
         st_dcol_ok = v0 + lo < p.Wo;
-        st_col_ok = lane < p.xcols && v0 + lane + p.col_shift < p.W;
+        st_col_ok = lane < p.xcols && v0 + lane + col_shift < p.W;
         const unsigned xlane_off = st_col_ok ? (unsigned)lane : 0u;
         st_nr_x = (p.H - u0 + p.d - 1) / p.d;             // x rows u0 + r*d that exist
         st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
@@ -1027,7 +1031,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 
     // ---- partial block out: part[split][tap][f][c]; lane = channel, registers = filters
     const long split = ROWSPLIT ? (long)s * 4 + wave : s;
-    float *part = p.part + split * p.Kp * p.Cp * taps;
+    float *part = p.part + pass * p.pass_stride + split * p.Kp * p.Cp * taps;
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
         const int tap = ROWSPLIT ? t : tap0 + tap_step * t;
@@ -1071,8 +1075,11 @@ __device__ inline float bw_reduce_sum(const float *__restrict__ src, long stride
 
 __global__ void __launch_bounds__(kThreads)
 bw_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int taps, int Kp, int Cp, int S,
-                 int taps_dw, int tap_stride, int tap_first)
+                 int taps_dw, int tap_stride, long pass_stride)
 {
+    // blockIdx.y: tap-column pass of a wide kernel (its blocks start pass_stride floats further on)
+    part += blockIdx.y * pass_stride;
+    const int tap_first = (int)blockIdx.y;
     __shared__ float red[kThreads];
     const long total = (long)K * C * taps;
     const long idx = (long)blockIdx.x * kRedOut + threadIdx.x % kRedOut;
@@ -1373,6 +1380,8 @@ static BwPlan bw_plan(const ConvShape &s, dsk_dtype in)
     c.kw = 1;                      // Wo stays that of the whole kernel
     b = bw_plan_one(c, false, in);
     b.col_passes = s.kw;
+    // all passes run in one launch: each has its own partial blocks
+    b.part_bytes = 4 * ((size_t)b.n_part * b.Kp * b.Cp * s.kh * s.kw + (size_t)s.K * kBiasSplit);
     return b;
 }
 
@@ -1482,7 +1491,9 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     p.Kp = b.Kp; p.Cp = b.Cp; p.xrows = b.xrows; p.xcols = b.xcols; p.xstride = b.xstride;
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
     p.n_fblk = b.fb2 ? (b.n_fblk + 1) / 2 : b.n_fblk; p.n_cblk = b.n_cblk;
-    const unsigned grid = (unsigned)(((long)p.n_fblk * b.n_cblk * b.S + kXcds - 1) / kXcds * kXcds);
+    p.n_pass = b.col_passes;
+    p.pass_stride = (long)b.n_part * b.Kp * b.Cp * taps;
+    const unsigned grid = (unsigned)(((long)p.n_fblk * b.n_cblk * b.S * b.col_passes + kXcds - 1) / kXcds * kXcds);
 #define DSK_BW_LAUNCH(TPW, XR, RS, PF, PB)                                                                 \
     do {                                                                                               \
         if (in == DSK_F32) {                                                                           \
@@ -1496,8 +1507,7 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
         }                                                                                              \
     } while (0)
     int rc = DSK_OK;
-    for (int pass = 0; pass < b.col_passes; ++pass) {
-        p.col_shift = pass * s.d;      // the partial blocks are reused: the passes run one after the other
+    {
 #define DSK_BFM_LAUNCH(TPW, AL)                                                                        \
     conv_bwd_weight_mfma_kernel<bf16, TPW, 8, false, true, false, AL><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p)
 #define DSK_BFM2_LAUNCH(TPW, XR, AL, PF)                                                                  \
@@ -1552,14 +1562,14 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
             bw_reduce_packb_kernel<<<dim3((unsigned)((total + kRedOut - 1) / kRedOut)), dim3(kThreads), 0, st>>>(
                 (const float *)ws, dw, s.K, s.C, s.kh, s.kw, b.Kp, b.n_part);
         else
-            bw_reduce_kernel<<<dim3((unsigned)((total + kRedOut - 1) / kRedOut)), dim3(kThreads), 0, st>>>(
+            bw_reduce_kernel<<<dim3((unsigned)((total + kRedOut - 1) / kRedOut), (unsigned)b.col_passes), dim3(kThreads), 0, st>>>(
                 (const float *)ws, dw, s.K, s.C, taps, b.Kp, b.Cp, b.n_part, s.kh * s.kw,
-                b.col_passes > 1 ? s.kw : 1, pass);
+                b.col_passes > 1 ? s.kw : 1, p.pass_stride);
     }
 #undef DSK_BW_LAUNCH
     rc = check_launch();
     if (rc != DSK_OK || !db) return rc;
-    float *bpart = (float *)ws + (size_t)b.n_part * b.Kp * b.Cp * (b.packb ? s.kh : taps);
+    float *bpart = (float *)ws + (size_t)b.n_part * b.Kp * b.Cp * (b.packb ? s.kh : taps) * b.col_passes;
     if (in == DSK_F32)
         bias_partial_kernel<float><<<dim3(s.K * kBiasSplit), dim3(kThreads), 0, st>>>((const float *)dy, bpart, s.N,
                                                                                     s.K, (long)s.Ho * s.Wo);

@@ -163,6 +163,9 @@ __device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][4]
 // written as raw accumulators to `partial`, and gc_fixup_kernel adds the pieces of every
 // left-over tile in a fixed order and applies the epilogue.
 //
+// With fewer tiles than workgroups (small maps) `rounds` is 0 and the workgroups share the chunks of all
+// tiles.
+//
 // Pipeline: the global loads of chunk t+1 are issued before the matrix cores start on chunk
 // t and land in registers meanwhile; they are written to LDS after chunk t is done.
 template <typename TI, typename TO, int WM, int XI, int WI, bool SPLIT>

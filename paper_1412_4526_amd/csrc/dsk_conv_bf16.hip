@@ -253,6 +253,22 @@ gemm_conv_bf16_kernel(GbParams p)
     const long plane = (long)p.Hout * p.Wout;
     TO *out_n = (TO *)p.out + ((long)n * p.Fout + (long)fg * TF) * plane;
     const int f_left = p.Fout - fg * TF;
+    // The biases of this lane's filters, fetched together BEFORE the first store: loaded where they
+    // are used, each load is waited for on the spot (it may not pass the stores before it), one
+    // memory round trip per output.  Filters beyond Fout read zero through the descriptor's range.
+    float bv[WM][16];
+    {
+        const BufRsrc rb = buf_rsrc(p.bias, p.bias + (p.bias ? p.Fout : 0));
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                bv[wm][i] = buf_ld(rb, p.bias, (unsigned)(fg * TF + wm * 32 + 8 * (i / 4) + (i % 4) + 4 * hi), 0u);
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(bv[wm][i]));
+    }
 #pragma unroll
     for (int wn = 0; wn < 4; ++wn) {
         const int row = u0 + (2 * wave + (wn >> 1)) * p.d;
@@ -264,15 +280,7 @@ gemm_conv_bf16_kernel(GbParams p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int fl = wm * 32 + 8 * (i / 4) + (i % 4);
-                if (fl + 4 * hi < f_left) {
-                    float v = acc[wm][wn][i];
-                    if (p.bias) {
-                        const float b0 = p.bias[fg * TF + fl];
-                        const float b1 = fl + 4 < f_left ? p.bias[fg * TF + fl + 4] : 0.f;
-                        v += hi ? b1 : b0;
-                    }
-                    stf(o, (long)fl * plane, act_apply(p.act, v));
-                }
+                if (fl + 4 * hi < f_left) stf(o, (long)fl * plane, act_apply(p.act, acc[wm][wn][i] + bv[wm][i]));
             }
         }
     }

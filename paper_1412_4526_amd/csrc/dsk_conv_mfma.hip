@@ -124,6 +124,23 @@ __device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][4]
     const long plane = (long)p.Hout * p.Wout;
     TO *out_n = (TO *)p.out + ((long)n * p.Fout + (long)fg * TF) * plane;
     const int f_left = p.Fout - fg * TF;      // filters of this group that exist
+    // The biases of this lane's filters, fetched together BEFORE the first store.  Loaded where
+    // they are used, each load has to be waited for on the spot (it may not pass the stores
+    // before it: `out` could alias `bias`), and a tile's 64-128 outputs per lane then cost as
+    // many memory round trips.  Filters beyond Fout read zero through the descriptor's range.
+    float bv[WM][16];
+    {
+        const BufRsrc rb = buf_rsrc(p.bias, p.bias + (p.bias ? p.Fout : 0));
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                bv[wm][i] = buf_ld(rb, p.bias, (unsigned)(fg * TF + wm * 32 + 8 * (i / 4) + (i % 4) + 4 * hi), 0u);
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(bv[wm][i]));
+    }
 #pragma unroll
     for (int wn = 0; wn < 4; ++wn) {
         const int row = u0 + (2 * wave + (wn >> 1)) * p.d;
@@ -135,15 +152,7 @@ __device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][4]
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int fl = wm * 32 + 8 * (i / 4) + (i % 4);      // filter of the hi = 0 lanes
-                if (fl + 4 * hi < f_left) {
-                    float v = acc[wm][wn][i];
-                    if (p.bias) {
-                        const float b0 = p.bias[fg * TF + fl];
-                        const float b1 = fl + 4 < f_left ? p.bias[fg * TF + fl + 4] : 0.f;
-                        v += hi ? b1 : b0;
-                    }
-                    stf(o, (long)fl * plane, act_apply(p.act, v));
-                }
+                if (fl + 4 * hi < f_left) stf(o, (long)fl * plane, act_apply(p.act, acc[wm][wn][i] + bv[wm][i]));
             }
         }
     }
@@ -374,16 +383,23 @@ gc_fixup_kernel(GcParams p)
     const int col = v0 + (wn & 1) * 32 + lo;
     if (row >= p.Hout || col >= p.Wout) return;
     TO *out = (TO *)p.out;
+    // the biases are fetched together before the first store (see gc_epilogue); beyond Fout they read zero
+    float bv[kFixRows];
+    {
+        const BufRsrc rb = buf_rsrc(p.bias, p.bias + (p.bias ? p.Fout : 0));
+#pragma unroll
+        for (int r = 0; r < kFixRows; ++r) {
+            const int i = i0 + r;
+            bv[r] = buf_ld(rb, p.bias, (unsigned)(fg * TF + wm * 32 + 8 * (i / 4) + 4 * hi + (i % 4)), 0u);
+        }
+#pragma unroll
+        for (int r = 0; r < kFixRows; ++r) asm volatile("" : "+v"(bv[r]));
+    }
 #pragma unroll
     for (int r = 0; r < kFixRows; ++r) {
         const int i = i0 + r;
         const int f = fg * TF + wm * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
-        if (f < p.Fout) {
-            float v = acc[r];
-            if (p.bias) v += p.bias[f];
-            v = act_apply(p.act, v);
-            stf(out, (((long)n * p.Fout + f) * p.Hout + row) * p.Wout + col, v);
-        }
+        if (f < p.Fout) stf(out, (((long)n * p.Fout + f) * p.Hout + row) * p.Wout + col, act_apply(p.act, acc[r] + bv[r]));
     }
 }
 
@@ -626,6 +642,20 @@ pw_conv_kernel(PwParams p)
         // bias, non-linearity, store (register i of a lane: filter 8*(i/4) + i%4 + 4*hi of its block)
         TO *out_n = (TO *)p.out + ((long)n * p.Fout + (long)fg * TF) * p.HW;
         const int f_left = p.Fout - fg * TF;
+        // this lane's biases, fetched together before the first store (see gc_epilogue)
+        float bv[WM][16];
+        {
+            const BufRsrc rb = buf_rsrc(p.bias, p.bias + (p.bias ? p.Fout : 0));
+#pragma unroll
+            for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    bv[wm][i] = buf_ld(rb, p.bias, (unsigned)(fg * TF + wm * 32 + 8 * (i / 4) + (i % 4) + 4 * hi), 0u);
+#pragma unroll
+            for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(bv[wm][i]));
+        }
 #pragma unroll
         for (int wn = 0; wn < 4; ++wn) {
             const unsigned q = q0 + 32u * wn + lo;
@@ -636,15 +666,7 @@ pw_conv_kernel(PwParams p)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int fl = wm * 32 + 8 * (i / 4) + (i % 4);
-                    if (fl + 4 * hi < f_left) {
-                        float v = acc[wm][wn][i];
-                        if (p.bias) {
-                            const float b0 = p.bias[fg * TF + fl];
-                            const float b1 = fl + 4 < f_left ? p.bias[fg * TF + fl + 4] : 0.f;
-                            v += hi ? b1 : b0;
-                        }
-                        stf(o, (long)fl * p.HW, act_apply(p.act, v));
-                    }
+                    if (fl + 4 * hi < f_left) stf(o, (long)fl * p.HW, act_apply(p.act, acc[wm][wn][i] + bv[wm][i]));
                 }
         }
     }

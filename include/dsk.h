@@ -24,8 +24,9 @@
  *     accumulated in fp32, weights are rounded to bf16 inside the kernel).
  *   - Arguments are validated before anything is launched, so every error below
  *     except DSK_ELAUNCH is returned without touching the GPU.  No exceptions
- *     cross this boundary; apart from the diagnostic switch dsk_set_conv_algo the
- *     library keeps no state and calls are re-entrant.
+ *     cross this boundary.  Calls are re-entrant: the library keeps no state
+ *     between calls apart from the calling thread's diagnostic switch
+ *     dsk_set_conv_algo.
  *   - Return value: DSK_OK (0) or a negative dsk_status.
  */
 #ifndef DSK_H
@@ -189,7 +190,9 @@ size_t dsk_softmax_xent_workspace_bytes(int N, int Cls, int H, int W);
  *   loss[0] = -(1/count) * sum_{mask != 0} log p[label]        (0 if count == 0)
  *   dscores = (mask != 0) * (p - onehot(label)) / count        (0 if count == 0)
  *             [N][Cls][H][W], stored in type `dt` (the arithmetic is fp32 either way)
- * Errors of unchosen pixels are exactly zero; cost does not depend on the mask.
+ * Errors of unchosen pixels are exactly zero (they are written without their
+ * scores being read, so the call gets a little cheaper as the mask gets sparser;
+ * everything after it in the backward pass is dense, Sec. 4.3).
  * A label outside [0, Cls) at a chosen pixel is the caller's error (the pixel
  * then contributes p as its error and nothing to the loss).  loss: 1 device float. */
 int dsk_masked_softmax_xent(const float *scores, const int32_t *labels, const uint8_t *mask,
@@ -203,7 +206,8 @@ int dsk_masked_softmax_xent(const float *scores, const int32_t *labels, const ui
 /* 0 = automatic (matrix-core kernels where they apply), 1 = force the plain
  * one-thread-per-output kernels, 2 = automatic but bf16 maps are multiplied on the
  * fp32 matrix path (converted while they are staged) instead of the bf16 one.
- * Process-wide; returns the previous value. */
+ * Applies to the calling thread's later calls only; returns the previous value
+ * (an invalid argument changes nothing). */
 int dsk_set_conv_algo(int algo);
 
 #ifdef __cplusplus

@@ -10,5 +10,5 @@ this package.  It shares no code with the HIP path and imports nothing from it.
 """
 from .scan import (build, pad_image, pack_params, unpack_params, patch_forward,  # noqa: F401
                    STORE_EXACT, STORE_BF16,
-                   scan_forward, scan_backward, num_threads, geometry)
+                   scan_forward, scan_forward_maps, scan_backward, num_threads, geometry)
 from .loss import masked_softmax_xent  # noqa: F401

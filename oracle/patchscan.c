@@ -145,20 +145,12 @@ static void round_map(double *p, long count, int storage)
 /* Forward of the original CNN on one patch.  acts[act_off[0]...] must already
  * hold the patch (C0 x n x n).  Fills every later map; amax gets, at the same
  * offsets as the map it belongs to, the winning tap index of each max-pool
- * output (other entries untouched).
- *
- * margin (may be NULL) receives how far the patch is from the nearest point
- * where its gradient is discontinuous, relative to the size of the values
- * involved: the minimum over ReLU units of |pre-activation| / max|pre-activation
- * of that layer|, and over max-pool windows of (winner - best different-valued
- * other tap) / max|input of that layer|.  Exact zeros and exact ties (zero
- * padding, ReLU outputs) are decided the same way in any precision and do not
- * count.  Tests use it to keep away from inputs
- * on which two correct finite-precision evaluations may decide differently. */
+ * output (other entries untouched).  pre (may be NULL) gets, at the offsets of
+ * each conv layer's output map, the value BEFORE the non-linearity (bias
+ * included); entries of other maps are untouched. */
 static void patch_forward(const orc_layer *L, const orc_geom *g, const double *params,
-                          double *acts, int *amax, int storage, double *margin)
+                          double *acts, int *amax, int storage, double *pre)
 {
-    double worst = 1.0;
     round_map(acts + g->act_off[0], g->act_off[1] - g->act_off[0], storage);
     for (int l = 0; l < g->nL; ++l) {
         const int Ci = g->C[l], mi = g->m[l], Co = g->C[l + 1], mo = g->m[l + 1];
@@ -168,7 +160,7 @@ static void patch_forward(const orc_layer *L, const orc_geom *g, const double *p
         if (L[l].kind == ORC_CONV) {
             const double *w = params + g->par_off[l];
             const double *b = w + (long)Co * Ci * k * k;
-            double zmax = 0.0, zmin = INFINITY;
+            double *z = pre ? pre + g->act_off[l + 1] : NULL;
             for (int f = 0; f < Co; ++f)
                 for (int u = 0; u < mo; ++u)
                     for (int v = 0; v < mo; ++v) {
@@ -179,15 +171,10 @@ static void patch_forward(const orc_layer *L, const orc_geom *g, const double *p
                                     acc += w[(((long)f * Ci + c) * k + a) * k + bb] *
                                            x[((long)c * mi + (u * s + a)) * mi + (v * s + bb)];
                         y[((long)f * mo + u) * mo + v] = act_apply(L[l].act, acc);
-                        if (fabs(acc) > zmax) zmax = fabs(acc);
-                        if (acc != 0.0 && fabs(acc) < zmin) zmin = fabs(acc);
+                        if (z) z[((long)f * mo + u) * mo + v] = acc;
                     }
-            if (L[l].act == ORC_ACT_RELU && zmax > 0.0 && zmin / zmax < worst) worst = zmin / zmax;
         } else if (L[l].kind == ORC_MAXPOOL) {
             int *am = amax ? amax + g->act_off[l + 1] : NULL;
-            double xmax = 0.0, gapmin = INFINITY;
-            for (long t = 0; t < (long)Ci * mi * mi; ++t)
-                if (fabs(x[t]) > xmax) xmax = fabs(x[t]);
             for (int c = 0; c < Ci; ++c)
                 for (int u = 0; u < mo; ++u)
                     for (int v = 0; v < mo; ++v) {
@@ -200,14 +187,7 @@ static void patch_forward(const orc_layer *L, const orc_geom *g, const double *p
                             }
                         y[((long)c * mo + u) * mo + v] = best;
                         if (am) am[((long)c * mo + u) * mo + v] = bi;
-                        if (margin)
-                            for (int a = 0; a < k; ++a)
-                                for (int bb = 0; bb < k; ++bb) {
-                                    double t = x[((long)c * mi + (u * s + a)) * mi + (v * s + bb)];
-                                    if (t != best && best - t < gapmin) gapmin = best - t;
-                                }
                     }
-            if (xmax > 0.0 && gapmin / xmax < worst) worst = gapmin / xmax;
         } else { /* ORC_AVGPOOL */
             for (int c = 0; c < Ci; ++c)
                 for (int u = 0; u < mo; ++u)
@@ -221,7 +201,6 @@ static void patch_forward(const orc_layer *L, const orc_geom *g, const double *p
         }
         if (l + 1 < g->nL) round_map(y, (long)Co * mo * mo, storage);
     }
-    if (margin) *margin = worst;
 }
 
 /* Textbook backward of the original CNN on one patch.  grads holds, at the
@@ -290,15 +269,16 @@ static void crop_patch(const double *xpad, int C0, int Hp, int Wp, int n,
 }
 
 /* One patch, all intermediates (for layer-by-layer checks).  patch: C0*n*n.
- * acts: orc_sizes().act_total doubles; amax: same count of ints (may be NULL). */
+ * acts: orc_sizes().act_total doubles; amax: same count of ints (may be NULL);
+ * pre: same count of doubles (may be NULL), see patch_forward. */
 int orc_patch_forward(const orc_layer *L, int nL, int C0, int n, const double *params,
-                      const double *patch, double *acts, int *amax, int storage)
+                      const double *patch, double *acts, int *amax, double *pre, int storage)
 {
     orc_geom g;
     if (geom_build(L, nL, C0, n, &g)) return -1;
     memcpy(acts, patch, sizeof(double) * (size_t)C0 * n * n);
     if (amax) for (long t = 0; t < g.act_off[nL + 1]; ++t) amax[t] = -1;
-    patch_forward(L, &g, params, acts, amax, storage, NULL);
+    patch_forward(L, &g, params, acts, amax, storage, pre);
     return 0;
 }
 
@@ -306,12 +286,12 @@ int orc_patch_forward(const orc_layer *L, int nL, int C0, int n, const double *p
  * i, j) in UNPADDED pixel coordinates; the patch of (i, j) is padded rows
  * i..i+n-1, columns j..j+n-1.  scores: [P][classes].  last_amax (may be NULL):
  * [P][classes] winning tap indices when the last layer is a max pool.  The net
- * must reduce the patch to 1 x 1.  storage: ORC_STORE_*; margins (may be NULL):
- * [P] distance of each patch from a gradient discontinuity (see patch_forward).  Returns 0, or -1 on a malformed net / out-of-range pixel. */
+ * must reduce the patch to 1 x 1.  storage: ORC_STORE_*.  Returns 0, or -1 on a
+ * malformed net / out-of-range pixel. */
 int orc_scan_forward(const orc_layer *L, int nL, int C0, int n, const double *params,
                      const double *xpad, int N, int Hp, int Wp,
                      const int *pix, long P, double *scores, int *last_amax,
-                     int storage, double *margins)
+                     int storage)
 {
     orc_geom g;
     if (geom_build(L, nL, C0, n, &g) || g.m[nL] != 1) return -1;
@@ -332,7 +312,7 @@ int orc_scan_forward(const orc_layer *L, int nL, int C0, int n, const double *pa
         for (long p = 0; p < P; ++p) {
             if (!acts || (last_amax && !amax)) continue;
             crop_patch(xpad, C0, Hp, Wp, n, pix[3 * p], pix[3 * p + 1], pix[3 * p + 2], acts);
-            patch_forward(L, &g, params, acts, amax, storage, margins ? margins + p : NULL);
+            patch_forward(L, &g, params, acts, amax, storage, NULL);
             memcpy(scores + p * cls, acts + g.act_off[nL], sizeof(double) * (size_t)cls);
             if (last_amax)
                 memcpy(last_amax + p * cls, amax + g.act_off[nL], sizeof(int) * (size_t)cls);
@@ -341,6 +321,36 @@ int orc_scan_forward(const orc_layer *L, int nL, int C0, int n, const double *pa
         free(amax);
     }
     return fail ? -2 : 0;
+}
+
+/* The same scan, keeping everything: acts [P][act_total] holds all maps of every
+ * patch (map 0 = the patch itself), amax [P][act_total] the winning tap index
+ * of each max-pool output (-1 elsewhere), pre [P][act_total] (may be NULL) the
+ * pre-activation values of conv outputs (0 elsewhere).  By the correspondence
+ * of Fig. 3, entry (u, v) of map l of the patch at (i, j) is the whole-image
+ * map l at (i + D*u, j + D*v), D = product of the strides of layers 1..l. */
+int orc_scan_forward_maps(const orc_layer *L, int nL, int C0, int n, const double *params,
+                          const double *xpad, int N, int Hp, int Wp,
+                          const int *pix, long P, double *acts, int *amax, double *pre,
+                          int storage)
+{
+    orc_geom g;
+    if (geom_build(L, nL, C0, n, &g)) return -1;
+    for (long p = 0; p < P; ++p)
+        if (pix[3 * p] < 0 || pix[3 * p] >= N || pix[3 * p + 1] < 0 || pix[3 * p + 1] + n > Hp ||
+            pix[3 * p + 2] < 0 || pix[3 * p + 2] + n > Wp) return -1;
+    const long na = g.act_off[nL + 1];
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long p = 0; p < P; ++p) {
+        double *a = acts + p * na;
+        int *am = amax + p * na;
+        double *z = pre ? pre + p * na : NULL;
+        for (long t = 0; t < na; ++t) am[t] = -1;
+        if (z) memset(z, 0, sizeof(double) * (size_t)na);
+        crop_patch(xpad, C0, Hp, Wp, n, pix[3 * p], pix[3 * p + 1], pix[3 * p + 2], a);
+        patch_forward(L, &g, params, a, am, storage, z);
+    }
+    return 0;
 }
 
 /* Backward scan: each listed patch goes forward, then backward with output

@@ -43,8 +43,9 @@ def _load():
         ci, cl = ctypes.c_int, ctypes.c_long
         lib.orc_sizes.argtypes = [Lp, ci, ci, ci, lp, lp, ip, ip]
         lib.orc_geometry.argtypes = [Lp, ci, ci, ci, ip, ip, lp, lp]
-        lib.orc_patch_forward.argtypes = [Lp, ci, ci, ci, dp, dp, dp, ip, ci]
-        lib.orc_scan_forward.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp, ip, ci, dp]
+        lib.orc_patch_forward.argtypes = [Lp, ci, ci, ci, dp, dp, dp, ip, dp, ci]
+        lib.orc_scan_forward.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp, ip, ci]
+        lib.orc_scan_forward_maps.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp, ip, dp, ci]
         lib.orc_scan_backward.argtypes = [Lp, ci, ci, ci, dp, dp, ci, ci, ci, ip, cl, dp, dp, dp, ci]
         lib.orc_num_threads.restype = ci
         _lib = lib
@@ -134,11 +135,20 @@ def unpack_params(net, flat):
 STORE_EXACT, STORE_BF16 = 0, 1
 
 
-def patch_forward(net, params, patch, storage=STORE_EXACT):
+def _split_maps(g, flat, nL):
+    out = []
+    for l in range(nL + 1):
+        o, C, m = int(g["act_off"][l]), int(g["C"][l]), int(g["m"][l])
+        out.append(flat[..., o:o + C * m * m].reshape(flat.shape[:-1] + (C, m, m)))
+    return out
+
+
+def patch_forward(net, params, patch, storage=STORE_EXACT, want_pre=False):
     """Original CNN on one patch [C0, n, n].  Returns (maps, argmax): lists over
     l = 0..L of fp64 [C_l, m_l, m_l] maps (map 0 is the patch) and int32 arrays of
     the same shapes holding the winning tap index a*k+b of max-pool outputs
-    (-1 elsewhere)."""
+    (-1 elsewhere).  With want_pre a third list: the values of conv outputs before
+    the non-linearity (0 elsewhere)."""
     lib = _load()
     g = geometry(net)
     arr, nL = _clayers(net)
@@ -148,23 +158,46 @@ def patch_forward(net, params, patch, storage=STORE_EXACT):
     assert params.size == g["n_params"]
     acts = np.zeros(g["act_total"], np.float64)
     amax = np.zeros(g["act_total"], np.int32)
+    pre = np.zeros(g["act_total"], np.float64) if want_pre else None
     if lib.orc_patch_forward(arr, nL, net.C0, net.patch, _dptr(params), _dptr(patch),
-                             _dptr(acts), _iptr(amax), storage):
+                             _dptr(acts), _iptr(amax), _dptr(pre) if want_pre else None, storage):
         raise ValueError("malformed net")
-    maps, ams = [], []
-    for l in range(nL + 1):
-        o, C, m = int(g["act_off"][l]), int(g["C"][l]), int(g["m"][l])
-        maps.append(acts[o:o + C * m * m].reshape(C, m, m).copy())
-        ams.append(amax[o:o + C * m * m].reshape(C, m, m).copy())
-    return maps, ams
+    res = ([m.copy() for m in _split_maps(g, acts, nL)], [m.copy() for m in _split_maps(g, amax, nL)])
+    if want_pre:
+        res += ([m.copy() for m in _split_maps(g, pre, nL)],)
+    return res
 
 
-def scan_forward(net, params, xpad, pix, want_argmax=False, storage=STORE_EXACT, want_margin=False):
+def scan_forward_maps(net, params, xpad, pix, storage=STORE_EXACT):
+    """Every map of every listed patch.  Returns (maps, argmax, pre): lists over l = 0..L of
+    arrays [P, C_l, m_l, m_l] -- fp64 maps (map 0 = the patches), int32 winning tap indices of
+    max-pool outputs (-1 elsewhere), fp64 conv outputs before the non-linearity (0 elsewhere).
+    Entry (u, v) of map l of the patch at (i, j) is the whole-image map l at (i + D*u, j + D*v),
+    D = product of the strides of layers 1..l (Fig. 3)."""
+    lib = _load()
+    g = geometry(net)
+    arr, nL = _clayers(net)
+    params = np.ascontiguousarray(params, np.float64)
+    xpad = np.ascontiguousarray(xpad, np.float64)
+    pix = np.ascontiguousarray(pix, np.int32).reshape(-1, 3)
+    assert params.size == g["n_params"]
+    N, C0, Hp, Wp = xpad.shape
+    assert C0 == net.C0
+    P = pix.shape[0]
+    acts = np.zeros((P, g["act_total"]), np.float64)
+    amax = np.zeros((P, g["act_total"]), np.int32)
+    pre = np.zeros((P, g["act_total"]), np.float64)
+    rc = lib.orc_scan_forward_maps(arr, nL, net.C0, net.patch, _dptr(params), _dptr(xpad),
+                                   N, Hp, Wp, _iptr(pix), P, _dptr(acts), _iptr(amax), _dptr(pre), storage)
+    if rc:
+        raise ValueError("orc_scan_forward_maps failed: %d" % rc)
+    return _split_maps(g, acts, nL), _split_maps(g, amax, nL), _split_maps(g, pre, nL)
+
+
+def scan_forward(net, params, xpad, pix, want_argmax=False, storage=STORE_EXACT):
     """Scores [P, classes] of the patches at pix [P, 3] = (image, i, j).  With
-    want_argmax (last layer a max pool) also the winning tap indices [P, classes]; with
-    want_margin also each patch's relative distance [P] from the nearest ReLU gate / max-pool
-    near-tie, where the gradient is discontinuous.  storage=STORE_BF16 rounds the patch and
-    every layer output but the last to bfloat16."""
+    want_argmax (last layer a max pool) also the winning tap indices [P, classes].
+    storage=STORE_BF16 rounds the patch and every layer output but the last to bfloat16."""
     lib = _load()
     g = geometry(net)
     if g["m_last"] != 1:
@@ -178,15 +211,12 @@ def scan_forward(net, params, xpad, pix, want_argmax=False, storage=STORE_EXACT,
     assert C0 == net.C0
     out = np.zeros((pix.shape[0], g["classes"]), np.float64)
     am = np.zeros((pix.shape[0], g["classes"]), np.int32) if want_argmax else None
-    mg = np.ones(pix.shape[0], np.float64) if want_margin else None
     rc = lib.orc_scan_forward(arr, nL, net.C0, net.patch, _dptr(params), _dptr(xpad),
                               N, Hp, Wp, _iptr(pix), pix.shape[0], _dptr(out),
-                              _iptr(am) if want_argmax else None, storage,
-                              _dptr(mg) if want_margin else None)
+                              _iptr(am) if want_argmax else None, storage)
     if rc:
         raise ValueError("orc_scan_forward failed: %d" % rc)
-    res = (out,) + ((am,) if want_argmax else ()) + ((mg,) if want_margin else ())
-    return res if len(res) > 1 else out
+    return (out, am) if want_argmax else out
 
 
 def scan_backward(net, params, xpad, pix, delta, want_dx=False, storage=STORE_EXACT):

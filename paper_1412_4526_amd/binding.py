@@ -308,3 +308,4 @@ def dsk_masked_softmax_xent(scores, labels, mask, dscores_dtype=torch.float32, l
                                        _dtype_code(dscores), N, Cls, H, W, wsp, wsb, _stream()),
            "dsk_masked_softmax_xent")
     return loss, dscores
+

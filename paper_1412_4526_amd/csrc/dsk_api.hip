@@ -1,6 +1,6 @@
 // C-ABI entry points of libdsk: argument validation (before any launch),
 // Algorithm 1's host-side planner, and dispatch to the kernels.
-#include <atomic>
+#include <mutex>
 
 #include "dsk_internal.h"
 
@@ -8,7 +8,8 @@ using namespace dsk;
 
 namespace {
 
-std::atomic<int> g_conv_algo{0};
+// kernel selection of the calling thread (a diagnostic switch; nothing is shared between threads)
+thread_local int g_conv_algo = 0;
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool bad_ptr(const void *p) { return p == nullptr || !aligned16(p); }
@@ -37,10 +38,28 @@ int pool_check(const void *a, const void *b, int N, int C, int H, int W, int k, 
     const long Ho = (long)H - (long)(k - 1) * d, Wo = (long)W - (long)(k - 1) * d;
     if (Ho < 1 || Wo < 1) return DSK_ESHAPE;
     if ((long)N * C * H * W > kMaxElems) return DSK_ESHAPE;
+    if ((long)H * W >= (1L << 30)) return DSK_ESHAPE;      // 32-bit byte offsets inside a plane
     return DSK_OK;
 }
 
 } // namespace
+
+namespace dsk {
+int device_cu_count()
+{
+    static std::mutex mu;
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+} // namespace dsk
 
 extern "C" {
 
@@ -59,8 +78,9 @@ const char *dsk_status_string(int status)
 
 int dsk_set_conv_algo(int algo)
 {
-    if (algo < 0 || algo > 2) return g_conv_algo.load();
-    return g_conv_algo.exchange(algo);
+    const int prev = g_conv_algo;
+    if (algo >= 0 && algo <= 2) g_conv_algo = algo;
+    return prev;
 }
 
 int dsk_plan(const dsk_layer *layers, int L, int C0, int H, int W, int n,
@@ -117,6 +137,7 @@ int dsk_pad_image(const float *x, void *xpad, int N, int C, int H, int W, int lo
     if (bad_ptr(x) || bad_ptr(xpad)) return DSK_EINVAL;
     if (N < 1 || C < 1 || H < 1 || W < 1 || lo < 0 || hi < 0 || bad_dtype(out)) return DSK_EINVAL;
     if ((long)N * C * ((long)H + lo + hi) * ((long)W + lo + hi) > kMaxElems) return DSK_ESHAPE;
+    clear_errors();
     return launch_pad_image(x, xpad, N, C, H, W, lo, hi, out, (hipStream_t)stream);
 }
 
@@ -140,9 +161,10 @@ int dsk_conv_fwd(const void *x, const float *w, const float *b, void *y,
     const size_t need = conv_ws_bytes(DSK_WS_CONV_FWD, s, in);
     if (need > 0 && (ws == nullptr || !aligned16(ws) || ws_bytes < need)) return DSK_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    if (g_conv_algo.load() == 0 && in == DSK_BF16 && conv_bf16_supported(DSK_WS_CONV_FWD, s))
+    clear_errors();
+    if (g_conv_algo == 0 && in == DSK_BF16 && conv_bf16_supported(DSK_WS_CONV_FWD, s))
         return launch_conv_fwd_bf16(x, w, b, y, s, out, act, ws, st);
-    if (g_conv_algo.load() != 1 && conv_mfma_supported(DSK_WS_CONV_FWD, s, in, out))
+    if (g_conv_algo != 1 && conv_mfma_supported(DSK_WS_CONV_FWD, s, in, out))
         return launch_conv_fwd_mfma(x, w, b, y, s, in, out, act, ws, st);
     return launch_conv_fwd_direct(x, w, b, y, s, in, out, act, st);
 }
@@ -159,9 +181,10 @@ int dsk_conv_bwd_data(const void *dy, const float *w, void *dx,
     const size_t need = conv_ws_bytes(DSK_WS_CONV_BWD_DATA, s, in);
     if (need > 0 && (ws == nullptr || !aligned16(ws) || ws_bytes < need)) return DSK_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    if (g_conv_algo.load() == 0 && in == DSK_BF16 && conv_bf16_supported(DSK_WS_CONV_BWD_DATA, s))
+    clear_errors();
+    if (g_conv_algo == 0 && in == DSK_BF16 && conv_bf16_supported(DSK_WS_CONV_BWD_DATA, s))
         return launch_conv_bwd_data_bf16(dy, w, dx, s, out, ws, st);
-    if (g_conv_algo.load() != 1 && conv_mfma_supported(DSK_WS_CONV_BWD_DATA, s, in, out))
+    if (g_conv_algo != 1 && conv_mfma_supported(DSK_WS_CONV_BWD_DATA, s, in, out))
         return launch_conv_bwd_data_mfma(dy, w, dx, s, in, out, ws, st);
     return launch_conv_bwd_data_direct(dy, w, dx, s, in, out, st);
 }
@@ -178,7 +201,8 @@ int dsk_conv_bwd_weight(const void *x, const void *dy, float *dw, float *db,
     const size_t need = conv_ws_bytes(DSK_WS_CONV_BWD_WEIGHT, s, in);
     if (need > 0 && (ws == nullptr || !aligned16(ws) || ws_bytes < need)) return DSK_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    if (g_conv_algo.load() != 1 && conv_mfma_supported(DSK_WS_CONV_BWD_WEIGHT, s, in, DSK_F32))
+    clear_errors();
+    if (g_conv_algo != 1 && conv_mfma_supported(DSK_WS_CONV_BWD_WEIGHT, s, in, DSK_F32))
         return launch_conv_bwd_weight_mfma(x, dy, dw, db, s, in, ws, st);
     return launch_conv_bwd_weight_direct(x, dy, dw, db, s, in, st);
 }
@@ -188,6 +212,8 @@ int dsk_maxpool_fwd(const void *x, void *y, uint8_t *argmax, int N, int C, int H
 {
     int rc = pool_check(x, y, N, C, H, W, k, d, t);
     if (rc != DSK_OK) return rc;
+    if (argmax && !aligned16(argmax)) return DSK_EINVAL;
+    clear_errors();
     return launch_maxpool_fwd(x, y, argmax, N, C, H, W, k, d, t, (hipStream_t)stream);
 }
 
@@ -196,7 +222,8 @@ int dsk_maxpool_bwd(const void *dy, const uint8_t *argmax, void *dx, int N, int 
 {
     int rc = pool_check(dy, dx, N, C, H, W, k, d, t);
     if (rc != DSK_OK) return rc;
-    if (argmax == nullptr) return DSK_EINVAL;
+    if (bad_ptr(argmax)) return DSK_EINVAL;
+    clear_errors();
     return launch_maxpool_bwd(dy, argmax, dx, N, C, H, W, k, d, t, (hipStream_t)stream);
 }
 
@@ -204,6 +231,7 @@ int dsk_avgpool_fwd(const void *x, void *y, int N, int C, int H, int W, int k, i
 {
     int rc = pool_check(x, y, N, C, H, W, k, d, t);
     if (rc != DSK_OK) return rc;
+    clear_errors();
     return launch_avgpool_fwd(x, y, N, C, H, W, k, d, t, (hipStream_t)stream);
 }
 
@@ -211,6 +239,7 @@ int dsk_avgpool_bwd(const void *dy, void *dx, int N, int C, int H, int W, int k,
 {
     int rc = pool_check(dy, dx, N, C, H, W, k, d, t);
     if (rc != DSK_OK) return rc;
+    clear_errors();
     return launch_avgpool_bwd(dy, dx, N, C, H, W, k, d, t, (hipStream_t)stream);
 }
 
@@ -219,6 +248,7 @@ int dsk_act_bwd(const void *y, void *dy, size_t count, dsk_act act, dsk_dtype t,
     if (bad_ptr(y) || bad_ptr(dy) || bad_dtype(t)) return DSK_EINVAL;
     if (act < DSK_ACT_NONE || act > DSK_ACT_TANH) return DSK_EINVAL;
     if (count > (size_t)kMaxElems) return DSK_ESHAPE;
+    clear_errors();
     return launch_act_bwd(y, dy, count, act, t, (hipStream_t)stream);
 }
 
@@ -236,6 +266,7 @@ int dsk_act_bwd_bias(const void *y, void *dy, float *db, int N, int K, int Ho, i
     if (N < 1 || K < 1 || Ho < 1 || Wo < 1) return DSK_EINVAL;
     if ((long)N * K * Ho * Wo > kMaxElems) return DSK_ESHAPE;
     if (ws == nullptr || !aligned16(ws) || ws_bytes < act_bwd_bias_ws_bytes(K)) return DSK_EWORKSPACE;
+    clear_errors();
     return launch_act_bwd_bias(y, dy, db, N, K, (long)Ho * Wo, act, t, ws, (hipStream_t)stream);
 }
 
@@ -257,6 +288,7 @@ int dsk_masked_softmax_xent(const float *scores, const int32_t *labels, const ui
     if ((long)N * Cls * H * W > kMaxElems) return DSK_ESHAPE;
     const size_t need = softmax_xent_ws_bytes((long)N * H * W);
     if (ws == nullptr || !aligned16(ws) || ws_bytes < need) return DSK_EWORKSPACE;
+    clear_errors();
     return launch_masked_softmax_xent(scores, labels, mask, loss, dscores, dt, N, Cls, H, W, ws, (hipStream_t)stream);
 }
 

@@ -14,6 +14,8 @@
 //
 // fp32 path: v_mfma_f32_32x32x2_f32.  Lane l supplies A[i = l%32][k = l/32] and
 // B[k = l/32][j = l%32]; register r of the 16 results holds D[8*(r/4) + 4*(l/32) + r%4][l%32].
+#include <atomic>
+
 #include "dsk_internal.h"
 
 namespace dsk {
@@ -29,12 +31,18 @@ static constexpr int kXcds = 8;
 static constexpr size_t kMaxLds = 64 * 1024;      // forward / backward-data: two workgroups per CU
 static constexpr size_t kMaxLdsBw = 76 * 1024;    // backward-weight: still two per CU (160 KB)
 
-// Dynamic LDS beyond the default limit has to be enabled per kernel.
-template <typename F>
-static void allow_lds(F kernel, size_t bytes)
+// Dynamic LDS beyond the default limit has to be enabled per kernel (and device): done the first
+// time a kernel needs that much, not on every launch.
+template <auto Kernel>
+static void allow_lds(size_t bytes)
 {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+    static std::atomic<size_t> granted[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
+    if (dev >= 0 && granted[dev].load(std::memory_order_acquire) >= bytes) return;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)bytes);
+    if (dev >= 0) granted[dev].store(bytes, std::memory_order_release);
 }
 
 
@@ -406,7 +414,6 @@ gc_fixup_kernel(GcParams p)
 static constexpr int kXI = 16;   // input-tile elements per thread per chunk, at most
 static constexpr int kXIBig = 24;   // the same for tiles with a large halo (second set of kernels)
 static constexpr int kWI = 8;    // weight float4s per thread per chunk, at most
-static constexpr long kSlots = 512;   // workgroups resident at once: 2 per CU, 256 CUs
 
 struct GcPlan {
     bool ok, split;      // split: persistent workgroups with split tiles
@@ -422,6 +429,7 @@ struct GcPlan {
 static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int kw, int d)
 {
     GcPlan g{};
+    const long kSlots = 2L * device_cu_count();      // workgroups resident at once: two per CU
     g.WM = Fout > 32 ? 2 : 1;
     g.TF = g.WM * 32;
     g.n_fgrp = (Fout + g.TF - 1) / g.TF;
@@ -527,6 +535,7 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
 {
     const GcPlan g = gc_plan(N, Cin, Fout, Hout, Wout, kh, kw, d);
     if (!g.ok) return DSK_ESHAPE;
+    if ((g.n_wg + kXcds - 1) / kXcds * kXcds > 0x7fffffffL) return DSK_ESHAPE;      // before anything is launched
     const int taps = kh * kw;
     float *wt = (float *)ws;
     {
@@ -705,6 +714,7 @@ static int pw_run(const void *in, void *out, const float *w, const float *bias, 
 {
     const PwPlan g = pw_plan(Cin, Fout, HW, 1, 1);
     if (!g.ok) return DSK_ESHAPE;
+    if (((long)N * ((HW + 127) / 128) + 3) / 4 > 0x7fffffffL) return DSK_ESHAPE;      // before anything is launched
     float *wt = (float *)ws;
     const long total = (long)g.n_fgrp * g.Cpad * g.TF;
     gc_weight_prep_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
@@ -1522,11 +1532,11 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
 #define DSK_BW_LAUNCH(TPW, XR, RS, PF, PB)                                                                 \
     do {                                                                                               \
         if (in == DSK_F32) {                                                                           \
-            allow_lds(conv_bwd_weight_mfma_kernel<float, TPW, XR, RS, PF, PB>, b.lds_bytes);               \
+            allow_lds<&conv_bwd_weight_mfma_kernel<float, TPW, XR, RS, PF, PB>>(b.lds_bytes);               \
             conv_bwd_weight_mfma_kernel<float, TPW, XR, RS, PF, PB>                                        \
                 <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                  \
         } else {                                                                                       \
-            allow_lds(conv_bwd_weight_mfma_kernel<bf16, TPW, XR, RS, PF, PB>, b.lds_bytes);                \
+            allow_lds<&conv_bwd_weight_mfma_kernel<bf16, TPW, XR, RS, PF, PB>>(b.lds_bytes);                \
             conv_bwd_weight_mfma_kernel<bf16, TPW, XR, RS, PF, PB>                                         \
                 <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                  \
         }                                                                                              \
@@ -1537,7 +1547,7 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     conv_bwd_weight_mfma_kernel<bf16, TPW, 8, false, true, false, AL><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p)
 #define DSK_BFM2_LAUNCH(TPW, XR, AL, PF)                                                                  \
     do {                                                                                               \
-        allow_lds(conv_bwd_weight_mfma_kernel<bf16, TPW, XR, false, PF, false, AL, 2>, b.lds_bytes);     \
+        allow_lds<&conv_bwd_weight_mfma_kernel<bf16, TPW, XR, false, PF, false, AL, 2>>(b.lds_bytes);     \
         conv_bwd_weight_mfma_kernel<bf16, TPW, XR, false, PF, false, AL, 2>                              \
             <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                      \
     } while (0)
@@ -1560,11 +1570,11 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
 #undef DSK_BFM_LAUNCH
         else if (b.fb2) {
             if (in == DSK_F32) {
-                allow_lds(conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 0, 2>, b.lds_bytes);
+                allow_lds<&conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 0, 2>>(b.lds_bytes);
                 conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 0, 2>
                     <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
             } else {
-                allow_lds(conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 0, 2>, b.lds_bytes);
+                allow_lds<&conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 0, 2>>(b.lds_bytes);
                 conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 0, 2>
                     <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
             }

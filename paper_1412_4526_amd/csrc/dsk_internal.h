@@ -140,9 +140,19 @@ int launch_masked_softmax_xent(const float *scores, const int32_t *labels, const
                                void *dscores, dsk_dtype dt, int N, int Cls, int H, int W, void *ws,
                                hipStream_t st);
 
+
+// Launch errors are sticky in the HIP runtime: an entry point forgets what the caller's earlier
+// HIP calls may have left behind before its first launch, so that check_launch reports only its own.
+inline void clear_errors()
+{
+    (void)hipGetLastError();
+}
 inline int check_launch()
 {
     return hipGetLastError() == hipSuccess ? DSK_OK : DSK_ELAUNCH;
 }
+
+// multiprocessors of the current device (cached per device)
+int device_cu_count();
 
 } // namespace dsk

@@ -330,3 +330,137 @@ def test_patch_geometry_of_paper_models():
     assert 256 + 133 - 1 == 388
     g = oracle.geometry(EXAMPLE)
     assert list(g["m"]) == [15, 14, 7, 6, 2, 1]        # Fig. 3 (c2)-(f2)
+
+
+# ---------------------------------------------------------------------------
+# The bf16-storage mode, the pre-activation output and the all-maps scan: options of the
+# oracle that the end-to-end GPU checks rely on, pinned here to torch's bfloat16 conversion,
+# to hand-rounded values and to the plain scan.
+# ---------------------------------------------------------------------------
+def _torch_bf16(a):
+    return torch.from_numpy(np.asarray(a, np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def test_bf16_storage_rounds_like_torch_and_ties_to_even():
+    net = Net("id", 1, 8, (conv(1, 8),))          # map 0 (the patch) is what gets rounded
+    e = 2.0 ** -8                                   # half a bf16 step at 1.0 (8 significant bits)
+    hand = [
+        (1.0 + e, 1.0),                  # exact tie, kept mantissa even -> down
+        (1.0 + 3 * e, 1.0 + 4 * e),      # exact tie, kept mantissa odd -> up to the even one
+        (1.0 + 5 * e, 1.0 + 4 * e),      # exact tie -> down to the even one
+        (1.0 + e + 2.0 ** -20, 1.0 + 2 * e),   # just above a tie -> up
+        (1.0 + e - 2.0 ** -20, 1.0),           # just below a tie -> down
+        (-1.0 - 3 * e, -1.0 - 4 * e),    # sign does not matter
+        (-1.0 - e, -1.0),
+        (3.0 + 3.0 / 128, 3.03125),      # 11.0000011b: tie, odd -> 11.000010b
+        (0.0, 0.0), (255.0, 255.0), (257.0, 256.0), (259.0, 260.0),
+        (2.0 ** -126, 2.0 ** -126), (1e-3, float(_torch_bf16([1e-3])[0])),
+    ]
+    rng = np.random.default_rng(0)
+    vals = [h[0] for h in hand]
+    vals += list(rng.standard_normal(64 - len(vals)).astype(np.float32) * 10.0 ** rng.integers(-6, 6, 64 - len(vals)))
+    patch = np.asarray(vals, np.float64).reshape(1, 8, 8)
+    maps, _ = oracle.patch_forward(net, np.zeros(65), patch, storage=oracle.STORE_BF16)
+    got = maps[0].ravel()
+    for t, (v, want) in enumerate(hand):
+        assert got[t] == want, (v, got[t], want)
+    np.testing.assert_array_equal(got, _torch_bf16(patch).ravel())
+    # truncation instead of nearest-even would fail here
+    assert got[1] != np.float64(np.float32(1.0 + 2 * e)) and got[3] == 1.0 + 2 * e
+    # exact mode leaves the patch alone
+    maps, _ = oracle.patch_forward(net, np.zeros(65), patch)
+    np.testing.assert_array_equal(maps[0], patch)
+
+
+def test_bf16_storage_rounds_every_map_but_the_last():
+    """Three 1x1 layers on a 1x1 patch: every value is known by hand.
+    patch 1 + 2^-8 + 2^-20 -> stored 1 + 2^-7; layer 1 (w = 3): 3 + 3/128 is a tie, stored
+    3.03125; layer 2 (w = 0.5, ReLU): 1.515625 = 1.1000010b is representable; the last layer
+    (w = 0.3) is not rounded."""
+    net = Net("chain", 1, 1, (conv(1, 1), conv(1, 1, 1, ACT_RELU), conv(1, 1)))
+    params = oracle.pack_params([np.full((1, 1, 1, 1), 3.0), np.full((1, 1, 1, 1), 0.5), np.full((1, 1, 1, 1), 0.3)],
+                                [np.zeros(1), np.zeros(1), np.zeros(1)])
+    x = 1.0 + 2.0 ** -8 + 2.0 ** -20
+    maps, _ = oracle.patch_forward(net, params, np.full((1, 1, 1), x), storage=oracle.STORE_BF16)
+    assert maps[0].item() == 1.0 + 2.0 ** -7
+    assert maps[1].item() == 3.03125
+    assert maps[2].item() == 1.515625
+    assert maps[3].item() == 0.3 * 1.515625
+    exact, _ = oracle.patch_forward(net, params, np.full((1, 1, 1), x))
+    assert exact[3].item() == 0.3 * (0.5 * (3.0 * x))
+    # the scans use the same storage rule: scores and the gradient of the stored chain
+    xpad = np.full((1, 1, 1, 1), x)
+    s = oracle.scan_forward(net, params, xpad, [(0, 0, 0)], storage=oracle.STORE_BF16)
+    assert s.item() == 0.3 * 1.515625
+    g, dx = oracle.scan_backward(net, params, xpad, [(0, 0, 0)], [[1.0]], want_dx=True, storage=oracle.STORE_BF16)
+    dws, dbs = oracle.unpack_params(net, g)
+    # d out / d w3 = stored map 2; d out / d w2 = 0.3 * stored map 1; d out / d w1 = 0.3 * 0.5 * stored patch
+    assert dws[2].item() == 1.515625 and dws[1].item() == 0.3 * 3.03125
+    np.testing.assert_allclose(dws[0].item(), 0.3 * 0.5 * (1.0 + 2.0 ** -7), rtol=1e-15)
+
+
+def test_bf16_storage_decides_gates_and_winners_on_stored_values():
+    # a pool window whose largest value rounds down onto its neighbour: a tie in storage precision, lowest index wins
+    net = Net("p", 1, 2, (maxpool(2, 2),))
+    w = np.array([[[1.0, 1.0 + 2.0 ** -9], [0.5, 0.25]]])
+    _, ams = oracle.patch_forward(net, np.zeros(0), w)
+    assert ams[1].item() == 1
+    maps, ams = oracle.patch_forward(net, np.zeros(0), w, storage=oracle.STORE_BF16)
+    assert ams[1].item() == 0 and maps[1].item() == 1.0
+    # against torch on a random network: layer by layer with torch's own bfloat16 conversions
+    net = EXAMPLE_MC
+    ws, bs = _params(net, 41)
+    ws = [_torch_bf16(w) for w in ws]
+    rng = np.random.default_rng(42)
+    patch = rng.uniform(-1, 1, (net.C0, net.patch, net.patch))
+    maps, ams = oracle.patch_forward(net, oracle.pack_params(ws, bs), patch, storage=oracle.STORE_BF16)
+    x = torch.from_numpy(_torch_bf16(patch))[None]
+    wi = 0
+    for l, L in enumerate(net.layers):
+        if L.kind == CONV:
+            x = F.conv2d(x, torch.from_numpy(ws[wi]), torch.from_numpy(bs[wi]), stride=L.s)
+            wi += 1
+            x = torch.relu(x) if L.act == ACT_RELU else torch.tanh(x) if L.act == ACT_TANH else x
+        elif L.kind == MAXPOOL:
+            x = F.max_pool2d(x, L.k, L.s)
+        else:
+            x = F.avg_pool2d(x, L.k, L.s)
+        if l + 1 < len(net.layers):
+            # fp64 -> fp32 -> bf16 as the oracle does (a value within 1e-12 of a rounding boundary could differ; none here)
+            x = x.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+        np.testing.assert_allclose(maps[l + 1], x[0].numpy(), rtol=1e-12, atol=1e-13, err_msg="map %d" % (l + 1))
+
+
+@pytest.mark.parametrize("net", NETS, ids=lambda n: n.name)
+def test_pre_activation_output_and_all_maps_scan(net):
+    ws, bs = _params(net, 51)
+    rng = np.random.default_rng(52)
+    N, H, W = 2, 4, 5
+    img = rng.uniform(-1, 1, (N, net.C0, H, W))
+    xpad = oracle.pad_image(img, net.patch)
+    params = oracle.pack_params(ws, bs)
+    pix = np.array([(1, 3, 4), (0, 0, 0), (1, 2, 1), (0, 3, 2), (0, 1, 4)], np.int32)
+    maps, ams, pre = oracle.scan_forward_maps(net, params, xpad, pix)
+    np.testing.assert_array_equal(maps[-1][:, :, 0, 0], oracle.scan_forward(net, params, xpad, pix))
+    n = net.patch
+    tw, tb = [torch.from_numpy(w) for w in ws], [torch.from_numpy(b) for b in bs]
+    for t, (im, i, j) in enumerate(pix):
+        pm, pam, ppre = oracle.patch_forward(net, params, xpad[im, :, i:i + n, j:j + n], want_pre=True)
+        x = torch.from_numpy(xpad[im, :, i:i + n, j:j + n])[None]
+        wi = 0
+        for l, L in enumerate(net.layers):
+            np.testing.assert_array_equal(maps[l + 1][t], pm[l + 1])
+            np.testing.assert_array_equal(ams[l + 1][t], pam[l + 1])
+            np.testing.assert_array_equal(pre[l + 1][t], ppre[l + 1])
+            if L.kind == CONV:
+                # pinned to torch: the convolution WITHOUT its non-linearity, computed on the oracle's own input map
+                z = F.conv2d(torch.from_numpy(pm[l])[None], tw[wi], tb[wi], stride=L.s)[0].numpy()
+                wi += 1
+                np.testing.assert_allclose(ppre[l + 1], z, rtol=1e-12, atol=1e-13)
+                want = np.maximum(z, 0) if L.act == ACT_RELU else np.tanh(z) if L.act == ACT_TANH else z
+                np.testing.assert_allclose(pm[l + 1], want, rtol=1e-12, atol=1e-13)
+                assert np.array_equal(pm[l + 1] > 0, ppre[l + 1] > 0) or L.act != ACT_RELU
+                assert (pam[l + 1] == -1).all()
+            else:
+                assert not ppre[l + 1].any()
+                assert ((pam[l + 1] >= 0).all() and (pam[l + 1] < L.k * L.k).all()) if L.kind == MAXPOOL else (pam[l + 1] == -1).all()

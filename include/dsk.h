@@ -26,7 +26,8 @@
  *     except DSK_ELAUNCH is returned without touching the GPU.  No exceptions
  *     cross this boundary.  Calls are re-entrant: the library keeps no state
  *     between calls apart from the calling thread's diagnostic switch
- *     dsk_set_conv_algo.
+ *     dsk_set_conv_algo and the per-GPU scratch array of
+ *     dsk_masked_softmax_xent_static.
  *   - Return value: DSK_OK (0) or a negative dsk_status.
  */
 #ifndef DSK_H
@@ -198,6 +199,23 @@ size_t dsk_softmax_xent_workspace_bytes(int N, int Cls, int H, int W);
 int dsk_masked_softmax_xent(const float *scores, const int32_t *labels, const uint8_t *mask,
                             float *loss, void *dscores, dsk_dtype dt, int N, int Cls, int H, int W,
                             void *ws, size_t ws_bytes, void *stream);
+
+/* The same call for callers that cannot allocate device memory or size a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments and results as dsk_masked_softmax_xent
+ * minus the workspace: the partial counts and sums live in an array the
+ * library holds in every GPU's memory until the process ends (8208 bytes:
+ * 1024 counts and 1024 sums, whatever the size of the map).
+ *   - Size limits are those of dsk_masked_softmax_xent (N*Cls*H*W <= 2^31-1,
+ *     else DSK_ESHAPE): the scratch array never is what limits a call.
+ *   - The device of `stream` must be the current device.  The first call on a
+ *     device looks the array up (no allocation); make it outside graph capture.
+ *   - Every call on a GPU shares that GPU's array: calls that overlap on one
+ *     GPU (different streams, different threads) race.  The array is re-initialised
+ *     by each call's own kernels, so nothing has to be cleared in between. */
+int dsk_masked_softmax_xent_static(const float *scores, const int32_t *labels, const uint8_t *mask,
+                                   float *loss, void *dscores, dsk_dtype dt, int N, int Cls, int H, int W,
+                                   void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Kernel selection (diagnostics)                                              */

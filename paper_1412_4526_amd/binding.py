@@ -24,7 +24,7 @@ SYMBOLS = ("dsk_plan", "dsk_status_string", "dsk_pad_image", "dsk_conv_workspace
            "dsk_conv_fwd", "dsk_conv_bwd_data", "dsk_conv_bwd_weight",
            "dsk_maxpool_fwd", "dsk_maxpool_bwd", "dsk_avgpool_fwd", "dsk_avgpool_bwd",
            "dsk_act_bwd", "dsk_act_bwd_bias_workspace_bytes", "dsk_act_bwd_bias",
-           "dsk_softmax_xent_workspace_bytes", "dsk_masked_softmax_xent",
+           "dsk_softmax_xent_workspace_bytes", "dsk_masked_softmax_xent", "dsk_masked_softmax_xent_static",
            "dsk_set_conv_algo")
 
 
@@ -77,6 +77,7 @@ def _load():
     lib.dsk_softmax_xent_workspace_bytes.argtypes = [ci] * 4
     lib.dsk_softmax_xent_workspace_bytes.restype = sz
     lib.dsk_masked_softmax_xent.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.dsk_masked_softmax_xent_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
     lib.dsk_set_conv_algo.argtypes = [ci]
     for name in SYMBOLS:
         getattr(lib, name)      # AttributeError here = header and library disagree
@@ -309,3 +310,13 @@ def dsk_masked_softmax_xent(scores, labels, mask, dscores_dtype=torch.float32, l
            "dsk_masked_softmax_xent")
     return loss, dscores
 
+
+def dsk_masked_softmax_xent_static(scores, labels, mask, loss, dscores):
+    """The allocation-free form: every buffer is the caller's, the scratch memory is the library's own."""
+    N, Cls, H, W = scores.shape
+    assert labels.shape == (N, H, W) and mask.shape == (N, H, W) and dscores.shape == scores.shape
+    _check(lib.dsk_masked_softmax_xent_static(_dev(scores, torch.float32), _dev(labels, torch.int32),
+                                              _dev(mask, torch.uint8), _dev(loss, torch.float32), _dev(dscores),
+                                              _dtype_code(dscores), N, Cls, H, W, _stream()),
+           "dsk_masked_softmax_xent_static")
+    return loss, dscores

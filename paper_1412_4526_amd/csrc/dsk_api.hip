@@ -292,4 +292,21 @@ int dsk_masked_softmax_xent(const float *scores, const int32_t *labels, const ui
     return launch_masked_softmax_xent(scores, labels, mask, loss, dscores, dt, N, Cls, H, W, ws, (hipStream_t)stream);
 }
 
+int dsk_masked_softmax_xent_static(const float *scores, const int32_t *labels, const uint8_t *mask,
+                                   float *loss, void *dscores, dsk_dtype dt, int N, int Cls, int H, int W,
+                                   void *stream)
+{
+    if (bad_dtype(dt)) return DSK_EINVAL;
+    if (bad_ptr(scores) || bad_ptr(labels) || bad_ptr(mask) || bad_ptr(dscores) || loss == nullptr ||
+        (reinterpret_cast<uintptr_t>(loss) & 3u))
+        return DSK_EINVAL;
+    if (N < 1 || Cls < 1 || H < 1 || W < 1) return DSK_EINVAL;
+    if ((long)N * Cls * H * W > kMaxElems) return DSK_ESHAPE;
+    void *ws = nullptr;
+    const int rc = static_scratch_of_current_device(&ws);
+    if (rc != DSK_OK) return rc;
+    clear_errors();
+    return launch_masked_softmax_xent(scores, labels, mask, loss, dscores, dt, N, Cls, H, W, ws, (hipStream_t)stream);
+}
+
 } // extern "C"

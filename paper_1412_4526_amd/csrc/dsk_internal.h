@@ -140,6 +140,7 @@ int launch_masked_softmax_xent(const float *scores, const int32_t *labels, const
                                void *dscores, dsk_dtype dt, int N, int Cls, int H, int W, void *ws,
                                hipStream_t st);
 
+int static_scratch_of_current_device(void **out);
 
 // Launch errors are sticky in the HIP runtime: an entry point forgets what the caller's earlier
 // HIP calls may have left behind before its first launch, so that check_launch reports only its own.

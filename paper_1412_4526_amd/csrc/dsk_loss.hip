@@ -14,6 +14,8 @@
 //      adds the loss terms                                        -> dscores, loss[0]
 // An unchosen pixel gets zeros without its scores being read; the scores of a chosen
 // pixel are read by both kernels.
+#include <mutex>
+
 #include "dsk_internal.h"
 
 namespace dsk {
@@ -25,6 +27,11 @@ static constexpr int kCountBlocks = 1024;      // at most; a share is a multiple
 static inline long n_blocks(long pixels) { return (pixels + kThreads - 1) / kThreads; }
 
 size_t softmax_xent_ws_bytes(long) { return (size_t)(4 + 2 * kCountBlocks) * 4; }
+
+// Scratch of dsk_masked_softmax_xent_static: the workspace (its size does not depend on the map), one copy per
+// GPU, held until the process ends.
+static constexpr size_t kStaticScratchBytes = (size_t)(4 + 2 * kCountBlocks) * 4;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 __device__ inline unsigned wave_sum(unsigned v)
 {
@@ -230,6 +237,25 @@ int launch_masked_softmax_xent(const float *scores, const int32_t *labels, const
     else
         launch_softmax<bf16>(scores, labels, mask, (uint32_t *)ws, n_cnt, share, (bf16 *)dscores, loss, Cls, HW, pixels, st);
     return check_launch();
+}
+
+// The scratch array of the current device: the symbol is looked up once per device.
+static constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mu;
+
+int static_scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DSK_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return DSK_ELAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DSK_OK;
 }
 
 } // namespace dsk

@@ -46,9 +46,12 @@ def layer_costs(net, elem):
         elif p.kind == dsk.DSK_MAXPOOL:
             out[("maxpool_fwd", l)] = dict(flops=0.0, bytes=nin * elem + nout * (elem + 1))
             out[("maxpool_bwd", l)] = dict(flops=0.0, bytes=nout * (elem + 1) + nin * elem)
+            # fused with the non-linearity backward of the conv layer in front: that layer's output is read too
+            out[("pool_bwd_act", l)] = dict(flops=0.0, bytes=nout * (elem + 1) + 2 * nin * elem)
         else:
             out[("avgpool_fwd", l)] = dict(flops=0.0, bytes=nin * elem + nout * elem)
             out[("avgpool_bwd", l)] = dict(flops=0.0, bytes=nout * elem + nin * elem)
+            out[("pool_bwd_act", l)] = dict(flops=0.0, bytes=nout * elem + 2 * nin * elem)
     last = net.plan[-1]
     px = N * last.Ho * last.Wo
     out[("softmax_xent", L)] = dict(flops=0.0, bytes=px * (last.K * 4 + 4 + 1 + last.K * elem))
@@ -122,6 +125,8 @@ def main():
                     help="time replays of the step captured in a HIP graph (per-call rates then come from an "
                          "eager pass before the timed region)")
     ap.add_argument("--algo", type=int, default=0)
+    ap.add_argument("--no-fuse", action="store_true",
+                    help="backward: pool gradient and non-linearity backward + bias gradient as separate calls")
     ap.add_argument("--layers", action="store_true", help="print the per-call table to stderr")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference "
@@ -147,7 +152,7 @@ def main():
     wl = make_workload(cfg.net, cfg.N, cfg.H, cfg.W, cfg.mask_frac, cfg.seed, positive_frac=cfg.positive_frac)
     dev = "cuda:0"
     dsk.dsk_set_conv_algo(args.algo)
-    net = dsk.WholeImageNet(cfg.net, cfg.N, cfg.H, cfg.W, dtype, dev, train=not args.forward_only)
+    net = dsk.WholeImageNet(cfg.net, cfg.N, cfg.H, cfg.W, dtype, dev, train=not args.forward_only, fuse=not args.no_fuse)
     net.load_params(wl.weights, wl.biases)
     image = torch.from_numpy(wl.image).to(dev)
     labels = torch.from_numpy(wl.labels).to(dev)

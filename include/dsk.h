@@ -179,6 +179,19 @@ size_t dsk_act_bwd_bias_workspace_bytes(int K);
 int dsk_act_bwd_bias(const void *y, void *dy, float *db, int N, int K, int Ho, int Wo,
                      dsk_act act, dsk_dtype t, void *ws, size_t ws_bytes, void *stream);
 
+/* A pooling layer's gradient fused with the backward of the convolution layer in front of it, in ONE pass
+ * over the error map (Sec. 4.2 for the pool; Sec. 1 / Sec. 4.1 for the non-linearity and the bias):
+ *   dx[n][c][p][q] = act'(.) * (pool gradient of dy at [n][c][p][q])   act' through that layer's output y
+ *   db[c]          = sum_{n,p,q} dx[n][c][p][q]   of the values as stored (fp32, fixed order)
+ * kind: DSK_MAXPOOL (argmax as recorded by dsk_maxpool_fwd) or DSK_AVGPOOL (argmax ignored, may be NULL).
+ * dy[N][C][Ho][Wo], y and dx [N][C][H][W], all of type t; y may be NULL for DSK_ACT_NONE.  The result equals
+ * dsk_maxpool_bwd / dsk_avgpool_bwd followed by dsk_act_bwd_bias: dx is then the error map that
+ * dsk_conv_bwd_weight (with db = NULL) and dsk_conv_bwd_data of the convolution layer take. */
+size_t dsk_pool_bwd_act_bias_workspace_bytes(int kind, int N, int C, int H, int W, int k, int d, dsk_dtype t);
+int dsk_pool_bwd_act_bias(int kind, const void *dy, const uint8_t *argmax, const void *y, void *dx, float *db,
+                          int N, int C, int H, int W, int k, int d, dsk_act act, dsk_dtype t,
+                          void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Last layer: masked softmax cross-entropy (pixel mask of Sec. 4.3)           */
 /* ------------------------------------------------------------------------- */

@@ -24,6 +24,7 @@ SYMBOLS = ("dsk_plan", "dsk_status_string", "dsk_pad_image", "dsk_conv_workspace
            "dsk_conv_fwd", "dsk_conv_bwd_data", "dsk_conv_bwd_weight",
            "dsk_maxpool_fwd", "dsk_maxpool_bwd", "dsk_avgpool_fwd", "dsk_avgpool_bwd",
            "dsk_act_bwd", "dsk_act_bwd_bias_workspace_bytes", "dsk_act_bwd_bias",
+           "dsk_pool_bwd_act_bias_workspace_bytes", "dsk_pool_bwd_act_bias",
            "dsk_softmax_xent_workspace_bytes", "dsk_masked_softmax_xent", "dsk_masked_softmax_xent_static",
            "dsk_set_conv_algo")
 
@@ -74,6 +75,9 @@ def _load():
     lib.dsk_act_bwd_bias_workspace_bytes.argtypes = [ci]
     lib.dsk_act_bwd_bias_workspace_bytes.restype = sz
     lib.dsk_act_bwd_bias.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.dsk_pool_bwd_act_bias_workspace_bytes.argtypes = [ci] * 8
+    lib.dsk_pool_bwd_act_bias_workspace_bytes.restype = sz
+    lib.dsk_pool_bwd_act_bias.argtypes = [ci, vp, vp, vp, vp, vp] + [ci] * 6 + [ci, ci, vp, sz, vp]
     lib.dsk_softmax_xent_workspace_bytes.argtypes = [ci] * 4
     lib.dsk_softmax_xent_workspace_bytes.restype = sz
     lib.dsk_masked_softmax_xent.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
@@ -286,6 +290,30 @@ def dsk_act_bwd_bias(y, dy, act, db=None, ws=None):
     _check(lib.dsk_act_bwd_bias(None if act == DSK_ACT_NONE else _dev(y), _dev(dy), _dev(db, torch.float32),
                                 N, K, Ho, Wo, act, _dtype_code(dy), wsp, wsb, _stream()), "dsk_act_bwd_bias")
     return db
+
+
+def dsk_pool_bwd_act_bias_workspace_bytes(kind, N, C, H, W, k, d, code):
+    return int(lib.dsk_pool_bwd_act_bias_workspace_bytes(kind, N, C, H, W, k, d, code))
+
+
+def dsk_pool_bwd_act_bias(kind, dy, argmax, y, k, d, H, W, act, dx=None, db=None, ws=None):
+    """Pool gradient, non-linearity backward of the conv layer in front of the pool and that layer's bias
+    gradient in one pass.  Returns (dx, db)."""
+    N, C, Ho, Wo = dy.shape
+    assert Ho == H - (k - 1) * d and Wo == W - (k - 1) * d
+    if dx is None:
+        dx = torch.empty((N, C, H, W), dtype=dy.dtype, device=dy.device)
+    if db is None:
+        db = torch.empty((C,), dtype=torch.float32, device=dy.device)
+    need = dsk_pool_bwd_act_bias_workspace_bytes(kind, N, C, H, W, k, d, _dtype_code(dy))
+    if ws is None or ws.numel() * ws.element_size() < need:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dy.device)
+    wsp, wsb = _ws(ws)
+    _check(lib.dsk_pool_bwd_act_bias(kind, _dev(dy), None if argmax is None else _dev(argmax, torch.uint8),
+                                     None if act == DSK_ACT_NONE else _dev(y), _dev(dx), _dev(db, torch.float32),
+                                     N, C, H, W, k, d, act, _dtype_code(dy), wsp, wsb, _stream()),
+           "dsk_pool_bwd_act_bias")
+    return dx, db
 
 
 def dsk_softmax_xent_workspace_bytes(N, Cls, H, W):

@@ -243,6 +243,39 @@ int dsk_avgpool_bwd(const void *dy, void *dx, int N, int C, int H, int W, int k,
     return launch_avgpool_bwd(dy, dx, N, C, H, W, k, d, t, (hipStream_t)stream);
 }
 
+size_t dsk_pool_bwd_act_bias_workspace_bytes(int kind, int N, int C, int H, int W, int k, int d, dsk_dtype t)
+{
+    if ((kind != DSK_MAXPOOL && kind != DSK_AVGPOOL) || bad_dtype(t)) return 0;
+    if (N < 1 || C < 1 || H < 1 || W < 1 || k < 1 || d < 1 || (long)H - (long)(k - 1) * d < 1 || (long)W - (long)(k - 1) * d < 1)
+        return 0;
+    const size_t a = act_bwd_bias_ws_bytes(C);
+    const size_t b = pool_walk_ok(N, C, H, W, k, d, t) ? pool_bwd_act_bias_ws_bytes(N, C, H, W, k, d, t) : 0;
+    return a > b ? a : b;
+}
+
+int dsk_pool_bwd_act_bias(int kind, const void *dy, const uint8_t *argmax, const void *y, void *dx, float *db,
+                          int N, int C, int H, int W, int k, int d, dsk_act act, dsk_dtype t,
+                          void *ws, size_t ws_bytes, void *stream)
+{
+    if (kind != DSK_MAXPOOL && kind != DSK_AVGPOOL) return DSK_EINVAL;
+    int rc = pool_check(dy, dx, N, C, H, W, k, d, t);
+    if (rc != DSK_OK) return rc;
+    if (kind == DSK_MAXPOOL && bad_ptr(argmax)) return DSK_EINVAL;
+    if (act < DSK_ACT_NONE || act > DSK_ACT_TANH || bad_ptr(db)) return DSK_EINVAL;
+    if (act != DSK_ACT_NONE && bad_ptr(y)) return DSK_EINVAL;
+    const size_t need = dsk_pool_bwd_act_bias_workspace_bytes(kind, N, C, H, W, k, d, t);
+    if (ws == nullptr || !aligned16(ws) || ws_bytes < need) return DSK_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    clear_errors();
+    if (pool_walk_ok(N, C, H, W, k, d, t))
+        return launch_pool_walk_bwd(dy, argmax, dx, y, db, act, ws, N, C, H, W, k, d, kind == DSK_MAXPOOL, t, st);
+    // other window sizes: the two passes one after the other
+    rc = kind == DSK_MAXPOOL ? launch_maxpool_bwd(dy, argmax, dx, N, C, H, W, k, d, t, st)
+                             : launch_avgpool_bwd(dy, dx, N, C, H, W, k, d, t, st);
+    if (rc != DSK_OK) return rc;
+    return launch_act_bwd_bias(y, dx, db, N, C, (long)H * W, act, t, ws, st);
+}
+
 int dsk_act_bwd(const void *y, void *dy, size_t count, dsk_act act, dsk_dtype t, void *stream)
 {
     if (bad_ptr(y) || bad_ptr(dy) || bad_dtype(t)) return DSK_EINVAL;

@@ -129,6 +129,13 @@ int launch_avgpool_fwd(const void *x, void *y, int N, int C, int H, int W, int k
                        hipStream_t st);
 int launch_avgpool_bwd(const void *dy, void *dx, int N, int C, int H, int W, int k, int d, dsk_dtype t,
                        hipStream_t st);
+// 2 x 2 and 3 x 3 windows: a thread walks down a residue class of rows (dsk_pool_walk.hip)
+bool pool_walk_ok(int N, int C, int H, int W, int k, int d, dsk_dtype t);
+int launch_pool_walk_fwd(const void *x, void *y, uint8_t *am, int N, int C, int H, int W, int k, int d, bool is_max,
+                         dsk_dtype t, hipStream_t st);
+size_t pool_bwd_act_bias_ws_bytes(int N, int C, int H, int W, int k, int d, dsk_dtype t);
+int launch_pool_walk_bwd(const void *dy, const uint8_t *am, void *dx, const void *yprev, float *db, int act, void *ws,
+                         int N, int C, int H, int W, int k, int d, bool is_max, dsk_dtype t, hipStream_t st);
 int launch_pad_image(const float *x, void *xpad, int N, int C, int H, int W, int lo, int hi, dsk_dtype out,
                      hipStream_t st);
 int launch_act_bwd(const void *y, void *dy, size_t count, int act, dsk_dtype t, hipStream_t st);

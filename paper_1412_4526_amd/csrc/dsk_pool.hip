@@ -682,6 +682,10 @@ static int pool_fwd_dispatch(const void *x, void *y, uint8_t *am, int N, int C, 
                              hipStream_t st)
 {
     if (pool_span_ok(N, C, H, W, k, d, sizeof(T))) return pool_span_fwd<IS_MAX>(x, y, am, N, C, H, W, k, st);
+    // 2 x 2 and 3 x 3 windows: the walking kernels with 16-byte accesses -- unless the rows of an fp32 map begin at
+    // odd multiples of 4 bytes (odd width), where a 16-byte access per lane is slower than four 4-byte ones
+    if (pool_walk_ok(N, C, H, W, k, d, sizeof(T) == 4 ? DSK_F32 : DSK_BF16) && (sizeof(T) == 2 || W % 2 == 0))
+        return launch_pool_walk_fwd(x, y, am, N, C, H, W, k, d, IS_MAX, sizeof(T) == 4 ? DSK_F32 : DSK_BF16, st);
     // pairs pay where the instruction count binds: 2-byte pixels (fp32 kernels run as fast with one pixel per thread)
     return pool_pairs(W, d) && sizeof(T) == 2 ? pool_fwd_dispatch<T, IS_MAX, 2>(x, y, am, N, C, H, W, k, d, st)
                             : pool_fwd_dispatch<T, IS_MAX, 1>(x, y, am, N, C, H, W, k, d, st);
@@ -693,6 +697,9 @@ static int pool_bwd_dispatch(const void *dy, const uint8_t *am, void *dx, int N,
 {
     if (pool_span_ok(N, C, H, W, k, d, sizeof(T)) && (W - (k - 1)) % 4 == 0)
         return pool_span_bwd<IS_MAX>(dy, am, dx, N, C, H, W, k, st);
+    if (pool_walk_ok(N, C, H, W, k, d, sizeof(T) == 4 ? DSK_F32 : DSK_BF16))
+        return launch_pool_walk_bwd(dy, am, dx, nullptr, nullptr, DSK_ACT_NONE, nullptr, N, C, H, W, k, d, IS_MAX,
+                                    sizeof(T) == 4 ? DSK_F32 : DSK_BF16, st);
     // ... and the max-pool gradient, which loads a tap index with every pixel
     return pool_pairs(W, d) && (sizeof(T) == 2 || IS_MAX) ? pool_bwd_dispatch<T, IS_MAX, 2>(dy, am, dx, N, C, H, W, k, d, st)
                             : pool_bwd_dispatch<T, IS_MAX, 1>(dy, am, dx, N, C, H, W, k, d, st);

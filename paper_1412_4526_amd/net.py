@@ -15,10 +15,13 @@ class WholeImageNet:
     net: object with C0, patch, layers (each: kind, K, k, s, act) -- the ORIGINAL CNN.
     dtype: "f32", or "bf16" (activations and error maps stored in bfloat16, fp32
     accumulation; scores, loss, weights and their gradients stay fp32).
+    fuse=False keeps every backward step a call of its own (pool gradient, then
+    non-linearity backward + bias gradient).
     """
 
-    def __init__(self, net, N, H, W, dtype="f32", device="cuda:0", train=True):
+    def __init__(self, net, N, H, W, dtype="f32", device="cuda:0", train=True, fuse=True):
         self.net, self.N, self.H, self.W = net, N, H, W
+        self.fuse = fuse      # backward: pool gradient + non-linearity backward + bias gradient as one call
         self.device = torch.device(device)
         self.act_dtype = torch.float32 if dtype == "f32" else torch.bfloat16
         self.code = B.DSK_F32 if dtype == "f32" else B.DSK_BF16
@@ -54,6 +57,8 @@ class WholeImageNet:
         if train:
             ws_bytes = max(ws_bytes, B.dsk_softmax_xent_workspace_bytes(N, last.K, H, W))
             ws_bytes = max([ws_bytes] + [B.dsk_act_bwd_bias_workspace_bytes(p.K) for p in self.plan])
+            ws_bytes = max([ws_bytes] + [B.dsk_pool_bwd_act_bias_workspace_bytes(p.kind, N, p.C, p.H, p.W, p.k, p.d, self.code)
+                                         for p in self.plan if p.kind != B.DSK_CONV])
             self.loss = torch.zeros((1,), dtype=torch.float32, device=dev)
             self.dw = [torch.empty_like(w) for w in self.weights]
             self.db = [torch.empty_like(b) for b in self.biases]
@@ -116,19 +121,29 @@ class WholeImageNet:
         self._timed("softmax_xent", L, B.dsk_masked_softmax_xent, self.scores, labels, mask, loss=self.loss,
                     dscores=g, ws=self.ws)
         ci = len(self.weights) - 1
+        act_done = False      # the error map in g already went through the non-linearity of the conv layer it belongs to
         for l in range(L - 1, -1, -1):
             p = self.plan[l]
             x, y = self.maps[l], self.maps[l + 1]
             gin = self._g[1 - cur][:x.numel()].view(x.shape) if l > 0 else None
             if p.kind == B.DSK_CONV:
-                # non-linearity backward and bias gradient in one pass over the error map
-                self._timed("act_bwd", l, B.dsk_act_bwd_bias, y, g, p.act, db=self.db[ci], ws=self.ws)
+                if not act_done:
+                    # non-linearity backward and bias gradient in one pass over the error map
+                    self._timed("act_bwd", l, B.dsk_act_bwd_bias, y, g, p.act, db=self.db[ci], ws=self.ws)
+                act_done = False
                 self._timed("conv_bwd_weight", l, B.dsk_conv_bwd_weight, x, g, p.k, p.k, p.d, dw=self.dw[ci],
                             want_db=False, ws=self.ws)
                 if l > 0:        # nobody needs the error map of the image itself
                     self._timed("conv_bwd_data", l, B.dsk_conv_bwd_data, g, self.weights[ci], p.d, p.H, p.W,
                                 dx=gin, ws=self.ws)
                 ci -= 1
+            elif l > 0 and self.plan[l - 1].kind == B.DSK_CONV and self.fuse:
+                # the pool's gradient, the non-linearity backward of the conv layer in front of it and that
+                # layer's bias gradient: one pass (x is that layer's output)
+                q = self.plan[l - 1]
+                self._timed("pool_bwd_act", l, B.dsk_pool_bwd_act_bias, p.kind, g, self.argmax[l], x, p.k, p.d,
+                            p.H, p.W, q.act, dx=gin, db=self.db[ci], ws=self.ws)
+                act_done = True
             elif p.kind == B.DSK_MAXPOOL:
                 self._timed("maxpool_bwd", l, B.dsk_maxpool_bwd, g, self.argmax[l], p.k, p.d, p.H, p.W, dx=gin)
             else:

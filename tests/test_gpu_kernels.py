@@ -375,3 +375,54 @@ def test_launch_errors_are_reported_not_raised_as_faults():
     with pytest.raises(dsk.DskError) as e:
         dsk.dsk_maxpool_fwd(x, 2, 8)
     assert e.value.status == dsk.DSK_ESHAPE
+
+
+# odd widths and spacings: 16-byte accesses at any alignment, partial groups at the row ends
+WALK_CASES = [(1, 3, 37, 53, 2, 3), (2, 2, 41, 67, 3, 1), (1, 2, 150, 39, 2, 5), (1, 1, 300, 21, 3, 7), (1, 2, 19, 5, 2, 1),
+              (1, 2, 200, 130, 2, 2), (1, 1, 33, 1030, 3, 6)]
+
+
+@pytest.mark.parametrize("case", POOL_CASES[:7] + WALK_CASES, ids=lambda c: "N%dC%dH%dW%dk%dd%d" % c)
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("is_max", [True, False], ids=["max", "avg"])
+def test_pool_bwd_act_bias(case, dt, is_max):
+    """Pool gradient + non-linearity backward of the layer in front + its bias gradient in one call, against
+    the oracle's pool gradient times act'(y) written out; also the pool kernels themselves on odd shapes."""
+    N, C, H, W, k, d = case
+    _say("pool_bwd_act_bias", case, dt, is_max)
+    bf = dt == torch.bfloat16
+    rng = np.random.default_rng(hash(case) % 2**31 + 9)
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    x[rng.random(x.shape) < 0.3] = 0.0          # closed gates of the ReLU in front of the pool
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    dy = rng.standard_normal((N, C, Ho, Wo)).astype(np.float32)
+    if bf:
+        x, dy = bf16_round(x), bf16_round(dy)
+    ry, ram = oracle_pool_fwd(x, k, d, is_max)
+    rdx = oracle_pool_bwd(x, k, d, is_max, dy)
+    xt, gt = _t(x, dt), _t(dy, dt)
+    if is_max:
+        y, am = dsk.dsk_maxpool_fwd(xt, k, d)
+        assert np.array_equal(to_np(y), ry) and np.array_equal(am.cpu().numpy().astype(np.int32), ram)
+        plain = dsk.dsk_maxpool_bwd(gt, am, k, d, H, W)
+    else:
+        y, am = dsk.dsk_avgpool_fwd(xt, k, d), None
+        assert_close(y, ry, "avgpool y", bf16=bf)
+        plain = dsk.dsk_avgpool_bwd(gt, k, d, H, W)
+    assert_close(plain, rdx, "pool dx", bf16=bf)
+    kind = dsk.DSK_MAXPOOL if is_max else dsk.DSK_AVGPOOL
+    for act in (1, 2, 0):
+        f = (x > 0) if act == 1 else (1 - x.astype(np.float64) ** 2) if act == 2 else 1.0
+        want = rdx * f
+        dx, db = dsk.dsk_pool_bwd_act_bias(kind, gt, am, xt, k, d, H, W, act)
+        torch.cuda.synchronize()
+        assert_close(dx, want, "fused dx act %d" % act, bf16=bf)
+        assert_close(db, to_np(dx).sum(axis=(0, 2, 3)), "fused db act %d (sum of the stored map)" % act)
+        if not bf:
+            assert_close(db, want.sum(axis=(0, 2, 3)), "fused db act %d" % act)
+        # the same as the two separate calls, bit for bit
+        sep = plain.clone()
+        db2 = dsk.dsk_act_bwd_bias(xt, sep, act)
+        assert torch.equal(dx, sep) or (bf and act == 2)      # bf16 tanh: the separate form rounds twice
+        if not (bf and act == 2):
+            assert_close(db, to_np(db2), "db of the two forms")

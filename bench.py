@@ -127,6 +127,9 @@ def main():
     ap.add_argument("--algo", type=int, default=0)
     ap.add_argument("--no-fuse", action="store_true",
                     help="backward: pool gradient and non-linearity backward + bias gradient as separate calls")
+    ap.add_argument("--compare-fast-scanning", action="store_true",
+                    help="also time the forward pass of the comparison method (fast scanning: strided layers run once "
+                         "per starting offset on fragments) on the same workload; reported under \"fast_scanning\"")
     ap.add_argument("--layers", action="store_true", help="print the per-call table to stderr")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference "
@@ -269,6 +272,26 @@ def main():
         "worst_pool_frac_of_hbm_peak": None if worst_pool is None else round(worst_pool, 4),
         "layers": sorted(rows, key=lambda r: (r["layer"], r["call"])),
     }
+    if args.compare_fast_scanning:
+        fs = dsk.FastScanNet(cfg.net, cfg.N, cfg.H, cfg.W, dtype, dev)
+        fs.load_params(wl.weights, wl.biases)
+        for _ in range(args.warmup):
+            fs.forward(image)
+        torch.cuda.synchronize()
+        fs.timeline = []
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fs.forward(image)
+        torch.cuda.synchronize()
+        fdt = time.perf_counter() - t0
+        fper = {}
+        for tag, layer, e0, e1 in fs.timeline:
+            fper.setdefault((tag, layer), []).append(e0.elapsed_time(e1))
+        out["fast_scanning"] = {
+            "what": "forward pass of the comparison method on the same workload (it has no backward pass)",
+            "ms_per_step": fdt / args.steps * 1e3, "labelled_pixels_per_s": pixels * args.steps / fdt,
+            "fragments_per_image_after_each_layer": fs.fragments(),
+            "layers": [{"call": k[0], "layer": k[1], "ms": round(sum(v) / len(v), 4)} for k, v in sorted(fper.items(), key=lambda kv: kv[0][1])]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, wl, args.forward_only)
     print(json.dumps(out))

@@ -231,6 +231,32 @@ int dsk_masked_softmax_xent_static(const float *scores, const int32_t *labels, c
                                    void *stream);
 
 /* ------------------------------------------------------------------------- */
+/* Fast scanning: the method the paper compares with (Sec. 2; Sec. 3.6, last    */
+/* paragraph; Table 1).  Forward only.  A comparator, not part of the hot path. */
+/* ------------------------------------------------------------------------- */
+
+/* Fast scanning keeps every layer's ORIGINAL stride s and runs a strided layer s*s times, once per
+ * starting offset (ay, ax); every run yields one output fragment.  With fragment spacing D (the product of
+ * the strides so far) an image has D*D fragments, stored as a batch [N*D*D][C][h][w] with index
+ * n*D*D + fy*D + fx: fragment (fy, fx) holds the whole-image map's entries (fy + D*u, fx + D*v); all
+ * fragments have the size of the largest one, h = ceil(H/D), smaller ones leave their last row / column
+ * unused.  Stride-1 layers are ordinary dense layers on that batch (dsk_conv_fwd with d = 1).
+ *
+ * dsk_fs_pool_fwd / dsk_fs_conv_fwd: one strided layer, all s*s offsets in one call:
+ *   out fragment (fy + D*ay, fx + D*ax) at spacing D*s, entry (u, v)
+ *       = pool / conv of in fragment (fy, fx) over the taps (ay + s*u + a, ax + s*v + b), 0 <= a, b < k
+ * in[N*D*D][C][hi][wi], out[N*D*s*D*s][C or K][ho][wo]; taps outside the stored fragment are skipped (they
+ * only ever belong to entries that are unused themselves).  One thread per output entry, taps read at
+ * stride s with the run's offset: that access pattern is the method.
+ * dsk_fs_assemble: the label map out[n][c][i][j] = fragment (n, i % D, j % D), entry (i / D, j / D). */
+int dsk_fs_pool_fwd(int kind, const void *in, void *out, int N, int D, int C, int hi, int wi, int k, int s,
+                    int ho, int wo, dsk_dtype t, void *stream);
+int dsk_fs_conv_fwd(const void *in, const float *w, const float *b, void *out, int N, int D, int C, int hi, int wi,
+                    int K, int k, int s, int ho, int wo, dsk_act act, dsk_dtype t, void *stream);
+int dsk_fs_assemble(const void *frag, void *out, int N, int D, int C, int hf, int wf, int H, int W,
+                    dsk_dtype tin, dsk_dtype tout, void *stream);
+
+/* ------------------------------------------------------------------------- */
 /* Kernel selection (diagnostics)                                              */
 /* ------------------------------------------------------------------------- */
 

@@ -8,3 +8,4 @@ from . import binding  # noqa: F401
 from .binding import *  # noqa: F401,F403
 from .binding import DskError, lib, LIB_PATH, SYMBOLS, status_string, torch_dtype  # noqa: F401
 from .net import WholeImageNet  # noqa: F401
+from .fastscan import FastScanNet  # noqa: F401

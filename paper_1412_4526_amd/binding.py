@@ -26,6 +26,7 @@ SYMBOLS = ("dsk_plan", "dsk_status_string", "dsk_pad_image", "dsk_conv_workspace
            "dsk_act_bwd", "dsk_act_bwd_bias_workspace_bytes", "dsk_act_bwd_bias",
            "dsk_pool_bwd_act_bias_workspace_bytes", "dsk_pool_bwd_act_bias",
            "dsk_softmax_xent_workspace_bytes", "dsk_masked_softmax_xent", "dsk_masked_softmax_xent_static",
+           "dsk_fs_pool_fwd", "dsk_fs_conv_fwd", "dsk_fs_assemble",
            "dsk_set_conv_algo")
 
 
@@ -82,6 +83,9 @@ def _load():
     lib.dsk_softmax_xent_workspace_bytes.restype = sz
     lib.dsk_masked_softmax_xent.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.dsk_masked_softmax_xent_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
+    lib.dsk_fs_pool_fwd.argtypes = [ci, vp, vp] + [ci] * 9 + [ci, vp]
+    lib.dsk_fs_conv_fwd.argtypes = [vp, vp, vp, vp] + [ci] * 10 + [ci, ci, vp]
+    lib.dsk_fs_assemble.argtypes = [vp, vp] + [ci] * 7 + [ci, ci, vp]
     lib.dsk_set_conv_algo.argtypes = [ci]
     for name in SYMBOLS:
         getattr(lib, name)      # AttributeError here = header and library disagree
@@ -348,3 +352,37 @@ def dsk_masked_softmax_xent_static(scores, labels, mask, loss, dscores):
                                               _dtype_code(dscores), N, Cls, H, W, _stream()),
            "dsk_masked_softmax_xent_static")
     return loss, dscores
+
+
+# --------------------------------------------------------------------------- fast scanning (comparison method)
+def dsk_fs_pool_fwd(kind, x, D, k, s, ho, wo, out=None):
+    """x [N*D*D, C, hi, wi] -> [N*D*s*D*s, C, ho, wo]: a strided pool run once per starting offset."""
+    F, C, hi, wi = x.shape
+    N = F // (D * D)
+    if out is None:
+        out = torch.empty((F * s * s, C, ho, wo), dtype=x.dtype, device=x.device)
+    _check(lib.dsk_fs_pool_fwd(kind, _dev(x), _dev(out), N, D, C, hi, wi, k, s, ho, wo, _dtype_code(x), _stream()),
+           "dsk_fs_pool_fwd")
+    return out
+
+
+def dsk_fs_conv_fwd(x, w, b, D, s, ho, wo, act=DSK_ACT_NONE, out=None):
+    F, C, hi, wi = x.shape
+    K, Cw, k, _ = w.shape
+    assert Cw == C
+    N = F // (D * D)
+    if out is None:
+        out = torch.empty((F * s * s, K, ho, wo), dtype=x.dtype, device=x.device)
+    _check(lib.dsk_fs_conv_fwd(_dev(x), _dev(w, torch.float32), None if b is None else _dev(b, torch.float32), _dev(out),
+                               N, D, C, hi, wi, K, k, s, ho, wo, act, _dtype_code(x), _stream()), "dsk_fs_conv_fwd")
+    return out
+
+
+def dsk_fs_assemble(frag, D, H, W, out=None, out_dtype=None):
+    F, C, hf, wf = frag.shape
+    N = F // (D * D)
+    if out is None:
+        out = torch.empty((N, C, H, W), dtype=out_dtype or frag.dtype, device=frag.device)
+    _check(lib.dsk_fs_assemble(_dev(frag), _dev(out), N, D, C, hf, wf, H, W, _dtype_code(frag), _dtype_code(out),
+                               _stream()), "dsk_fs_assemble")
+    return out

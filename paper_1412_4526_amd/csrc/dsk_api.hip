@@ -76,6 +76,51 @@ const char *dsk_status_string(int status)
     }
 }
 
+// ---- fast scanning (comparison method) ----
+static int fs_check(int N, int D, int C, int hi, int wi, int K, int k, int s, int ho, int wo)
+{
+    if (N < 1 || D < 1 || C < 1 || hi < 1 || wi < 1 || K < 1 || k < 1 || s < 1 || ho < 1 || wo < 1) return DSK_EINVAL;
+    if ((long)D * s > 4096) return DSK_ESHAPE;
+    const long fi = (long)N * D * D, fo = fi * s * s;
+    if (fi * C * hi * wi > kMaxElems || fo * K * ho * wo > kMaxElems) return DSK_ESHAPE;
+    // the last entry of the run with offset 0 has its first tap inside the fragment
+    if ((long)s * (ho - 1) >= hi || (long)s * (wo - 1) >= wi) return DSK_ESHAPE;
+    return DSK_OK;
+}
+
+int dsk_fs_pool_fwd(int kind, const void *in, void *out, int N, int D, int C, int hi, int wi, int k, int s, int ho, int wo,
+                    dsk_dtype t, void *stream)
+{
+    if (kind != DSK_MAXPOOL && kind != DSK_AVGPOOL) return DSK_EINVAL;
+    if (bad_ptr(in) || bad_ptr(out) || bad_dtype(t)) return DSK_EINVAL;
+    const int rc = fs_check(N, D, C, hi, wi, C, k, s, ho, wo);
+    if (rc != DSK_OK) return rc;
+    clear_errors();
+    return launch_fs_pool(in, out, kind == DSK_MAXPOOL, N, D, C, hi, wi, k, s, ho, wo, t, (hipStream_t)stream);
+}
+
+int dsk_fs_conv_fwd(const void *in, const float *w, const float *b, void *out, int N, int D, int C, int hi, int wi, int K,
+                    int k, int s, int ho, int wo, dsk_act act, dsk_dtype t, void *stream)
+{
+    if (bad_ptr(in) || bad_ptr(w) || bad_ptr(out) || (b && !aligned16(b)) || bad_dtype(t)) return DSK_EINVAL;
+    if (act < DSK_ACT_NONE || act > DSK_ACT_TANH) return DSK_EINVAL;
+    const int rc = fs_check(N, D, C, hi, wi, K, k, s, ho, wo);
+    if (rc != DSK_OK) return rc;
+    clear_errors();
+    return launch_fs_conv(in, w, b, out, N, D, C, hi, wi, K, k, s, ho, wo, act, t, (hipStream_t)stream);
+}
+
+int dsk_fs_assemble(const void *frag, void *out, int N, int D, int C, int hf, int wf, int H, int W, dsk_dtype tin,
+                    dsk_dtype tout, void *stream)
+{
+    if (bad_ptr(frag) || bad_ptr(out) || bad_dtype(tin) || bad_dtype(tout)) return DSK_EINVAL;
+    if (N < 1 || D < 1 || C < 1 || hf < 1 || wf < 1 || H < 1 || W < 1) return DSK_EINVAL;
+    if ((long)(H - 1) / D >= hf || (long)(W - 1) / D >= wf) return DSK_ESHAPE;      // the fragments do not cover the map
+    if ((long)N * D * D * C * hf * wf > kMaxElems || (long)N * C * H * W > kMaxElems) return DSK_ESHAPE;
+    clear_errors();
+    return launch_fs_assemble(frag, out, N, D, C, hf, wf, H, W, tin, tout, (hipStream_t)stream);
+}
+
 int dsk_set_conv_algo(int algo)
 {
     const int prev = g_conv_algo;

@@ -136,6 +136,13 @@ int launch_pool_walk_fwd(const void *x, void *y, uint8_t *am, int N, int C, int 
 size_t pool_bwd_act_bias_ws_bytes(int N, int C, int H, int W, int k, int d, dsk_dtype t);
 int launch_pool_walk_bwd(const void *dy, const uint8_t *am, void *dx, const void *yprev, float *db, int act, void *ws,
                          int N, int C, int H, int W, int k, int d, bool is_max, dsk_dtype t, hipStream_t st);
+// fast scanning, the comparison method (dsk_fastscan.hip)
+int launch_fs_pool(const void *in, void *out, bool is_max, int N, int D, int C, int hi, int wi, int k, int s, int ho, int wo,
+                   dsk_dtype t, hipStream_t st);
+int launch_fs_conv(const void *in, const float *w, const float *b, void *out, int N, int D, int C, int hi, int wi, int K, int k,
+                   int s, int ho, int wo, int act, dsk_dtype t, hipStream_t st);
+int launch_fs_assemble(const void *frag, void *out, int N, int D, int C, int hf, int wf, int H, int W, dsk_dtype ti, dsk_dtype to,
+                       hipStream_t st);
 int launch_pad_image(const float *x, void *xpad, int N, int C, int H, int W, int lo, int hi, dsk_dtype out,
                      hipStream_t st);
 int launch_act_bwd(const void *y, void *dy, size_t count, int act, dsk_dtype t, hipStream_t st);

@@ -137,6 +137,42 @@ def test_graph_replay_matches_eager():
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("case", SMALL_NETS, ids=lambda c: c[0].name)
+def test_fast_scanning_comparator_small_nets(case):
+    """The comparison method (fast scanning: strided layers run once per starting offset, fragments re-organised at
+    the end) gives the same label map: against the oracle at every pixel."""
+    net, N, H, W, frac = case
+    _say("fast scanning", net.name)
+    wl = make_workload(net, N, H, W, frac, seed=0, bias_std=0.1)
+    params = oracle.pack_params(wl.weights, wl.biases)
+    xpad = oracle.pad_image(wl.image, net.patch)
+    ref = oracle.scan_forward(net, params, xpad, all_pixels(N, H, W)).reshape(N, H, W, -1).transpose(0, 3, 1, 2)
+    fs = dsk.FastScanNet(net, N, H, W, "f32", DEV)
+    fs.load_params(wl.weights, wl.biases)
+    scores = fs.forward(torch.from_numpy(wl.image).to(DEV))
+    torch.cuda.synchronize()
+    assert_close(scores, ref, "fast scanning scores")
+    strides = int(np.prod([L.s for L in net.layers]))
+    assert fs.fragments()[-1] == strides * strides
+
+
+def test_fast_scanning_comparator_plain_cnn1():
+    """Plain CNN_1 of the paper's Table 1 at full size (256 x 256 labelled pixels): 64, then 256 fragments per image."""
+    cfg = CONFIGS[5]
+    net = cfg.net
+    wl = make_workload(net, cfg.N, cfg.H, cfg.W, cfg.mask_frac, cfg.seed)
+    params = oracle.pack_params(wl.weights, wl.biases)
+    xpad = oracle.pad_image(wl.image, net.patch)
+    pix = sample_pixels(cfg.N, cfg.H, cfg.W, 256, seed=4)
+    ref = oracle.scan_forward(net, params, xpad, pix)
+    fs = dsk.FastScanNet(net, cfg.N, cfg.H, cfg.W, "f32", DEV)
+    fs.load_params(wl.weights, wl.biases)
+    scores = fs.forward(torch.from_numpy(wl.image).to(DEV))
+    torch.cuda.synchronize()
+    assert fs.fragments() == [1, 64, 64, 256, 256]
+    assert_close(to_np(scores[pix[:, 0], :, pix[:, 1], pix[:, 2]]), ref, "fast scanning scores at 256 sampled pixels")
+
+
 # ---------------------------------------------------------------------------
 # Full-size benchmark configurations
 # ---------------------------------------------------------------------------

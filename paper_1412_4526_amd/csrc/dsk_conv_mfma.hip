@@ -878,6 +878,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     const TI *dy_end = dy + (long)p.N * p.K * HoWo, *x_end = x + (long)p.N * p.C * HW;
     int st_nr_dy = 0, st_nr_x = 0;             // rows of the staged tile that exist
     bool st_dcol_ok = false, st_col_ok = false; // this lane's column exists
+    bool st_full = false;                       // every row, filter and channel of the staged tile exists (uniform)
     auto load_tile = [&](long pt) {
         const int ct = (int)(pt % p.n_coltile);
         const int rt = (int)((pt / p.n_coltile) % p.n_rowtile);
@@ -923,7 +924,8 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         const unsigned xlane_off = st_col_ok ? (unsigned)lane : 0u;
         st_nr_x = (p.H - u0 + p.d - 1) / p.d;             // x rows u0 + r*d that exist
         st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
-        if (full_blocks && st_nr_dy >= PH && st_nr_x == p.xrows) {
+        st_full = full_blocks && st_nr_dy >= PH && st_nr_x == p.xrows;
+        if (st_full) {
             // every row, filter and channel of the tile exists (all but the tiles at the bottom
             // of a map): buffer loads with one per-lane offset for the whole tile and a scalar
             // offset per load; only the lane's column may fall outside (read column 0 then)
@@ -992,13 +994,23 @@ conv_bwd_weight_mfma_kernel(BwParams p)
                     }
             }
         } else {
+        if (PREFETCH && st_full) {      // (uniform) only the lane's column may be outside the map: one mask for all entries
 #pragma unroll
-        for (int i = 0; i < 16 * FB; ++i) {
-            const int seg = wave * 2 + hi + 8 * i;
-            const bool ok = st_dcol_ok && (seg >> 2) < nf_valid && (seg & 3) < st_nr_dy;
-            const float v = ok ? dr[i] : 0.f;
-            if (BFM) dyb[(seg >> 2) * DYB + (seg & 3) * PW + lo] = bw_raw16(v);
-            else dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
+            for (int i = 0; i < 16 * FB; ++i) {
+                const int seg = wave * 2 + hi + 8 * i;
+                const float v = st_dcol_ok ? dr[i] : 0.f;
+                if (BFM) dyb[(seg >> 2) * DYB + (seg & 3) * PW + lo] = bw_raw16(v);
+                else dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16 * FB; ++i) {
+                const int seg = wave * 2 + hi + 8 * i;
+                const bool ok = st_dcol_ok && (seg >> 2) < nf_valid && (seg & 3) < st_nr_dy;
+                const float v = ok ? dr[i] : 0.f;
+                if (BFM) dyb[(seg >> 2) * DYB + (seg & 3) * PW + lo] = bw_raw16(v);
+                else dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
+            }
         }
         if (lane < p.xcols) {
 #pragma unroll
@@ -1006,8 +1018,10 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
                 for (int r = 0; r < XR; ++r)
                     if (r < p.xrows) {
-                        const bool ok = st_col_ok && wave + 4 * ci < nc_valid && r < st_nr_x;
-                        const float v = ok ? xr[ci][r] : 0.f;
+                        // No zeroing here: an x entry outside the map (it was read from the tile's base instead, a
+                        // finite value of the map) only ever meets dy entries outside ITS map, which are zeros,
+                        // and the columns of channels beyond C are never written out.
+                        const float v = xr[ci][r];
                         if (BFM) xb16[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = bw_raw16(v);
                         else xs[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = v;
                     }
@@ -1048,18 +1062,40 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             continue;
         }
         // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
+        // Steps of two pixel pairs (one two-address LDS read per operand).  The operands of step s+1 are read into
+        // a second set of registers BEFORE the matrix instructions of step s are issued: with one set, a read could
+        // only be issued after the instructions that use its registers, and its latency would be exposed once per
+        // step.  The eight steps of a tile row are unrolled, so that every offset is an immediate.
         const float *ab = dys + (my_fb * 32 + lo) * DY_STRIDE + hi;
         const float *bb = xs + blane + hi;
-        for (int r = ROWSPLIT ? wave : 0; r < (ROWSPLIT ? wave + 1 : PH); ++r) {
-#pragma unroll 4
-            for (int q = 0; q < PW / 2; ++q) {
-                const float A = ab[r * PW + 2 * q];
-                float B[TPW];
+        constexpr int NS = PW / 4;      // steps per row
+        float A[2][2], B[2][TPW][2];
+        auto lds_step = [&](const float *ar, const float *br, int st, int buf) __attribute__((always_inline)) {
+            A[buf][0] = ar[4 * st];
+            A[buf][1] = ar[4 * st + 2];
 #pragma unroll
-                for (int t = 0; t < TPW; ++t) B[t] = bb[boff[t] + r * p.xcols + 2 * q];
+            for (int t = 0; t < TPW; ++t) {
+                B[buf][t][0] = br[boff[t] + 4 * st];
+                B[buf][t][1] = br[boff[t] + 4 * st + 2];
+            }
+        };
+        const int r_first = ROWSPLIT ? wave : 0, r_last = ROWSPLIT ? wave : PH - 1;
+        lds_step(ab + r_first * PW, bb + r_first * p.xcols, 0, 0);
+        for (int r = r_first; r <= r_last; ++r) {
+            const float *ar = ab + r * PW, *br = bb + r * p.xcols;
+            const int rn = r < r_last ? r + 1 : r_first;      // (after the last row: read for nothing)
+            const float *arn = ab + rn * PW, *brn = bb + rn * p.xcols;
 #pragma unroll
-                for (int t = 0; t < TPW; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(A, B[t], acc[t], 0, 0, 0);
+            for (int st = 0; st < NS; ++st) {
+                if (st + 1 < NS) lds_step(ar, br, st + 1, (st + 1) & 1);
+                else lds_step(arn, brn, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);      // the scheduler would sink the reads to their uses, one step later
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t)
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[st & 1][h], B[st & 1][t][h], acc[t], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }

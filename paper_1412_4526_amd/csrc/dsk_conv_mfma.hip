@@ -259,6 +259,14 @@ gemm_conv_kernel(GcParams p)
             }
         }
 
+        // Where no zeroing is needed when the tile is written to LDS (uniform).  Forward: a tile entry outside the
+        // map (read from offset 0 instead: a finite value of the map) only feeds outputs outside the output map,
+        // which are not stored.  Backward-data: tiles that lie wholly inside the error map.  (Channels beyond Cin
+        // meet zero weights, and the padding at the end of the LDS tile is never read.)
+        const bool no_zeroing = (p.off_h == 0 && p.off_w == 0) ||
+                                (u0 - p.off_h >= 0 && u0 - p.off_h + (p.rows - 1) * p.d < p.Hin &&
+                                 v0 - p.off_w >= 0 && v0 - p.off_w + p.cols <= p.Win);
+
         f32x16 acc[WM][4];
 #pragma unroll
         for (int wm = 0; wm < WM; ++wm)
@@ -299,9 +307,15 @@ gemm_conv_kernel(GcParams p)
         fetch(cb * p.Cc);
         for (int ch = cb; ch < ce; ++ch) {
             __syncthreads();      // every wave is done reading the previous chunk
+            if (no_zeroing) {
 #pragma unroll
-            for (int i = 0; i < XI; ++i)
-                if (i < p.n_xi) xs[tid + i * kThreads] = (zero >> i) & 1u ? 0.f : xv[i];
+                for (int i = 0; i < XI; ++i)
+                    if (i < p.n_xi) xs[tid + i * kThreads] = xv[i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < XI; ++i)
+                    if (i < p.n_xi) xs[tid + i * kThreads] = (zero >> i) & 1u ? 0.f : xv[i];
+            }
 #pragma unroll
             for (int q = 0; q < WI; ++q)
                 if (q < p.n_wi) ((f32x4 *)wsm)[q * kThreads + tid] = wv[q];

@@ -21,7 +21,7 @@
 namespace dsk {
 
 static constexpr int kThreads = 256;
-static constexpr int kCountBlocks = 1024;      // at most; a share is a multiple of 16 pixels
+static constexpr int kCountBlocks = 1024;      // at most; a share is a multiple of 1024 pixels
 
 // workspace (32-bit words): [0..3] unused, [4 .. 4+kCountBlocks) counts, then kCountBlocks loss sums
 static inline long n_blocks(long pixels) { return (pixels + kThreads - 1) / kThreads; }
@@ -113,14 +113,14 @@ mask_loss_kernel(const float *__restrict__ scores, const int32_t *__restrict__ l
         const long n = q / HW, hw = q - n * HW;
         nll += pixel_nll<CMAX>(scores + n * Cls * HW + hw, HW, Cls, labels[q]);
     };
-    // 16 mask bytes per load (the mask is 16-byte aligned and a share is a multiple of 16 pixels)
-    long t = lo + 16L * threadIdx.x;
-    for (; t + 16 <= hi; t += 16L * kThreads) {
-        const uint4 v = *(const uint4 *)(mask + t);
-        const unsigned w[4] = {v.x, v.y, v.z, v.w};
-        if ((w[0] | w[1] | w[2] | w[3]) == 0u) continue;
-        for (int i = 0; i < 16; ++i)
-            if ((w[i >> 2] >> (8 * (i & 3))) & 0xffu) pixel(t + i);
+    // 4 mask bytes per load (the mask is 16-byte aligned and a share is a multiple of 1024 pixels): neighbouring
+    // threads take neighbouring pixels, so that the score loads of chosen pixels are coalesced where the mask is dense
+    long t = lo + 4L * threadIdx.x;
+    for (; t + 4 <= hi; t += 4L * kThreads) {
+        const unsigned w = *(const unsigned *)(mask + t);
+        if (w == 0u) continue;
+        for (int i = 0; i < 4; ++i)
+            if ((w >> (8 * i)) & 0xffu) pixel(t + i);
     }
     if (t < hi)
         for (long q = t; q < hi; ++q)
@@ -227,10 +227,9 @@ int launch_masked_softmax_xent(const float *scores, const int32_t *labels, const
                                hipStream_t st)
 {
     const long HW = (long)H * W, pixels = (long)N * HW;
-    // shares of the mask: multiples of 16 pixels, at most kCountBlocks of them
+    // shares of the mask: multiples of 1024 pixels (four per thread), at most kCountBlocks of them
     long share = (pixels + kCountBlocks - 1) / kCountBlocks;
-    share = (share + 15) / 16 * 16;
-    if (share < 16L * kThreads) share = 16L * kThreads;
+    share = (share + 4 * kThreads - 1) / (4 * kThreads) * (4 * kThreads);
     const int n_cnt = (int)((pixels + share - 1) / share);
     if (dt == DSK_F32)
         launch_softmax<float>(scores, labels, mask, (uint32_t *)ws, n_cnt, share, (float *)dscores, loss, Cls, HW, pixels, st);

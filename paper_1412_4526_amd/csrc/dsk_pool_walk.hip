@@ -1,13 +1,13 @@
 // Stride-1 pooling with d-regularly sparse 2 x 2 and 3 x 3 kernels (paper Sec. 3.1-3.2;
 // backward Sec. 4.2): the kernels the benchmark networks spend their pooling time in.
 //
-// A thread owns V neighbouring columns (16 bytes: 4 fp32 or 8 bf16 pixels) and WALKS
+// A thread owns V = 4 neighbouring columns (16 bytes in fp32, 8 in bf16) and WALKS
 // DOWN one residue class of rows modulo d (rows u, u+d, u+2d, ...): the k tap rows of
 // an output row are the next rows of the same class, so what the thread computed from
 // the previous k-1 input rows stays in registers and every input row is loaded once
 // per walk, not once per tile of 8 rows.  A class is cut into segments of at most 64
 // rows (one thread each), which costs (k-1)/64 re-reads.  Every memory instruction
-// moves 16 bytes per lane (tap indices: 4 or 8 bytes): the vector memory path takes as
+// moves four pixels per lane (tap indices: 4 bytes): the vector memory path takes as
 // long for a 4-byte access per lane as for a 16-byte one.
 //
 // Max-pool ties: taps are ranked by a*k+b and only a strictly greater value replaces
@@ -27,6 +27,7 @@ namespace dsk {
 
 static constexpr int kWT = 256;
 static constexpr int kSegRows = 64;
+static constexpr long kFillThreads = 2048L * 256;      // threads wanted in flight: eight workgroups per CU
 // cache policy (the aux operand of the buffer builtins) of the loads and of the stores.  Non-temporal accesses (2)
 // were measured: loads lose 10-20 % (neighbouring lanes and tap columns share lines), stores gain 1 % on maps whose
 // rows are 16-byte aligned and lose 5-15 % on the others.
@@ -71,10 +72,10 @@ __device__ inline void wld(BufRsrc r, const float *, unsigned off, float (&o)[V]
 template <int V>
 __device__ inline void wld(BufRsrc r, const bf16 *, unsigned off, float (&o)[V])
 {
-    static_assert(V == 8, "eight bf16 pixels per access");
-    const wu4 t = __builtin_amdgcn_raw_buffer_load_b128(r, (int)(off * 2u), 0, kAuxLd);
+    static_assert(V == 4, "four bf16 pixels per access");
+    const wu2 t = __builtin_amdgcn_raw_buffer_load_b64(r, (int)(off * 2u), 0, kAuxLd);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2; ++i) {
         o[2 * i] = __builtin_bit_cast(float, t[i] << 16);
         o[2 * i + 1] = __builtin_bit_cast(float, t[i] & 0xffff0000u);
     }
@@ -89,14 +90,14 @@ __device__ inline void wst(BufRsrc r, float *, unsigned off, float (&v)[V])
 template <int V>
 __device__ inline void wst(BufRsrc r, bf16 *, unsigned off, float (&v)[V])
 {
-    unsigned h[8];
+    unsigned h[4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < 4; ++j) {
         h[j] = f32_to_bf16(v[j]).v;
         v[j] = __builtin_bit_cast(float, h[j] << 16);
     }
-    const wu4 t = {h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16};
-    __builtin_amdgcn_raw_buffer_store_b128(t, r, (int)(off * 2u), 0, kAuxSt);
+    const wu2 t = {h[0] | h[1] << 16, h[2] | h[3] << 16};
+    __builtin_amdgcn_raw_buffer_store_b64(t, r, (int)(off * 2u), 0, kAuxSt);
 }
 __device__ inline float round_as(const float *, float v) { return v; }
 __device__ inline float round_as(const bf16 *, float v) { return bf16_to_f32(f32_to_bf16(v)); }
@@ -501,22 +502,31 @@ static WalkShape make_walk(int N, int C, int H, int W, int k, int d, int rows, i
     s.Ho = H - (k - 1) * d; s.Wo = W - (k - 1) * d;
     s.d = d;
     const int nj = (rows + d - 1) / d;      // rows of the longest class
-    s.nseg = (nj + kSegRows - 1) / kSegRows;
-    s.J = ((nj + s.nseg - 1) / s.nseg + R - 1) / R * R;
     s.lanes = (cols + V - 1) / V;
+    // segments of at most kSegRows rows -- shorter ones (down to one batch of R rows) on small maps, so that there
+    // are enough threads to fill the chip: a walk re-reads k-1 rows per segment
+    s.nseg = (nj + kSegRows - 1) / kSegRows;
+    const long want = (kFillThreads + (long)s.planes * d * s.lanes - 1) / ((long)s.planes * d * s.lanes);
+    if (s.nseg < want) s.nseg = (int)(want < (nj + R - 1) / R ? want : (nj + R - 1) / R);
+    if (s.nseg < 1) s.nseg = 1;
+    s.J = ((nj + s.nseg - 1) / s.nseg + R - 1) / R * R;
+    s.nseg = (nj + s.J - 1) / s.J;
     s.row_groups = d * s.nseg;
     s.bpp = (int)(((long)s.row_groups * s.lanes + kWT - 1) / kWT);
     s.n_blocks = (long)s.planes * s.bpp;
     return s;
 }
 
-// rows per batch of loads: what the registers hold (a bf16 access brings eight pixels)
-static constexpr int walk_rows(int k, bool is_bf16) { return (k == 2 ? 8 : 4) / (is_bf16 ? 2 : 1); }
+// rows per batch of loads: what the registers hold
+static constexpr int walk_rows(int k, bool) { return k == 2 ? 8 : 4; }
+// the gradient kernels hold two or three times as much per row (values and tap indices of k tap columns, and y)
+static constexpr int walk_rows_bwd(int k) { return k == 2 ? 4 : 2; }
 
 bool pool_walk_ok(int N, int C, int H, int W, int k, int d, dsk_dtype t)
 {
     if (k != 2 && k != 3) return false;
-    const int V = t == DSK_F32 ? 4 : 8, R = walk_rows(k, t != DSK_F32);
+    const int V = 4, R = walk_rows_bwd(k);
+    (void)t;
     return make_walk(N, C, H, W, k, d, H, W, V, R).n_blocks < 0x7fffffffL;      // the gradient's grid is the larger one
 }
 
@@ -537,13 +547,13 @@ int launch_pool_walk_fwd(const void *x, void *y, uint8_t *am, int N, int C, int 
     if (t == DSK_F32)
         return is_max ? walk_fwd<float, true, 4>(x, y, am, N, C, H, W, k, d, st)
                       : walk_fwd<float, false, 4>(x, y, am, N, C, H, W, k, d, st);
-    return is_max ? walk_fwd<bf16, true, 8>(x, y, am, N, C, H, W, k, d, st)
-                  : walk_fwd<bf16, false, 8>(x, y, am, N, C, H, W, k, d, st);
+    return is_max ? walk_fwd<bf16, true, 4>(x, y, am, N, C, H, W, k, d, st)
+                  : walk_fwd<bf16, false, 4>(x, y, am, N, C, H, W, k, d, st);
 }
 
 size_t pool_bwd_act_bias_ws_bytes(int N, int C, int H, int W, int k, int d, dsk_dtype t)
 {
-    const WalkShape s = make_walk(N, C, H, W, k, d, H, W, t == DSK_F32 ? 4 : 8, walk_rows(k, t != DSK_F32));
+    const WalkShape s = make_walk(N, C, H, W, k, d, H, W, 4, walk_rows_bwd(k));
     return (size_t)s.n_blocks * sizeof(float);
 }
 
@@ -552,11 +562,11 @@ static int walk_bwd(const void *dy, const uint8_t *am, void *dx, const void *ypr
                     int N, int C, int H, int W, int k, int d, hipStream_t st)
 {
     constexpr bool B16 = sizeof(T) == 2;
-    const WalkShape s = make_walk(N, C, H, W, k, d, H, W, V, walk_rows(k, B16));
+    const WalkShape s = make_walk(N, C, H, W, k, d, H, W, V, walk_rows_bwd(k));
     const dim3 grid((unsigned)s.n_blocks), block(kWT);
     float *part = (float *)ws;
     const bool fuse = db != nullptr;
-#define DSK_WB(KK, FU) pool_walk_bwd_kernel<T, KK, IS_MAX, V, walk_rows(KK, B16), FU><<<grid, block, 0, st>>>( \
+#define DSK_WB(KK, FU) pool_walk_bwd_kernel<T, KK, IS_MAX, V, walk_rows_bwd(KK), FU><<<grid, block, 0, st>>>( \
         (const T *)dy, am, (T *)dx, (const T *)yprev, part, act, s)
     if (k == 2 && fuse) DSK_WB(2, true);
     else if (k == 2) DSK_WB(2, false);
@@ -575,8 +585,8 @@ int launch_pool_walk_bwd(const void *dy, const uint8_t *am, void *dx, const void
     if (t == DSK_F32)
         return is_max ? walk_bwd<float, true, 4>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st)
                       : walk_bwd<float, false, 4>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st);
-    return is_max ? walk_bwd<bf16, true, 8>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st)
-                  : walk_bwd<bf16, false, 8>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st);
+    return is_max ? walk_bwd<bf16, true, 4>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st)
+                  : walk_bwd<bf16, false, 4>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st);
 }
 
 } // namespace dsk

@@ -257,6 +257,58 @@ int dsk_fs_assemble(const void *frag, void *out, int N, int D, int C, int hf, in
                     dsk_dtype tin, dsk_dtype tout, void *stream);
 
 /* ------------------------------------------------------------------------- */
+/* Video: 3-D convolution and 3-D pooling with kernels sparse in time and space  */
+/* (Sec. 6 proposes carrying the method over to video; Sec. 3.1-3.2, Sec. 4 and   */
+/* Algorithm 1 applied to the temporal axis as well)                           */
+/* ------------------------------------------------------------------------- */
+
+/* A cube classifier (nt frames of n x n pixels per labelled voxel) with temporal strides st and spatial
+ * strides s becomes a stride-1 network over the whole padded video: layer k's kernel has its temporal
+ * taps dt frames apart and its spatial taps d pixels apart, where dt / d are the products of the earlier
+ * temporal / spatial strides (dsk_plan on the (kt, st) list gives dt, on the (k, s) list gives d).
+ *
+ * Layout: maps [N][T][C][H][W] (frame-major: a video is a batch of T images, so dsk_pad_image,
+ * dsk_act_bwd*, dsk_masked_softmax_xent apply with N*T images); weights w[kt][K][C][kh][kw] fp32
+ * (one 2-D kernel per temporal tap), bias [K].  Output: [N][To][K][Ho][Wo], To = T-(kt-1)*dt,
+ * Ho = H-(kh-1)*d, Wo = W-(kw-1)*d.  All pointers are device pointers, 16-byte aligned; nothing is
+ * allocated; errors as for the 2-D calls.  kt = 1 is the 2-D layer applied to every frame.
+ *
+ *   y[n][t][f][u][v]  = act( b[f] + sum_{e,c,a,b} w[e][f][c][a][b] * x[n][t+e*dt][c][u+a*d][v+b*d] )
+ *   dx[n][t][c][p][q] = sum_{e,f,a,b} dy[n][t-e*dt][f][p-a*d][q-b*d] * w[e][f][c][a][b]   (dy = 0 outside)
+ *   dw[e][f][c][a][b] = sum_{n,t,u,v} dy[n][t][f][u][v] * x[n][t+e*dt][c][u+a*d][v+b*d]
+ *   db[f]             = sum_{n,t,u,v} dy[n][t][f][u][v]                    (db may be NULL) */
+/* xpad[N][T+tlo+thi][C][H+lo+hi][W+lo+hi] (type `out`) = zero-padded copy of the fp32 video x[N][T][C][H][W]:
+ * tlo / thi zero frames before / after, lo / hi zero rows and columns (Sec. 3.3 on all three axes). */
+int dsk_pad_video(const float *x, void *xpad, int N, int T, int C, int H, int W,
+                  int tlo, int thi, int lo, int hi, dsk_dtype out, void *stream);
+
+size_t dsk_conv3d_workspace_bytes(int which, int N, int T, int C, int H, int W, int K,
+                                  int kt, int kh, int kw, int dt, int d, dsk_dtype in);
+int dsk_conv3d_fwd(const void *x, const float *w, const float *b, void *y,
+                   int N, int T, int C, int H, int W, int K, int kt, int kh, int kw, int dt, int d,
+                   dsk_dtype in, dsk_dtype out, dsk_act act, void *ws, size_t ws_bytes, void *stream);
+int dsk_conv3d_bwd_data(const void *dy, const float *w, void *dx,
+                        int N, int T, int C, int H, int W, int K, int kt, int kh, int kw, int dt, int d,
+                        dsk_dtype in, dsk_dtype out, void *ws, size_t ws_bytes, void *stream);
+int dsk_conv3d_bwd_weight(const void *x, const void *dy, float *dw, float *db,
+                          int N, int T, int C, int H, int W, int K, int kt, int kh, int kw, int dt, int d,
+                          dsk_dtype in, void *ws, size_t ws_bytes, void *stream);
+
+/* 3-D pooling over kt x k x k taps (dt frames, d pixels apart); x[N][T][C][H][W] -> y[N][To][C][Ho][Wo].
+ * Max pooling records the winner's index (e*k + a)*k + b (needs kt*k*k <= 255); taps are visited in that
+ * order and replace the maximum only when strictly greater, so the lowest index wins ties.  Backward is the
+ * gather form of Sec. 4.2 (fixed order, no atomics); the average pool divides by kt*k*k.  argmax may be
+ * NULL in dsk_maxpool3d_fwd. */
+int dsk_maxpool3d_fwd(const void *x, void *y, uint8_t *argmax, int N, int T, int C, int H, int W,
+                      int kt, int k, int dt, int d, dsk_dtype t, void *stream);
+int dsk_maxpool3d_bwd(const void *dy, const uint8_t *argmax, void *dx, int N, int T, int C, int H, int W,
+                      int kt, int k, int dt, int d, dsk_dtype t, void *stream);
+int dsk_avgpool3d_fwd(const void *x, void *y, int N, int T, int C, int H, int W,
+                      int kt, int k, int dt, int d, dsk_dtype t, void *stream);
+int dsk_avgpool3d_bwd(const void *dy, void *dx, int N, int T, int C, int H, int W,
+                      int kt, int k, int dt, int d, dsk_dtype t, void *stream);
+
+/* ------------------------------------------------------------------------- */
 /* Kernel selection (diagnostics)                                              */
 /* ------------------------------------------------------------------------- */
 

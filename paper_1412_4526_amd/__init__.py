@@ -9,3 +9,4 @@ from .binding import *  # noqa: F401,F403
 from .binding import DskError, lib, LIB_PATH, SYMBOLS, status_string, torch_dtype  # noqa: F401
 from .net import WholeImageNet  # noqa: F401
 from .fastscan import FastScanNet  # noqa: F401
+from .video import WholeVideoNet  # noqa: F401

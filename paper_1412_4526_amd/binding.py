@@ -27,6 +27,8 @@ SYMBOLS = ("dsk_plan", "dsk_status_string", "dsk_pad_image", "dsk_conv_workspace
            "dsk_pool_bwd_act_bias_workspace_bytes", "dsk_pool_bwd_act_bias",
            "dsk_softmax_xent_workspace_bytes", "dsk_masked_softmax_xent", "dsk_masked_softmax_xent_static",
            "dsk_fs_pool_fwd", "dsk_fs_conv_fwd", "dsk_fs_assemble",
+           "dsk_pad_video", "dsk_conv3d_workspace_bytes", "dsk_conv3d_fwd", "dsk_conv3d_bwd_data", "dsk_conv3d_bwd_weight",
+           "dsk_maxpool3d_fwd", "dsk_maxpool3d_bwd", "dsk_avgpool3d_fwd", "dsk_avgpool3d_bwd",
            "dsk_set_conv_algo")
 
 
@@ -86,6 +88,16 @@ def _load():
     lib.dsk_fs_pool_fwd.argtypes = [ci, vp, vp] + [ci] * 9 + [ci, vp]
     lib.dsk_fs_conv_fwd.argtypes = [vp, vp, vp, vp] + [ci] * 10 + [ci, ci, vp]
     lib.dsk_fs_assemble.argtypes = [vp, vp] + [ci] * 7 + [ci, ci, vp]
+    lib.dsk_pad_video.argtypes = [vp, vp] + [ci] * 9 + [ci, vp]
+    lib.dsk_conv3d_workspace_bytes.argtypes = [ci] * 13
+    lib.dsk_conv3d_workspace_bytes.restype = sz
+    lib.dsk_conv3d_fwd.argtypes = [vp, vp, vp, vp] + [ci] * 11 + [ci, ci, ci, vp, sz, vp]
+    lib.dsk_conv3d_bwd_data.argtypes = [vp, vp, vp] + [ci] * 11 + [ci, ci, vp, sz, vp]
+    lib.dsk_conv3d_bwd_weight.argtypes = [vp, vp, vp, vp] + [ci] * 11 + [ci, vp, sz, vp]
+    lib.dsk_maxpool3d_fwd.argtypes = [vp, vp, vp] + [ci] * 9 + [ci, vp]
+    lib.dsk_maxpool3d_bwd.argtypes = [vp, vp, vp] + [ci] * 9 + [ci, vp]
+    lib.dsk_avgpool3d_fwd.argtypes = [vp, vp] + [ci] * 9 + [ci, vp]
+    lib.dsk_avgpool3d_bwd.argtypes = [vp, vp] + [ci] * 9 + [ci, vp]
     lib.dsk_set_conv_algo.argtypes = [ci]
     for name in SYMBOLS:
         getattr(lib, name)      # AttributeError here = header and library disagree
@@ -386,3 +398,122 @@ def dsk_fs_assemble(frag, D, H, W, out=None, out_dtype=None):
     _check(lib.dsk_fs_assemble(_dev(frag), _dev(out), N, D, C, hf, wf, H, W, _dtype_code(frag), _dtype_code(out),
                                _stream()), "dsk_fs_assemble")
     return out
+
+
+# --------------------------------------------------------------------------- video (3-D) layers
+# maps [N, T, C, H, W]; weights [kt, K, C, kh, kw]
+def dsk_pad_video(x, tlo, thi, lo, hi, out_dtype=torch.float32, xpad=None):
+    N, T, C, H, W = x.shape
+    if xpad is None:
+        xpad = torch.empty((N, T + tlo + thi, C, H + lo + hi, W + lo + hi), dtype=out_dtype, device=x.device)
+    _check(lib.dsk_pad_video(_dev(x, torch.float32), _dev(xpad), N, T, C, H, W, tlo, thi, lo, hi, _dtype_code(xpad),
+                             _stream()), "dsk_pad_video")
+    return xpad
+
+
+def dsk_conv3d_workspace_bytes(which, N, T, C, H, W, K, kt, kh, kw, dt, d, in_code):
+    return int(lib.dsk_conv3d_workspace_bytes(which, N, T, C, H, W, K, kt, kh, kw, dt, d, in_code))
+
+
+def _conv3d_ws(which, shape, in_code, ws, device):
+    need = dsk_conv3d_workspace_bytes(which, *shape, in_code)
+    if need and (ws is None or ws.numel() * ws.element_size() < need):
+        ws = torch.empty(need, dtype=torch.uint8, device=device)
+    return ws
+
+
+def dsk_conv3d_fwd(x, w, b, dt, d, act=DSK_ACT_NONE, out_dtype=None, y=None, ws=None):
+    N, T, C, H, W = x.shape
+    kt, K, Cw, kh, kw = w.shape
+    assert Cw == C
+    if y is None:
+        To, Ho, Wo = T - (kt - 1) * dt, H - (kh - 1) * d, W - (kw - 1) * d
+        if To < 1 or Ho < 1 or Wo < 1:
+            raise DskError(DSK_ESHAPE, "dsk_conv3d_fwd")
+        y = torch.empty((N, To, K, Ho, Wo), dtype=out_dtype or x.dtype, device=x.device)
+    shape = (N, T, C, H, W, K, kt, kh, kw, dt, d)
+    ws = _conv3d_ws(DSK_WS_CONV_FWD, shape, _dtype_code(x), ws, x.device)
+    wsp, wsb = _ws(ws)
+    _check(lib.dsk_conv3d_fwd(_dev(x), _dev(w, torch.float32), None if b is None else _dev(b, torch.float32), _dev(y),
+                              *shape, _dtype_code(x), _dtype_code(y), act, wsp, wsb, _stream()), "dsk_conv3d_fwd")
+    return y
+
+
+def dsk_conv3d_bwd_data(dy, w, dt, d, T, H, W, out_dtype=None, dx=None, ws=None):
+    N, To, K, Ho, Wo = dy.shape
+    kt, Kw, C, kh, kw = w.shape
+    assert Kw == K and To == T - (kt - 1) * dt and Ho == H - (kh - 1) * d and Wo == W - (kw - 1) * d
+    if dx is None:
+        dx = torch.empty((N, T, C, H, W), dtype=out_dtype or dy.dtype, device=dy.device)
+    shape = (N, T, C, H, W, K, kt, kh, kw, dt, d)
+    ws = _conv3d_ws(DSK_WS_CONV_BWD_DATA, shape, _dtype_code(dy), ws, dy.device)
+    wsp, wsb = _ws(ws)
+    _check(lib.dsk_conv3d_bwd_data(_dev(dy), _dev(w, torch.float32), _dev(dx), *shape, _dtype_code(dy), _dtype_code(dx),
+                                   wsp, wsb, _stream()), "dsk_conv3d_bwd_data")
+    return dx
+
+
+def dsk_conv3d_bwd_weight(x, dy, kt, kh, kw, dt, d, dw=None, db=None, want_db=True, ws=None):
+    N, T, C, H, W = x.shape
+    N2, To, K, Ho, Wo = dy.shape
+    assert N2 == N and To == T - (kt - 1) * dt and Ho == H - (kh - 1) * d and Wo == W - (kw - 1) * d and x.dtype == dy.dtype
+    if dw is None:
+        dw = torch.empty((kt, K, C, kh, kw), dtype=torch.float32, device=x.device)
+    if db is None and want_db:
+        db = torch.empty((K,), dtype=torch.float32, device=x.device)
+    shape = (N, T, C, H, W, K, kt, kh, kw, dt, d)
+    ws = _conv3d_ws(DSK_WS_CONV_BWD_WEIGHT, shape, _dtype_code(x), ws, x.device)
+    wsp, wsb = _ws(ws)
+    _check(lib.dsk_conv3d_bwd_weight(_dev(x), _dev(dy), _dev(dw, torch.float32), None if db is None else _dev(db, torch.float32),
+                                     *shape, _dtype_code(x), wsp, wsb, _stream()), "dsk_conv3d_bwd_weight")
+    return dw, db
+
+
+def _pool3d_out(x, kt, k, dt, d, where):
+    N, T, C, H, W = x.shape
+    To, Ho, Wo = T - (kt - 1) * dt, H - (k - 1) * d, W - (k - 1) * d
+    if To < 1 or Ho < 1 or Wo < 1:
+        raise DskError(DSK_ESHAPE, where)
+    return (N, To, C, Ho, Wo)
+
+
+def dsk_maxpool3d_fwd(x, kt, k, dt, d, y=None, argmax=None, want_argmax=True):
+    N, T, C, H, W = x.shape
+    shp = _pool3d_out(x, kt, k, dt, d, "dsk_maxpool3d_fwd")
+    if y is None:
+        y = torch.empty(shp, dtype=x.dtype, device=x.device)
+    if argmax is None and want_argmax:
+        argmax = torch.empty(shp, dtype=torch.uint8, device=x.device)
+    _check(lib.dsk_maxpool3d_fwd(_dev(x), _dev(y), None if argmax is None else _dev(argmax, torch.uint8),
+                                 N, T, C, H, W, kt, k, dt, d, _dtype_code(x), _stream()), "dsk_maxpool3d_fwd")
+    return y, argmax
+
+
+def dsk_maxpool3d_bwd(dy, argmax, kt, k, dt, d, T, H, W, dx=None):
+    N, To, C, Ho, Wo = dy.shape
+    assert To == T - (kt - 1) * dt and Ho == H - (k - 1) * d and Wo == W - (k - 1) * d and argmax.shape == dy.shape
+    if dx is None:
+        dx = torch.empty((N, T, C, H, W), dtype=dy.dtype, device=dy.device)
+    _check(lib.dsk_maxpool3d_bwd(_dev(dy), _dev(argmax, torch.uint8), _dev(dx), N, T, C, H, W, kt, k, dt, d,
+                                 _dtype_code(dy), _stream()), "dsk_maxpool3d_bwd")
+    return dx
+
+
+def dsk_avgpool3d_fwd(x, kt, k, dt, d, y=None):
+    N, T, C, H, W = x.shape
+    shp = _pool3d_out(x, kt, k, dt, d, "dsk_avgpool3d_fwd")
+    if y is None:
+        y = torch.empty(shp, dtype=x.dtype, device=x.device)
+    _check(lib.dsk_avgpool3d_fwd(_dev(x), _dev(y), N, T, C, H, W, kt, k, dt, d, _dtype_code(x), _stream()),
+           "dsk_avgpool3d_fwd")
+    return y
+
+
+def dsk_avgpool3d_bwd(dy, kt, k, dt, d, T, H, W, dx=None):
+    N, To, C, Ho, Wo = dy.shape
+    assert To == T - (kt - 1) * dt and Ho == H - (k - 1) * d and Wo == W - (k - 1) * d
+    if dx is None:
+        dx = torch.empty((N, T, C, H, W), dtype=dy.dtype, device=dy.device)
+    _check(lib.dsk_avgpool3d_bwd(_dev(dy), _dev(dx), N, T, C, H, W, kt, k, dt, d, _dtype_code(dy), _stream()),
+           "dsk_avgpool3d_bwd")
+    return dx

@@ -45,6 +45,38 @@ int pool_check(const void *a, const void *b, int N, int C, int H, int W, int k, 
 } // namespace
 
 namespace dsk {
+// Kernel choice for one 2-D convolution call (also the per-frame calls of the video layers): the bf16 matrix
+// cores for plain calls on bf16 maps they take, else the fp32 matrix cores, else the plain kernels.
+static bool plain2d(const ConvShape &s) { return s.gsize == 0 && s.bgroup == 0; }
+
+int dispatch_conv_fwd(const void *x, const float *w, const float *b, void *y, const ConvShape &s, dsk_dtype in,
+                      dsk_dtype out, int act, void *ws, hipStream_t st)
+{
+    if (g_conv_algo == 0 && in == DSK_BF16 && plain2d(s) && conv_bf16_supported(DSK_WS_CONV_FWD, s))
+        return launch_conv_fwd_bf16(x, w, b, y, s, out, act, ws, st);
+    if (g_conv_algo != 1 && conv_mfma_supported(DSK_WS_CONV_FWD, s, in, out))
+        return launch_conv_fwd_mfma(x, w, b, y, s, in, out, act, ws, st);
+    return launch_conv_fwd_direct(x, w, b, y, s, in, out, act, st);
+}
+
+int dispatch_conv_bwd_data(const void *dy, const float *w, void *dx, const ConvShape &s, dsk_dtype in, dsk_dtype out,
+                           void *ws, hipStream_t st)
+{
+    if (g_conv_algo == 0 && in == DSK_BF16 && plain2d(s) && conv_bf16_supported(DSK_WS_CONV_BWD_DATA, s))
+        return launch_conv_bwd_data_bf16(dy, w, dx, s, out, ws, st);
+    if (g_conv_algo != 1 && conv_mfma_supported(DSK_WS_CONV_BWD_DATA, s, in, out))
+        return launch_conv_bwd_data_mfma(dy, w, dx, s, in, out, ws, st);
+    return launch_conv_bwd_data_direct(dy, w, dx, s, in, out, st);
+}
+
+int dispatch_conv_bwd_weight(const void *x, const void *dy, float *dw, float *db, const ConvShape &s, dsk_dtype in,
+                             void *ws, hipStream_t st)
+{
+    if (g_conv_algo != 1 && conv_mfma_supported(DSK_WS_CONV_BWD_WEIGHT, s, in, DSK_F32))
+        return launch_conv_bwd_weight_mfma(x, dy, dw, db, s, in, ws, st);
+    return launch_conv_bwd_weight_direct(x, dy, dw, db, s, in, st);
+}
+
 int device_cu_count()
 {
     static std::mutex mu;
@@ -205,13 +237,8 @@ int dsk_conv_fwd(const void *x, const float *w, const float *b, void *y,
     if (rc != DSK_OK) return rc;
     const size_t need = conv_ws_bytes(DSK_WS_CONV_FWD, s, in);
     if (need > 0 && (ws == nullptr || !aligned16(ws) || ws_bytes < need)) return DSK_EWORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
     clear_errors();
-    if (g_conv_algo == 0 && in == DSK_BF16 && conv_bf16_supported(DSK_WS_CONV_FWD, s))
-        return launch_conv_fwd_bf16(x, w, b, y, s, out, act, ws, st);
-    if (g_conv_algo != 1 && conv_mfma_supported(DSK_WS_CONV_FWD, s, in, out))
-        return launch_conv_fwd_mfma(x, w, b, y, s, in, out, act, ws, st);
-    return launch_conv_fwd_direct(x, w, b, y, s, in, out, act, st);
+    return dispatch_conv_fwd(x, w, b, y, s, in, out, act, ws, (hipStream_t)stream);
 }
 
 int dsk_conv_bwd_data(const void *dy, const float *w, void *dx,
@@ -225,13 +252,8 @@ int dsk_conv_bwd_data(const void *dy, const float *w, void *dx,
     if (rc != DSK_OK) return rc;
     const size_t need = conv_ws_bytes(DSK_WS_CONV_BWD_DATA, s, in);
     if (need > 0 && (ws == nullptr || !aligned16(ws) || ws_bytes < need)) return DSK_EWORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
     clear_errors();
-    if (g_conv_algo == 0 && in == DSK_BF16 && conv_bf16_supported(DSK_WS_CONV_BWD_DATA, s))
-        return launch_conv_bwd_data_bf16(dy, w, dx, s, out, ws, st);
-    if (g_conv_algo != 1 && conv_mfma_supported(DSK_WS_CONV_BWD_DATA, s, in, out))
-        return launch_conv_bwd_data_mfma(dy, w, dx, s, in, out, ws, st);
-    return launch_conv_bwd_data_direct(dy, w, dx, s, in, out, st);
+    return dispatch_conv_bwd_data(dy, w, dx, s, in, out, ws, (hipStream_t)stream);
 }
 
 int dsk_conv_bwd_weight(const void *x, const void *dy, float *dw, float *db,
@@ -245,11 +267,8 @@ int dsk_conv_bwd_weight(const void *x, const void *dy, float *dw, float *db,
     if (rc != DSK_OK) return rc;
     const size_t need = conv_ws_bytes(DSK_WS_CONV_BWD_WEIGHT, s, in);
     if (need > 0 && (ws == nullptr || !aligned16(ws) || ws_bytes < need)) return DSK_EWORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
     clear_errors();
-    if (g_conv_algo != 1 && conv_mfma_supported(DSK_WS_CONV_BWD_WEIGHT, s, in, DSK_F32))
-        return launch_conv_bwd_weight_mfma(x, dy, dw, db, s, in, ws, st);
-    return launch_conv_bwd_weight_direct(x, dy, dw, db, s, in, st);
+    return dispatch_conv_bwd_weight(x, dy, dw, db, s, in, ws, (hipStream_t)stream);
 }
 
 int dsk_maxpool_fwd(const void *x, void *y, uint8_t *argmax, int N, int C, int H, int W, int k, int d,

@@ -73,6 +73,10 @@ struct GcParams {
     int rounds;          // persistent workgroups: whole tiles each of them takes first
     int rem_units;       // (tiles - rounds * n_wg) * NC: chunks of the tiles left after that
     long n_wg, per_xcd;  // logical workgroups; the grid is per_xcd * 8
+    // how the input's planes are found (video layers; see ConvShape): image n at slot n + n / bgroup * bskip,
+    // in_bstride elements per slot, channel v a further v*Hin*Win + v / gsize * gjump; in_extent readable elements
+    int gsize, bgroup, bskip;
+    long gjump, in_bstride, in_extent;
 };
 
 // Weight layout transform.  flip = 0: wt[g][c][t][fl] = w[g*TF+fl][c][t]            (forward)
@@ -233,8 +237,8 @@ gemm_conv_kernel(GcParams p)
         }
         int fg, n, u0, v0;
         gc_decode_tile(p, tile, fg, n, u0, v0);
-        const TI *in_n = (const TI *)p.in + (long)n * p.Cin * (long)HW;
-        const TI *in_end = (const TI *)p.in + (long)p.N * p.Cin * (long)HW;
+        const TI *in_n = (const TI *)p.in + (p.bgroup ? n + (long)(n / p.bgroup) * p.bskip : (long)n) * p.in_bstride;
+        const TI *in_end = (const TI *)p.in + p.in_extent;
 
         // Where this thread's share of the input tile comes from; the same for every chunk:
         // element e = tid + 256*i of the LDS tile [Cc][rows][cols] (padded to a multiple of 256)
@@ -280,19 +284,26 @@ gemm_conv_kernel(GcParams p)
         // Every load is issued unconditionally (padding reads offset 0): a load under a
         // condition makes the compiler wait for it right away to merge the two values.
         auto fetch = [&](int c0) __attribute__((always_inline)) {
-            const TI *src = in_n + (long)c0 * (long)HW;
+            const int g0 = p.gsize ? c0 / p.gsize : 0;      // the channel group the chunk begins in
+            const TI *src = in_n + (long)c0 * (long)HW + g0 * p.gjump;
             const BufRsrc rx = buf_rsrc(src, in_end);
-            if (c0 + p.Cc <= p.Cin) {
+            if (c0 + p.Cc <= p.Cin && (!p.gsize || c0 - g0 * p.gsize + p.Cc <= p.gsize)) {
 #pragma unroll
                 for (int i = 0; i < XI; ++i) xv[i] = buf_ld(rx, src, voff[i], 0u);
             } else {
-                // last chunk of a padded channel count: channels beyond Cin meet zero weights;
-                // read the chunk's first channel instead so the address stays inside the tensor
+                // Last chunk of a padded channel count: channels beyond Cin meet zero weights; read the
+                // chunk's first channel instead so the address stays inside the tensor.  A chunk that
+                // straddles channel groups: the later group's planes lie gjump elements further on
+                // (the host checks that this stays below 2^30 elements).
 #pragma unroll
                 for (int i = 0; i < XI; ++i) {
                     unsigned v = voff[i];
-                    const unsigned cl = __umulhi((unsigned)(tid + i * kThreads), p.m_cs);      // the element's channel
-                    v -= !((zero >> i) & 1u) && c0 + (int)cl >= p.Cin ? cl * HW : 0u;
+                    if (!((zero >> i) & 1u)) {
+                        const unsigned cl = __umulhi((unsigned)(tid + i * kThreads), p.m_cs);      // the element's channel
+                        const int cv = c0 + (int)cl;
+                        if (cv >= p.Cin) v -= cl * HW;
+                        else if (p.gsize) v += (unsigned)(cv / p.gsize - g0) * (unsigned)p.gjump;
+                    }
                     xv[i] = buf_ld(rx, src, v, 0u);
                 }
             }
@@ -545,7 +556,7 @@ static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
 
 static int gc_run(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Hin, int Win,
                   int Fout, int Hout, int Wout, int kh, int kw, int d, int off, int act, int flip,
-                  int K, int C, dsk_dtype tin, dsk_dtype tout, void *ws, hipStream_t st)
+                  int K, int C, dsk_dtype tin, dsk_dtype tout, void *ws, hipStream_t st, const ConvShape &s)
 {
     const GcPlan g = gc_plan(N, Cin, Fout, Hout, Wout, kh, kw, d);
     if (!g.ok) return DSK_ESHAPE;
@@ -571,6 +582,9 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     p.tiles = g.tiles; p.rounds = g.rounds; p.rem_units = g.rem_units; p.n_wg = g.n_wg;
     p.per_xcd = (p.n_wg + kXcds - 1) / kXcds;
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;
+    p.gsize = s.gsize; p.gjump = s.gjump; p.bgroup = s.bgroup; p.bskip = s.bskip;
+    p.in_bstride = (long)(s.gsize ? s.gsize : Cin) * Hin * Win;
+    p.in_extent = s.in_extent ? s.in_extent : (long)N * Cin * Hin * Win;
     if (tin == DSK_F32 && tout == DSK_F32) gc_launch<float, float>(p, g, st);
     else if (tin == DSK_F32 && tout == DSK_BF16) gc_launch<float, bf16>(p, g, st);
     else if (tin == DSK_BF16 && tout == DSK_BF16) gc_launch<bf16, bf16>(p, g, st);
@@ -789,6 +803,8 @@ struct BwParams {
     long n_ptile;        // N * n_rowtile * n_coltile
     int S;               // split count
     int n_fblk, n_cblk;
+    int bgroup, bskip;   // image n of x sits at slot n + n / bgroup * bskip (video layers; see ConvShape)
+    long x_extent;       // readable elements of x
 };
 
 // TPW: accumulator tiles (taps) per wave; XR: rows of the x tile, at most.
@@ -889,7 +905,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     const unsigned HW = (unsigned)(p.H * p.W), dW = (unsigned)(p.d * p.W);
     const int nf_valid = p.K - f_base, nc_valid = p.C - cb * 32;
     const bool full_blocks = !PACKB && nf_valid >= 32 * FB && nc_valid >= 32;
-    const TI *dy_end = dy + (long)p.N * p.K * HoWo, *x_end = x + (long)p.N * p.C * HW;
+    const TI *dy_end = dy + (long)p.N * p.K * HoWo, *x_end = x + p.x_extent;
     int st_nr_dy = 0, st_nr_x = 0;             // rows of the staged tile that exist
     bool st_dcol_ok = false, st_col_ok = false; // this lane's column exists
     bool st_full = false;                       // every row, filter and channel of the staged tile exists (uniform)
@@ -900,7 +916,8 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         const int u0 = (rt / p.d) * p.d * PH + (rt % p.d);
         const int v0 = ct * PW;
         const TI *dyt = dy + (((long)n * p.K + f_base) * p.Ho + u0) * p.Wo + v0;
-        const TI *xt = x + (((long)n * p.C + cb * 32) * p.H + u0) * p.W + v0 + col_shift;
+        const long xn = p.bgroup ? n + (long)(n / p.bgroup) * p.bskip : (long)n;
+        const TI *xt = x + ((xn * p.C + cb * 32) * p.H + u0) * p.W + v0 + col_shift;
         if constexpr (BFM != 0) {
             st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;
             st_nr_x = (p.H - u0 + p.d - 1) / p.d;
@@ -1473,28 +1490,31 @@ static BwPlan bw_plan(const ConvShape &s, dsk_dtype in)
 // ============================================================================
 // dispatch
 // ============================================================================
+// a 2-D call: the kernels that know nothing of grouped planes or batch slots may take it
+static bool plain_call(const ConvShape &s) { return s.gsize == 0 && s.bgroup == 0; }
+
 size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
 {
     // bf16 maps may take either set of kernels: room for both
-    if (in == DSK_BF16 && which != DSK_WS_CONV_BWD_WEIGHT && conv_bf16_supported(which, s)) {
+    if (in == DSK_BF16 && which != DSK_WS_CONV_BWD_WEIGHT && plain_call(s) && conv_bf16_supported(which, s)) {
         const size_t a = conv_bf16_ws_bytes(which, s), b = conv_ws_bytes(which, s, DSK_F32);
         return a > b ? a : b;
     }
     if (which == DSK_WS_CONV_FWD) {
         const PwPlan pw = pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw);
-        if (pw.ok) return pw.wt_bytes;
+        if (pw.ok && plain_call(s)) return pw.wt_bytes;
         const GcPlan g = gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d);
         return g.ok ? g.wt_bytes + g.partial_bytes : 0;
     }
     if (which == DSK_WS_CONV_BWD_DATA) {
         const PwPlan pw = pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw);
-        if (pw.ok) return pw.wt_bytes;
+        if (pw.ok && plain_call(s)) return pw.wt_bytes;
         const GcPlan g = gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d);
         return g.ok ? g.wt_bytes + g.partial_bytes : 0;
     }
     if (which == DSK_WS_CONV_BWD_WEIGHT) {
         const PbPlan pb = pb_plan(s);
-        if (pb.ok) return pb.part_bytes;
+        if (pb.ok && plain_call(s)) return pb.part_bytes;
         const BwPlan b = bw_plan(s, in);
         return b.ok ? b.part_bytes : 0;
     }
@@ -1509,36 +1529,38 @@ bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype 
     if ((long)s.H * s.W >= (1L << 28) || (long)s.C * s.H * s.W >= (1L << 30) ||
         (long)s.K * s.Ho * s.Wo >= (1L << 30))
         return false;
+    // grouped planes: a chunk of at most 8 channels may reach into 8 later groups with 32-bit element offsets
+    if (s.gsize && (s.gjump < 0 || 8 * (s.gjump + (long)s.H * s.W) >= (1L << 30))) return false;
     if (which == DSK_WS_CONV_FWD)
-        return pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw).ok || gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
+        return (plain_call(s) && pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw).ok) || gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
     if (which == DSK_WS_CONV_BWD_DATA)
-        return pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw).ok || gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
-    if (which == DSK_WS_CONV_BWD_WEIGHT) return pb_plan(s).ok || bw_plan(s, in).ok;
+        return (plain_call(s) && pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw).ok) || gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
+    if (which == DSK_WS_CONV_BWD_WEIGHT) return (plain_call(s) && pb_plan(s).ok) || bw_plan(s, in).ok;
     return false;
 }
 
 int launch_conv_fwd_mfma(const void *x, const float *w, const float *b, void *y, const ConvShape &s,
                          dsk_dtype in, dsk_dtype out, int act, void *ws, hipStream_t st)
 {
-    if (pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw).ok)
+    if (plain_call(s) && pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw).ok)
         return pw_run(x, y, w, b, s.N, s.C, s.K, (long)s.H * s.W, act, 0, s.K, s.C, in, out, ws, st);
     return gc_run(x, y, w, b, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d, 0, act, 0,
-                  s.K, s.C, in, out, ws, st);
+                  s.K, s.C, in, out, ws, st, s);
 }
 
 int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const ConvShape &s,
                               dsk_dtype in, dsk_dtype out, void *ws, hipStream_t st)
 {
-    if (pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw).ok)
+    if (plain_call(s) && pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw).ok)
         return pw_run(dy, dx, w, nullptr, s.N, s.K, s.C, (long)s.H * s.W, DSK_ACT_NONE, 1, s.K, s.C, in, out, ws, st);
     return gc_run(dy, dx, w, nullptr, s.N, s.K, s.Ho, s.Wo, s.C, s.H, s.W, s.kh, s.kw, s.d, 1, DSK_ACT_NONE, 1,
-                  s.K, s.C, in, out, ws, st);
+                  s.K, s.C, in, out, ws, st, s);
 }
 
 int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
                                 dsk_dtype in, void *ws, hipStream_t st)
 {
-    if (const PbPlan pb = pb_plan(s); pb.ok) {
+    if (const PbPlan pb = pb_plan(s); pb.ok && plain_call(s)) {
         PbParams q{};
         q.x = x; q.dy = dy; q.part = (float *)ws;
         q.N = s.N; q.C = s.C; q.K = s.K; q.Kp = pb.Kp; q.Cp = pb.Cp; q.S = pb.S; q.n_cg = pb.n_cg;
@@ -1577,6 +1599,8 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
     p.n_fblk = b.fb2 ? (b.n_fblk + 1) / 2 : b.n_fblk; p.n_cblk = b.n_cblk;
     p.n_pass = b.col_passes;
+    p.bgroup = s.bgroup; p.bskip = s.bskip;
+    p.x_extent = s.in_extent ? s.in_extent : (long)s.N * s.C * s.H * s.W;
     p.pass_stride = (long)b.n_part * b.Kp * b.Cp * taps;
     const unsigned grid = (unsigned)(((long)p.n_fblk * b.n_cblk * b.S * b.col_passes + kXcds - 1) / kXcds * kXcds);
 #define DSK_BW_LAUNCH(TPW, XR, RS, PF, PB)                                                                 \

@@ -22,7 +22,7 @@ conv_fwd_direct_kernel(const TI *__restrict__ x, const float *__restrict__ w, co
     const int n = (int)(idx / ((long)s.Wo * s.Ho * s.K));
     float acc = b ? b[f] : 0.f;
     for (int c = 0; c < s.C; ++c) {
-        const TI *xp = x + (((long)n * s.C + c) * s.H + u) * s.W + v;
+        const TI *xp = x + conv_in_offset(s, n, c, s.C, (long)s.H * s.W) + (long)u * s.W + v;
         const float *wp = w + ((long)f * s.C + c) * s.kh * s.kw;
         for (int a = 0; a < s.kh; ++a)
             for (int bb = 0; bb < s.kw; ++bb)
@@ -45,7 +45,7 @@ conv_bwd_data_direct_kernel(const TI *__restrict__ dy, const float *__restrict__
     const int n = (int)(idx / ((long)s.W * s.H * s.C));
     float acc = 0.f;
     for (int f = 0; f < s.K; ++f) {
-        const TI *dyp = dy + ((long)n * s.K + f) * s.Ho * s.Wo;
+        const TI *dyp = dy + conv_in_offset(s, n, f, s.K, (long)s.Ho * s.Wo);
         const float *wp = w + ((long)f * s.C + c) * s.kh * s.kw;
         for (int a = 0; a < s.kh; ++a) {
             const int u = p - a * s.d;
@@ -88,7 +88,7 @@ conv_bwd_weight_direct_kernel(const TI *__restrict__ x, const TI *__restrict__ d
     float acc = 0.f;
     for (int n = 0; n < s.N; ++n) {
         const TI *dyp = dy + ((long)n * s.K + f) * plane;
-        const TI *xp = x + (((long)n * s.C + c) * s.H + a * s.d) * s.W + bb * s.d;
+        const TI *xp = x + conv_in_offset(s, n, c, s.C, (long)s.H * s.W) + (long)a * s.d * s.W + bb * s.d;
         for (long t = threadIdx.x; t < plane; t += kThreads) {
             const int u = (int)(t / s.Wo), v = (int)(t % s.Wo);
             acc = fmaf(ldf(dyp, t), ldf(xp, (long)u * s.W + v), acc);

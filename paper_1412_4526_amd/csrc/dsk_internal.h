@@ -92,7 +92,27 @@ __device__ inline float act_apply(int act, float z)
 
 struct ConvShape {
     int N, C, H, W, K, kh, kw, d, Ho, Wo;
+    // Video (3-D) layers run as per-frame 2-D calls whose contraction also runs over the temporal taps: the
+    // frames of a video [T][C][H][W] are a batch of images, and the planes of temporal tap e are those of the
+    // frame e*dt further on.  All zero for a plain 2-D call.
+    //  * gsize / gjump (forward: channels of x; backward-data: filters of dy): the contraction's planes come in
+    //    groups of gsize; plane v of image slot b lies at (b*gsize + v)*plane + (v / gsize)*gjump elements.
+    //  * bgroup / bskip (the tensor the call reads: x, or dy for backward-data; for the weight gradient: x):
+    //    image n sits at slot n + n / bgroup * bskip (frames of the next video start bskip slots later).
+    //  * in_extent: elements of that tensor, from its first, that may be read (0: N*C*H*W, or N*K*Ho*Wo).
+    int gsize = 0;
+    long gjump = 0;
+    int bgroup = 0, bskip = 0;
+    long in_extent = 0;
 };
+
+// where plane c of image n of the tensor a convolution call reads begins (Cin planes of hw elements per image)
+__host__ __device__ inline long conv_in_offset(const ConvShape &s, int n, int c, int Cin, long hw)
+{
+    const long slot = s.bgroup ? n + (long)(n / s.bgroup) * s.bskip : n;
+    if (!s.gsize) return (slot * Cin + c) * hw;
+    return (slot * s.gsize + c) * hw + (long)(c / s.gsize) * s.gjump;
+}
 
 // ---- plain one-thread-per-output kernels (dsk_direct.hip) ----
 int launch_conv_fwd_direct(const void *x, const float *w, const float *b, void *y, const ConvShape &s,
@@ -111,6 +131,14 @@ int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const Co
                               dsk_dtype in, dsk_dtype out, void *ws, hipStream_t st);
 int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
                                 dsk_dtype in, void *ws, hipStream_t st);
+
+// kernel choice for one 2-D convolution call, as the entry points make it (dsk_api.hip)
+int dispatch_conv_fwd(const void *x, const float *w, const float *b, void *y, const ConvShape &s, dsk_dtype in,
+                      dsk_dtype out, int act, void *ws, hipStream_t st);
+int dispatch_conv_bwd_data(const void *dy, const float *w, void *dx, const ConvShape &s, dsk_dtype in, dsk_dtype out,
+                           void *ws, hipStream_t st);
+int dispatch_conv_bwd_weight(const void *x, const void *dy, float *dw, float *db, const ConvShape &s, dsk_dtype in,
+                             void *ws, hipStream_t st);
 
 // ---- bf16 matrix-core kernels for forward / backward-data on bf16 maps (dsk_conv_bf16.hip) ----
 size_t conv_bf16_ws_bytes(int which, const ConvShape &s);

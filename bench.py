@@ -91,6 +91,152 @@ def cpu_baseline(cfg, wl, forward_only, budget_s=20.0):
                          "forward only" if forward_only else "forward + backward", t)}
 
 
+def video_costs(net, elem):
+    """Algorithmic work per library call of a video network (3-D layers): FLOPs of the non-zero taps for convs,
+    minimum bytes for the rest."""
+    import paper_1412_4526_amd as dsk
+    N, out = net.N, {}
+    L = len(net.plan)
+    for l, (p, q) in enumerate(zip(net.plan, net.tplan)):
+        nin, nout = N * q.H * p.C * p.H * p.W, N * q.Ho * p.K * p.Ho * p.Wo
+        oel = 4 if l == L - 1 else elem
+        if p.kind == dsk.DSK_CONV:
+            fl = 2.0 * N * q.Ho * p.C * p.K * q.k * p.k * p.k * p.Ho * p.Wo
+            wb = q.k * p.K * p.C * p.k * p.k * 4
+            for tag in ("conv3d_fwd", "conv3d_bwd_data", "conv3d_bwd_weight"):
+                out[(tag, l)] = dict(flops=fl, bytes=nin * elem + nout * oel + wb)
+            out[("act_bwd", l)] = dict(flops=0.0, bytes=3 * nout * oel)
+        elif p.kind == dsk.DSK_MAXPOOL:
+            out[("maxpool3d_fwd", l)] = dict(flops=0.0, bytes=nin * elem + nout * (elem + 1))
+            out[("maxpool3d_bwd", l)] = dict(flops=0.0, bytes=nout * (elem + 1) + nin * elem)
+        else:
+            out[("avgpool3d_fwd", l)] = dict(flops=0.0, bytes=nin * elem + nout * elem)
+            out[("avgpool3d_bwd", l)] = dict(flops=0.0, bytes=nout * elem + nin * elem)
+    last = net.plan[-1]
+    vox = N * net.T * net.H * net.W
+    out[("softmax_xent", L)] = dict(flops=0.0, bytes=vox * (last.K * 4 + 4 + 1 + last.K * elem))
+    out[("pad", -1)] = dict(flops=0.0, bytes=N * net.T * net.net.C0 * net.H * net.W * 4 + net.xpad.numel() * elem)
+    return out
+
+
+def video_cpu_baseline(cfg, wl, forward_only, budget_s=20.0):
+    """The cube-scanning oracle on this machine's host cores, on a bounded sample of the clip's voxels."""
+    import numpy as np
+    import oracle
+    net = cfg.net
+    params = oracle.pack_params3d(wl.weights, wl.biases)
+    xpad = oracle.pad_video(wl.video, net.patch_t, net.patch)
+    threads = oracle.num_threads()
+    rng = np.random.default_rng(11)
+
+    def sample(count):
+        return np.stack([rng.integers(0, cfg.N, count), rng.integers(0, cfg.T, count), rng.integers(0, cfg.H, count),
+                         rng.integers(0, cfg.W, count)], 1).astype(np.int32)
+
+    def run(vox):
+        t0 = time.perf_counter()
+        oracle.cube_scan_forward(net, params, xpad, vox)
+        if not forward_only:
+            oracle.cube_scan_backward(net, params, xpad, vox, np.full((len(vox), net.classes), 1.0 / len(vox)))
+        return time.perf_counter() - t0
+
+    t_probe = run(sample(threads))
+    count = int(max(threads, threads * max(1.0, budget_s / max(t_probe, 1e-3))))
+    count -= count % threads
+    vox = sample(count)
+    t = run(vox)
+    return {"value": len(vox) / t, "unit": "labelled voxels/s", "cores": threads, "kind": "oracle",
+            "sample": "%d cubes of %dx%dx%d (of %d voxels), %s, cube-by-cube fp64, %.1f s"
+                      % (len(vox), net.patch_t, net.patch, net.patch, cfg.N * cfg.T * cfg.H * cfg.W,
+                         "forward only" if forward_only else "forward + backward", t)}
+
+
+def main_video(args):
+    """--video I: the same measurement on a video workload (3-D convolution and pooling; Sec. 6)."""
+    import numpy as np
+    import torch
+    import paper_1412_4526_amd as dsk
+    from workloads import VIDEO_CONFIGS, make_video_workload
+
+    cfg = VIDEO_CONFIGS[args.video]
+    dtype = args.dtype or cfg.dtype
+    elem = 4 if dtype == "f32" else 2
+    wl = make_video_workload(cfg.net, cfg.N, cfg.T, cfg.H, cfg.W, cfg.mask_frac, cfg.seed)
+    dev = "cuda:0"
+    dsk.dsk_set_conv_algo(args.algo)
+    net = dsk.WholeVideoNet(cfg.net, cfg.N, cfg.T, cfg.H, cfg.W, dtype, dev, train=not args.forward_only)
+    net.load_params(wl.weights, wl.biases)
+    video = torch.from_numpy(np.ascontiguousarray(np.transpose(wl.video, (0, 2, 1, 3, 4)))).to(dev)
+    labels = torch.from_numpy(wl.labels).to(dev)
+    mask = torch.from_numpy(wl.mask).to(dev)
+
+    def step():
+        net.forward(video)
+        if not args.forward_only:
+            net.loss_backward(labels, mask)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    net.timeline = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    timeline, net.timeline = net.timeline, None
+    per = {}
+    for tag, layer, e0, e1 in timeline:
+        per.setdefault((tag, layer), []).append(e0.elapsed_time(e1))
+    costs = video_costs(net, elem)
+    rows = []
+    for key, ms in per.items():
+        avg = sum(ms) / len(ms)
+        c = costs[key]
+        row = {"call": key[0], "layer": key[1], "ms": round(avg, 4)}
+        if 0 <= key[1] < len(net.plan):
+            p, q = net.plan[key[1]], net.tplan[key[1]]
+            row["shape"] = "C%d K%d kt%d k%d dt%d d%d %dx%dx%d" % (p.C, p.K, q.k, p.k, q.d, p.d, q.H, p.H, p.W)
+        if c["flops"] > 0:
+            row["tflops"] = round(c["flops"] / avg / 1e9, 2)
+            row["intensity"] = round(c["flops"] / c["bytes"], 1)
+        row["gbs"] = round(c["bytes"] / avg / 1e6, 1)
+        rows.append(row)
+    if args.layers:
+        for r in sorted(rows, key=lambda r: -r["ms"]):
+            sys.stderr.write(json.dumps(r) + "\n")
+    dom = max(rows, key=lambda r: r["ms"])
+    c = costs[(dom["call"], dom["layer"])]
+    peak_mfma = PEAK_FP32_MFMA      # video layers run on the fp32 matrix cores in both storage types
+    if c["flops"] > 0 and c["flops"] / c["bytes"] >= peak_mfma * 1e3 / PEAK_HBM:
+        roof = {"bound": "mfma", "achieved": dom["tflops"], "peak": peak_mfma, "unit": "TFLOP/s",
+                "frac": round(dom["tflops"] / peak_mfma, 4)}
+    else:
+        roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": PEAK_HBM, "unit": "GB/s", "frac": round(dom["gbs"] / PEAK_HBM, 4)}
+    roof.update(traffic=None, algorithmic_bytes=int(c["bytes"]), algorithmic_flops=int(c["flops"]),
+                kernel="%s layer %d (%s)" % (dom["call"], dom["layer"], dom.get("shape", "")), ms=dom["ms"])
+    voxels = cfg.N * cfg.T * cfg.H * cfg.W
+    worst_conv = min((r["tflops"] / peak_mfma for r in rows if "tflops" in r and r["intensity"] >= kDenseIntensity), default=None)
+    worst_pool = min((r["gbs"] / PEAK_HBM for r in rows if "pool" in r["call"]), default=None)
+    out = {
+        "metric": "labelled voxels/s whole-video %s" % ("fwd" if args.forward_only else "fwd+bwd"),
+        "value": voxels * args.steps / dt, "unit": "labelled voxels/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": "video[%d]: %s cube %dx%dx%d, %dx%dx%dx%dx%d clip, mask %.0f%%"
+                               % (args.video, cfg.net.name, cfg.net.patch_t, cfg.net.patch, cfg.net.patch, cfg.N, cfg.T,
+                                  cfg.net.C0, cfg.H, cfg.W, cfg.mask_frac * 100),
+                   "conv_algo": "auto" if args.algo == 0 else "direct", "launch": "eager"},
+        "roofline": roof,
+        "worst_dense_conv_frac_of_mfma_peak": None if worst_conv is None else round(worst_conv, 4),
+        "worst_pool_frac_of_hbm_peak": None if worst_pool is None else round(worst_pool, 4),
+        "layers": sorted(rows, key=lambda r: (r["layer"], r["call"])),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = video_cpu_baseline(cfg, wl, args.forward_only)
+    print(json.dumps(out))
+
+
 def measured_traffic(config, dtype, call, layer):
     """HBM bytes one launch of (call, layer) moved, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
     summary committed under profiles/ for this workload (bench.py cannot collect counters itself);
@@ -130,6 +276,8 @@ def main():
     ap.add_argument("--compare-fast-scanning", action="store_true",
                     help="also time the forward pass of the comparison method (fast scanning: strided layers run once "
                          "per starting offset on fragments) on the same workload; reported under \"fast_scanning\"")
+    ap.add_argument("--video", type=int, default=-1,
+                    help="measure video workload I (3-D convolution and pooling) instead of an image configuration")
     ap.add_argument("--layers", action="store_true", help="print the per-call table to stderr")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a known-size reference "
@@ -137,6 +285,9 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    if args.video >= 0:
+        return main_video(args)
 
     import numpy as np
     import torch

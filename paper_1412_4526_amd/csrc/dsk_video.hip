@@ -8,8 +8,8 @@
 // convolution is then a 2-D sparse convolution of every output frame whose contraction also runs over the kt
 // temporal taps: the planes of tap e are the C planes of the frame e*dt further on.  The 2-D matrix-core
 // kernels take such "grouped" planes (ConvShape), so a layer costs one launch (forward), kt launches (weight
-// gradient: one 2-D weight gradient per temporal tap, each over all frames), or one launch per video for the
-// frames that have all their temporal taps plus one per frame that has not (backward-data).
+// gradient: one 2-D weight gradient per temporal tap, each over all frames), or, per video, one launch for every
+// run of frames that are reached by the same temporal taps (backward-data).
 //
 // Weights are [kt][K][C][kh][kw]: a temporal tap's 2-D kernel is contiguous, which is what the weight gradient
 // writes and what backward-data reads (in reversed tap order); forward re-orders them once per call.
@@ -144,22 +144,23 @@ inline void tap_range(const Conv3 &c, int t, int &e_lo, int &e_hi)
     e_lo = over <= 0 ? 0 : (over + c.dt - 1) / c.dt;
 }
 
-// calls for one video: frames with all taps in one call, the others one by one; visit(call) or visit_zero(t)
+// calls for one video: one per run of consecutive frames that reach the same temporal taps (kt = 2, dt = 4: the
+// first four frames see tap 0 only, the last four tap 1 only, those between both); visit(call) or visit_zero(t0, cnt)
 template <typename F, typename Z>
 int for_bwd_data_calls(const Conv3 &c, F &&visit, Z &&visit_zero)
 {
-    const int lo = (c.kt - 1) * c.dt, hi = c.To;      // frames [lo, hi) have every tap
-    for (int t = 0; t < c.T; ++t) {
-        if (t == lo && lo < hi) {
-            const int rc = visit(bwd_data_call(c, lo, hi - lo, 0, c.kt - 1));
-            if (rc != DSK_OK) return rc;
-            t = hi - 1;
-            continue;
-        }
+    for (int t = 0; t < c.T;) {
         int e_lo, e_hi;
         tap_range(c, t, e_lo, e_hi);
-        const int rc = e_lo > e_hi ? visit_zero(t) : visit(bwd_data_call(c, t, 1, e_lo, e_hi));
+        int t1 = t + 1;
+        for (; t1 < c.T; ++t1) {
+            int lo, hi;
+            tap_range(c, t1, lo, hi);
+            if (lo != e_lo || hi != e_hi) break;
+        }
+        const int rc = e_lo > e_hi ? visit_zero(t, t1 - t) : visit(bwd_data_call(c, t, t1 - t, e_lo, e_hi));
         if (rc != DSK_OK) return rc;
+        t = t1;
     }
     return DSK_OK;
 }
@@ -198,7 +199,7 @@ size_t conv3_ws_bytes(int which, const Conv3 &c, dsk_dtype in)
         for_bwd_data_calls(c, [&](const BwdDataCall &q) {
             const size_t b = conv_ws_bytes(which, q.s, in);
             m = b > m ? b : m;
-            return (int)DSK_OK; }, [](int) { return (int)DSK_OK; });
+            return (int)DSK_OK; }, [](int, int) { return (int)DSK_OK; });
         return (c.kt > 1 ? align256(4 * (size_t)c.kt * c.w2d()) : 0) + m;
     }
     return 0;
@@ -497,11 +498,12 @@ int dsk_conv3d_bwd_data(const void *dy, const float *w, void *dx, int N, int T, 
                 return dispatch_conv_bwd_data((const char *)dy + first * ein, wr + (long)q.r_lo * c.w2d(),
                                               (char *)dx + ((long)n * c.T + q.t0) * c.frame_in() * eout, q.s, in, out, ws2, st);
             },
-            [&](int t) {
-                // a frame no output frame looks at (fewer output frames than the temporal spacing)
+            [&](int t, int cnt) {
+                // frames no output frame looks at (fewer output frames than the temporal spacing)
                 void *p = (char *)dx + ((long)n * c.T + t) * c.frame_in() * eout;
-                if (out == DSK_F32) fill_zero_kernel<float><<<dim3(blocks_for(c.frame_in())), dim3(kThreads), 0, st>>>((float *)p, c.frame_in());
-                else fill_zero_kernel<bf16><<<dim3(blocks_for(c.frame_in())), dim3(kThreads), 0, st>>>((bf16 *)p, c.frame_in());
+                const long count = (long)cnt * c.frame_in();
+                if (out == DSK_F32) fill_zero_kernel<float><<<dim3(blocks_for(count)), dim3(kThreads), 0, st>>>((float *)p, count);
+                else fill_zero_kernel<bf16><<<dim3(blocks_for(count)), dim3(kThreads), 0, st>>>((bf16 *)p, count);
                 return check_launch();
             });
         if (rc != DSK_OK) return rc;

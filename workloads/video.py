@@ -139,7 +139,7 @@ class VideoConfig:
 
 VIDEO_CONFIGS = (
     VideoConfig(TINY_VIDEO, 1, 5, 12, 14, 0.10),
-    VideoConfig(CLIP_NET, 1, 16, 128, 128, 0.01),
+    VideoConfig(CLIP_NET, 1, 16, 256, 256, 0.01),
 )
 
 

@@ -561,7 +561,6 @@ template <typename T, bool IS_MAX, int V>
 static int walk_bwd(const void *dy, const uint8_t *am, void *dx, const void *yprev, float *db, int act, void *ws,
                     int N, int C, int H, int W, int k, int d, hipStream_t st)
 {
-    constexpr bool B16 = sizeof(T) == 2;
     const WalkShape s = make_walk(N, C, H, W, k, d, H, W, V, walk_rows_bwd(k));
     const dim3 grid((unsigned)s.n_blocks), block(kWT);
     float *part = (float *)ws;

@@ -241,27 +241,55 @@ def test_clip_workload_sampled(dtype):
     assert_close(got, rs, "scores at sampled voxels", bf16=bf)
     if bf:
         return      # gradients in bf16 storage differ from the exact ones by the storage format itself (see the 2-D tests)
+
+    # Every stored map of every sampled cube against the oracle's per-cube maps: entry (q, u, v) of map l of the cube
+    # at (t, i, j) is the whole-video map l at (t + Dt*q, i + D*u, j + D*v).  Parity of the maps at the fp32 bar implies
+    # that a ReLU gate or pool winner the two sides decide differently is a near-tie: a gate differs only where both
+    # values are within the tolerance of zero, a winner only where the two taps are within twice the tolerance of each
+    # other in the pool's input map.  The gradient is discontinuous at such units (the whole error goes to the
+    # recorded winner), so gradients are compared on the cubes whose decisions are all identical.
+    maps, amax = oracle.cube_forward_maps(net, params, xpad, vox)
+    flipped = np.zeros(len(vox), bool)
+    decisions = 0
+    Dt = D = 1
+    for l, L in enumerate(net.layers):
+        Dt, D = Dt * L.st, D * L.s
+        ref = maps[l + 1]                                  # [P, C, mt, m, m]
+        mt, mm = ref.shape[2], ref.shape[3]
+        gm = m.maps[l + 1]
+        got = torch.stack([gm[v[0], v[1]:v[1] + Dt * mt:Dt, :, v[2]:v[2] + D * mm:D, v[3]:v[3] + D * mm:D] for v in vox])
+        got = to_np(got.permute(0, 2, 1, 3, 4))
+        assert_close(got, ref, "map %d of the sampled cubes" % (l + 1))
+        if L.kind == 1:      # max pool: recorded winners
+            ga = torch.stack([m.argmax[l][v[0], v[1]:v[1] + Dt * mt:Dt, :, v[2]:v[2] + D * mm:D, v[3]:v[3] + D * mm:D] for v in vox])
+            diff = ga.permute(0, 2, 1, 3, 4).cpu().numpy().astype(np.int32) != amax[l + 1]
+        elif L.act == ACT_RELU:
+            diff = (got > 0) != (ref > 0)
+        else:
+            continue
+        decisions += diff.size
+        flipped |= diff.reshape(len(vox), -1).any(1)
+    _say("clip workload: %d of %d sampled cubes hold a decision that differs (of %d decisions)" % (flipped.sum(), len(vox), decisions))
+    assert flipped.sum() <= len(vox) // 8
+    keep = vox[~flipped]
+    rk = rs[~flipped]
+    mask = np.zeros((N, T, H, W), np.uint8)
+    mask[keep[:, 0], keep[:, 1], keep[:, 2], keep[:, 3]] = 1
+    loss, dws, dbs = m.loss_backward(torch.from_numpy(wl.labels).to(DEV), torch.from_numpy(mask).to(DEV))
+    torch.cuda.synchronize()
     # per-voxel error from the oracle's own scores
     cls = net.classes
-    lab = wl.labels[vox[:, 0], vox[:, 1], vox[:, 2], vox[:, 3]]
-    z = rs - rs.max(1, keepdims=True)
+    lab = wl.labels[keep[:, 0], keep[:, 1], keep[:, 2], keep[:, 3]]
+    z = rk - rk.max(1, keepdims=True)
     p = np.exp(z) / np.exp(z).sum(1, keepdims=True)
-    onehot = np.eye(cls)[lab]
-    delta = (p - onehot) / len(vox)
-    rloss = -np.log(p[np.arange(len(vox)), lab]).mean()
-    rg, _ = oracle.cube_scan_backward(net, params, xpad, vox, delta)
+    delta = (p - np.eye(cls)[lab]) / len(keep)
+    rloss = -np.log(p[np.arange(len(keep)), lab]).mean()
+    rg, _ = oracle.cube_scan_backward(net, params, xpad, keep, delta)
     rdws, rdbs = oracle.unpack_params3d(net, rg)
     assert_close(loss, np.array([rloss]), "loss")
-    worst = 0.0
     for i in range(len(rdws)):
-        a, b = to_np(dws[i].permute(1, 2, 0, 3, 4)), rdws[i]
-        worst = max(worst, np.abs(a - b).max() / np.abs(b).max())
-        worst = max(worst, np.abs(to_np(dbs[i]) - rdbs[i]).max() / max(np.abs(rdbs[i]).max(), 1e-30))
-    _say("clip workload: worst relative gradient error %.3g" % worst)
-    # ReLU gates / pool winners that sit within rounding of a tie may be decided differently by two correct
-    # evaluations (see the 2-D full-size test, which verifies that on the maps); the bound here leaves room for
-    # one such unit in the sample
-    assert worst <= 2e-3, worst
+        assert_close(dws[i].permute(1, 2, 0, 3, 4), rdws[i], "dw%d" % i)
+        assert_close(dbs[i], rdbs[i], "db%d" % i)
 
 
 def test_video_argument_errors():

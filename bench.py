@@ -421,6 +421,11 @@ def main():
         "roofline": roof,
         "worst_dense_conv_frac_of_mfma_peak": None if worst_conv is None else round(worst_conv, 4),
         "worst_pool_frac_of_hbm_peak": None if worst_pool is None else round(worst_pool, 4),
+        # conv calls left out of the dense minimum (first layer, 1x1 layers): both fractions, the larger one binds
+        "conv_calls_near_or_below_the_ridge": [
+            {"call": r["call"], "layer": r["layer"], "shape": r.get("shape", ""), "intensity": r["intensity"],
+             "frac_of_mfma_peak": round(r["tflops"] / peak_mfma, 4), "frac_of_hbm_peak": round(r["gbs"] / PEAK_HBM, 4)}
+            for r in sorted(rows, key=lambda r: (r["layer"], r["call"])) if "tflops" in r and r["intensity"] < kDenseIntensity],
         "layers": sorted(rows, key=lambda r: (r["layer"], r["call"])),
     }
     if args.compare_fast_scanning:

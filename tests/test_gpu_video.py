@@ -292,6 +292,33 @@ def test_clip_workload_sampled(dtype):
         assert_close(dbs[i], rdbs[i], "db%d" % i)
 
 
+@pytest.mark.parametrize("case", CONV_CASES + [(1, 6, 32, 70, 200, 64, 3, 3, 2, 2, ACT_RELU), (2, 5, 64, 40, 130, 128, 2, 4, 1, 8, ACT_RELU)],
+                         ids=lambda c: "N%dT%dC%d_%dx%d_K%d_kt%dk%d_dt%dd%d" % c[:10])
+def test_conv3d_workspace_is_enough_and_respected(case):
+    """The three video convolution calls stay inside the workspace size the library asks for: a guard band behind
+    it keeps its pattern (results are covered by the parity tests)."""
+    N, T, C, H, W, K, kt, k, dt, d, act = case
+    _say("conv3d workspace", case)
+    x = torch.rand((N, T, C, H, W), device=DEV) - 0.5
+    w = torch.randn((kt, K, C, k, k), device=DEV) * 0.1
+    To, Ho, Wo = T - (kt - 1) * dt, H - (k - 1) * d, W - (k - 1) * d
+    dy = torch.randn((N, To, K, Ho, Wo), device=DEV)
+    guard = 1 << 16
+    for which in (dsk.DSK_WS_CONV_FWD, dsk.DSK_WS_CONV_BWD_DATA, dsk.DSK_WS_CONV_BWD_WEIGHT):
+        need = dsk.dsk_conv3d_workspace_bytes(which, N, T, C, H, W, K, kt, k, k, dt, d, dsk.DSK_F32)
+        need16 = (need + 15) // 16 * 16
+        buf = torch.full((need16 + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+        ws = buf[:max(need16, 16)]
+        if which == dsk.DSK_WS_CONV_FWD:
+            dsk.dsk_conv3d_fwd(x, w, None, dt, d, act, ws=ws)
+        elif which == dsk.DSK_WS_CONV_BWD_DATA:
+            dsk.dsk_conv3d_bwd_data(dy, w, dt, d, T, H, W, ws=ws)
+        else:
+            dsk.dsk_conv3d_bwd_weight(x, dy, kt, k, k, dt, d, ws=ws)
+        torch.cuda.synchronize()
+        assert bool((buf[need16:] == 0xA5).all()), "write beyond the workspace (call %d)" % which
+
+
 def test_video_argument_errors():
     x = torch.zeros((1, 4, 2, 8, 8), device=DEV)
     w = torch.zeros((3, 4, 2, 3, 3), device=DEV)

@@ -157,6 +157,38 @@ def test_pool_act_loss_argument_errors():
     assert dsk.status_string(0) == "DSK_OK"
 
 
+def test_video_argument_errors():
+    L = dsk.lib
+    ok = (1, 6, 4, 16, 16, 8, 2, 3, 3, 2, 2)        # N T C H W K kt kh kw dt d
+    f = lambda *a: L.dsk_conv3d_fwd(*a)
+    assert f(None, P, P, P, *ok, 0, 0, 0, None, 0, None) == dsk.DSK_EINVAL
+    assert f(P, P, P + 8, P, *ok, 0, 0, 0, None, 0, None) == dsk.DSK_EINVAL                       # misaligned bias
+    assert f(P, P, P, P, 1, 6, 4, 16, 16, 8, 2, 3, 3, 0, 2, 0, 0, 0, None, 0, None) == dsk.DSK_EINVAL   # dt < 1
+    assert f(P, P, P, P, 1, 6, 4, 16, 16, 8, 4, 3, 3, 2, 2, 0, 0, 0, None, 0, None) == dsk.DSK_ESHAPE   # 6-3*2 = 0 frames
+    assert f(P, P, P, P, 1, 6, 4, 16, 16, 8, 2, 9, 3, 2, 2, 0, 0, 0, None, 0, None) == dsk.DSK_ESHAPE
+    assert f(P, P, P, P, *ok, 0, 3, 0, None, 0, None) == dsk.DSK_EINVAL                          # bad dtype
+    assert L.dsk_conv3d_bwd_data(P, None, P, *ok, 0, 0, None, 0, None) == dsk.DSK_EINVAL
+    assert L.dsk_conv3d_bwd_weight(P, P, None, P, *ok, 0, None, 0, None) == dsk.DSK_EINVAL
+    big = (1, 8, 64, 64, 64, 64, 3, 3, 3, 2, 2)
+    for which, call in ((0, lambda ws, n: L.dsk_conv3d_fwd(P, P, P, P, *big, 0, 0, 0, ws, n, None)),
+                        (1, lambda ws, n: L.dsk_conv3d_bwd_data(P, P, P, *big, 0, 0, ws, n, None)),
+                        (2, lambda ws, n: L.dsk_conv3d_bwd_weight(P, P, P, P, *big, 0, ws, n, None))):
+        need = L.dsk_conv3d_workspace_bytes(which, *big, 0)
+        assert need > 0
+        assert call(None, 0) == dsk.DSK_EWORKSPACE
+        assert call(P, need - 1) == dsk.DSK_EWORKSPACE
+    assert L.dsk_conv3d_workspace_bytes(0, 1, 2, 4, 16, 16, 8, 3, 3, 3, 1, 1, 0) == 0             # invalid -> 0
+    pool = (1, 4, 2, 8, 8)
+    assert L.dsk_maxpool3d_fwd(None, P, P, *pool, 2, 2, 1, 1, 0, None) == dsk.DSK_EINVAL
+    assert L.dsk_maxpool3d_fwd(P, P, P, *pool, 2, 2, 4, 1, 0, None) == dsk.DSK_ESHAPE              # 4-1*4 = 0 frames
+    assert L.dsk_maxpool3d_fwd(P, P, P, *pool, 4, 8, 1, 1, 0, None) == dsk.DSK_ESHAPE              # 256 taps
+    assert L.dsk_maxpool3d_bwd(P, None, P, *pool, 2, 2, 1, 1, 0, None) == dsk.DSK_EINVAL           # argmax required
+    assert L.dsk_avgpool3d_fwd(P, P, *pool, 2, 2, 1, 0, 0, None) == dsk.DSK_EINVAL
+    assert L.dsk_avgpool3d_bwd(P, P + 4, *pool, 2, 2, 1, 1, 0, None) == dsk.DSK_EINVAL
+    assert L.dsk_pad_video(P, P, 1, 4, 3, 8, 8, -1, 0, 0, 0, 0, None) == dsk.DSK_EINVAL
+    assert L.dsk_pad_video(P, None, 1, 4, 3, 8, 8, 1, 1, 2, 2, 0, None) == dsk.DSK_EINVAL
+
+
 def test_product_does_not_touch_the_oracle():
     """The HIP path and the oracle share no code: nothing under the package mentions it."""
     pkg = os.path.join(ROOT, "paper_1412_4526_amd")

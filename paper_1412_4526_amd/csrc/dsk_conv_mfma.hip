@@ -53,6 +53,22 @@ static void allow_lds(size_t bytes)
 static constexpr int TH = 8;    // output rows per workgroup (one residue class mod d)
 static constexpr int TW = 64;   // output columns per workgroup
 
+// A rectangle of the output map covered by tiles of one shape: 4*nr rows of a residue class by 32*nh columns
+// (nr, nh = 1 or 2).  The whole map is one rectangle of 8 x 64 tiles unless its last tiles would be at most half
+// full: then the last strip of rows and / or columns is a rectangle of its own with tiles of half the height or
+// width, so that the matrix cores do not spend a whole tile on it.
+struct GcRegion {
+    int nr, nh;
+    int u_base, v_base;              // first row / column of the rectangle
+    int rows, cols, chan_stride;     // LDS tile: 4*nr+kh-1 by 32*nh+(kw-1)*d
+    unsigned m_cs, m_cols;           // 2^32 / chan_stride + 1 and 2^32 / cols + 1: e / x = mulhi(e, m) for the small e of the tile index
+    int n_xi;                        // input-tile floats per thread and chunk
+    int n_rowtile, n_coltile;
+    int nrb, full_cls;               // row blocks of d*4*nr rows; residue classes that have a tile in the last one (the others: nrb-1 tiles)
+    long tiles;                      // N * n_rowtile * n_coltile * n_fgrp
+    long first_block, per_xcd;       // physical workgroups [first_block, first_block + 8*per_xcd) take these tiles
+};
+
 struct GcParams {
     const void *in;
     void *out;
@@ -62,14 +78,12 @@ struct GcParams {
     int N, Cin, Hin, Win, Fout, Hout, Wout;
     int kh, kw, d, off_h, off_w, act;
     int Cpad, Cc, NC;    // padded channel count, channels per LDS chunk (even), chunks per tile
-    int rows, cols;      // LDS tile: TH+kh-1 by TW+(kw-1)*d
-    int chan_stride;     // rows*cols
-    unsigned m_cs, m_cols;   // 2^32 / chan_stride + 1 and 2^32 / cols + 1: e / x = mulhi(e, m) for the small e of the tile index
-    int xs_floats;       // Cc*chan_stride rounded up to a multiple of 256
-    int n_xi, n_wi;      // per thread and chunk: input-tile floats, weight float4s (both LDS parts padded)
-    int n_rowtile, n_coltile, n_fgrp;
-    int nrb, full_cls;   // row blocks of d*TH rows; residue classes that have a tile in the last one (the others: nrb-1 tiles)
-    long tiles;          // N * n_rowtile * n_coltile * n_fgrp output tiles
+    int xs_floats;       // Cc*chan_stride of the largest tile shape rounded up to a multiple of 256
+    int n_wi;            // weight float4s per thread and chunk (the LDS part is padded)
+    int n_fgrp;
+    GcRegion reg[4];     // reg[0] alone when the workgroups are persistent (split tiles)
+    int n_reg;
+    long tiles;          // output tiles of reg[0] (persistent workgroups)
     int rounds;          // persistent workgroups: whole tiles each of them takes first
     int rem_units;       // (tiles - rounds * n_wg) * NC: chunks of the tiles left after that
     long n_wg, per_xcd;  // logical workgroups; the grid is per_xcd * 8
@@ -104,32 +118,32 @@ gc_weight_prep_kernel(const float *__restrict__ w, float *__restrict__ wt, int K
 }
 
 // tile index -> filter group, image, first output row (of its residue class), first column
-__device__ inline void gc_decode_tile(const GcParams &p, long tile, int &fg, int &n, int &u0, int &v0)
+__device__ inline void gc_decode_tile(const GcParams &p, const GcRegion &g, long tile, int &fg, int &n, int &u0, int &v0)
 {
     fg = (int)(tile % p.n_fgrp); tile /= p.n_fgrp;
-    const int ct = (int)(tile % p.n_coltile); tile /= p.n_coltile;
-    const int rt = (int)(tile % p.n_rowtile);
-    n = (int)(tile / p.n_rowtile);
+    const int ct = (int)(tile % g.n_coltile); tile /= g.n_coltile;
+    const int rt = (int)(tile % g.n_rowtile);
+    n = (int)(tile / g.n_rowtile);
     // Row tiles are numbered class by class, down the map within a class: tiles that follow each other
     // (and run on one XCD at the same time) then share input rows and columns.  Numbered row block by
     // row block, neighbours would be different residue classes, which share no input row.
-    const int nf = p.full_cls * p.nrb;
+    const int nf = g.full_cls * g.nrb;
     int cls, rb;
     if (rt < nf) {
-        cls = rt / p.nrb; rb = rt - cls * p.nrb;
+        cls = rt / g.nrb; rb = rt - cls * g.nrb;
     } else {
-        const int q = (rt - nf) / (p.nrb - 1);
-        cls = p.full_cls + q; rb = rt - nf - q * (p.nrb - 1);
+        const int q = (rt - nf) / (g.nrb - 1);
+        cls = g.full_cls + q; rb = rt - nf - q * (g.nrb - 1);
     }
-    u0 = rb * p.d * TH + cls;
-    v0 = ct * TW;
+    u0 = g.u_base + rb * p.d * 4 * g.nr + cls;
+    v0 = g.v_base + ct * 32 * g.nh;
 }
 
 // bias, non-linearity, store; 32 consecutive pixels per filter per store instruction.
 // Register i of a lane belongs to filter 8*(i/4) + (i%4) + 4*hi of its 32-filter block: the
 // two candidates are uniform over the wave, so their biases come through scalar loads.
-template <typename TO, int WM>
-__device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][4], int fg, int n, int u0, int v0,
+template <typename TO, int WM, int NR, int NH>
+__device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][NR * NH], int fg, int n, int u0, int v0,
                                    int wave, int lo, int hi)
 {
     constexpr int TF = WM * 32;
@@ -154,9 +168,9 @@ __device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][4]
             for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(bv[wm][i]));
     }
 #pragma unroll
-    for (int wn = 0; wn < 4; ++wn) {
-        const int row = u0 + (2 * wave + (wn >> 1)) * p.d;
-        const int col = v0 + (wn & 1) * 32 + lo;
+    for (int wn = 0; wn < NR * NH; ++wn) {
+        const int row = u0 + (NR * wave + wn / NH) * p.d;
+        const int col = v0 + (wn % NH) * 32 + lo;
         if (row >= p.Hout || col >= p.Wout) continue;
         TO *o = out_n + (long)row * p.Wout + col + (hi ? 4 * plane : 0);
 #pragma unroll
@@ -189,21 +203,18 @@ __device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][4]
 //
 // Pipeline: the global loads of chunk t+1 are issued before the matrix cores start on chunk
 // t and land in registers meanwhile; they are written to LDS after chunk t is done.
-template <typename TI, typename TO, int WM, int XI, int WI, bool SPLIT>
-__global__ void __launch_bounds__(kThreads, 2)
-gemm_conv_kernel(GcParams p)
+//
+// NR, NH: shape of the tiles of rectangle g (4*NR rows by 32*NH columns); a wave owns rows NR*wave .. NR*wave+NR-1
+// of the tile and all its columns.  wg: the logical workgroup (persistent ones: of the launch; else: of g).
+template <typename TI, typename TO, int WM, int XI, int WI, bool SPLIT, int NR, int NH>
+__device__ __forceinline__ void gc_body(const GcParams &p, const GcRegion &g, const long wg, float *smem)
 {
-    extern __shared__ __align__(16) float smem[];
     constexpr int TF = WM * 32;
     float *xs = smem;                   // [Cc][rows][cols]
     float *wsm = smem + p.xs_floats;    // [Cc][taps][TF]
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    // consecutive physical workgroups go to different XCDs; give each XCD one contiguous
-    // run of logical workgroups so that neighbours (shared halo, same input tile) share an L2
-    const long wg = (long)(blockIdx.x % kXcds) * p.per_xcd + blockIdx.x / kXcds;
-    if (wg >= p.n_wg) return;
     int round = 0;
     int ub = (int)wg * p.rem_units / (int)p.n_wg;      // rem_units * n_wg < 2^31 by the host's choice
     const int ue = ((int)wg + 1) * p.rem_units / (int)p.n_wg;
@@ -220,7 +231,7 @@ gemm_conv_kernel(GcParams p)
         if (SPLIT) asm volatile("" : "+v"(tid));
         const int lane = tid & 63, lo = lane & 31, hi = lane >> 5;
         // per-lane LDS bases; the k-step offsets are uniform over the wave
-        const float *xlane = xs + hi * p.chan_stride + (2 * wave) * p.cols + lo;
+        const float *xlane = xs + hi * g.chan_stride + (NR * wave) * g.cols + lo;
         const float *wlane = wsm + hi * taps * TF + lo;
         long tile = wg;
         int cb = 0, ce = p.NC;
@@ -236,7 +247,7 @@ gemm_conv_kernel(GcParams p)
             }
         }
         int fg, n, u0, v0;
-        gc_decode_tile(p, tile, fg, n, u0, v0);
+        gc_decode_tile(p, g, tile, fg, n, u0, v0);
         const TI *in_n = (const TI *)p.in + (p.bgroup ? n + (long)(n / p.bgroup) * p.bskip : (long)n) * p.in_bstride;
         const TI *in_end = (const TI *)p.in + p.in_extent;
 
@@ -248,14 +259,14 @@ gemm_conv_kernel(GcParams p)
         unsigned voff[XI];
         unsigned zero = 0;
         {
-            const int n_x = p.Cc * p.chan_stride;
+            const int n_x = p.Cc * g.chan_stride;
             const int row0 = u0 - p.off_h, col0 = v0 - p.off_w;
 #pragma unroll
             for (int i = 0; i < XI; ++i) {
                 const int e = tid + i * kThreads;
                 // (exact: e * chan_stride and rem * cols stay below 2^32; a division costs some 40 instructions)
-                const int c = (int)__umulhi((unsigned)e, p.m_cs), rem = e - c * p.chan_stride;
-                const int r = (int)__umulhi((unsigned)rem, p.m_cols), col = rem - r * p.cols;
+                const int c = (int)__umulhi((unsigned)e, g.m_cs), rem = e - c * g.chan_stride;
+                const int r = (int)__umulhi((unsigned)rem, g.m_cols), col = rem - r * g.cols;
                 const int irow = row0 + r * p.d, icol = col0 + col;
                 const bool ok = e < n_x && irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win;
                 voff[i] = ok ? (unsigned)c * HW + (unsigned)(irow * p.Win + icol) : 0u;
@@ -268,14 +279,14 @@ gemm_conv_kernel(GcParams p)
         // which are not stored.  Backward-data: tiles that lie wholly inside the error map.  (Channels beyond Cin
         // meet zero weights, and the padding at the end of the LDS tile is never read.)
         const bool no_zeroing = (p.off_h == 0 && p.off_w == 0) ||
-                                (u0 - p.off_h >= 0 && u0 - p.off_h + (p.rows - 1) * p.d < p.Hin &&
-                                 v0 - p.off_w >= 0 && v0 - p.off_w + p.cols <= p.Win);
+                                (u0 - p.off_h >= 0 && u0 - p.off_h + (g.rows - 1) * p.d < p.Hin &&
+                                 v0 - p.off_w >= 0 && v0 - p.off_w + g.cols <= p.Win);
 
-        f32x16 acc[WM][4];
+        f32x16 acc[WM][NR * NH];
 #pragma unroll
         for (int wm = 0; wm < WM; ++wm)
 #pragma unroll
-            for (int wn = 0; wn < 4; ++wn)
+            for (int wn = 0; wn < NR * NH; ++wn)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
 
@@ -299,7 +310,7 @@ gemm_conv_kernel(GcParams p)
                 for (int i = 0; i < XI; ++i) {
                     unsigned v = voff[i];
                     if (!((zero >> i) & 1u)) {
-                        const unsigned cl = __umulhi((unsigned)(tid + i * kThreads), p.m_cs);      // the element's channel
+                        const unsigned cl = __umulhi((unsigned)(tid + i * kThreads), g.m_cs);      // the element's channel
                         const int cv = c0 + (int)cl;
                         if (cv >= p.Cin) v -= cl * HW;
                         else if (p.gsize) v += (unsigned)(cv / p.gsize - g0) * (unsigned)p.gjump;
@@ -321,11 +332,11 @@ gemm_conv_kernel(GcParams p)
             if (no_zeroing) {
 #pragma unroll
                 for (int i = 0; i < XI; ++i)
-                    if (i < p.n_xi) xs[tid + i * kThreads] = xv[i];
+                    if (i < g.n_xi) xs[tid + i * kThreads] = xv[i];
             } else {
 #pragma unroll
                 for (int i = 0; i < XI; ++i)
-                    if (i < p.n_xi) xs[tid + i * kThreads] = (zero >> i) & 1u ? 0.f : xv[i];
+                    if (i < g.n_xi) xs[tid + i * kThreads] = (zero >> i) & 1u ? 0.f : xv[i];
             }
 #pragma unroll
             for (int q = 0; q < WI; ++q)
@@ -335,20 +346,20 @@ gemm_conv_kernel(GcParams p)
 
             // ---- matrix cores: k index = (channel pair, tap); lanes 32..63 take the odd channel
             for (int cp = 0; cp < p.Cc; cp += 2) {
-                const float *xb = xlane + cp * p.chan_stride;
+                const float *xb = xlane + cp * g.chan_stride;
                 const float *wb = wlane + cp * taps * TF;
                 for (int ta = 0; ta < p.kh; ++ta) {
                     for (int tb = 0; tb < p.kw; ++tb) {
-                        const int xo = ta * p.cols + tb * p.d, wo = (ta * p.kw + tb) * TF;
-                        float A[WM], B[4];
+                        const int xo = ta * g.cols + tb * p.d, wo = (ta * p.kw + tb) * TF;
+                        float A[WM], B[NR * NH];
 #pragma unroll
                         for (int wm = 0; wm < WM; ++wm) A[wm] = wb[wo + wm * 32];
 #pragma unroll
-                        for (int wn = 0; wn < 4; ++wn) B[wn] = xb[xo + (wn >> 1) * p.cols + (wn & 1) * 32];
+                        for (int wn = 0; wn < NR * NH; ++wn) B[wn] = xb[xo + (wn / NH) * g.cols + (wn % NH) * 32];
 #pragma unroll
                         for (int wm = 0; wm < WM; ++wm)
 #pragma unroll
-                            for (int wn = 0; wn < 4; ++wn)
+                            for (int wn = 0; wn < NR * NH; ++wn)
                                 acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
                     }
                 }
@@ -356,14 +367,14 @@ gemm_conv_kernel(GcParams p)
         }
 
         if (!SPLIT || (cb == 0 && ce == p.NC)) {
-            gc_epilogue<TO, WM>(p, acc, fg, n, u0, v0, wave, lo, hi);
+            gc_epilogue<TO, WM, NR, NH>(p, acc, fg, n, u0, v0, wave, lo, hi);
         } else {
             // a piece of a split tile: slot 2g holds the piece a range begins with, 2g+1 the one it ends with
             float *slot = p.partial + (2 * wg + (first_piece ? 0 : 1)) * (long)(WM * 64 * kThreads);
 #pragma unroll
             for (int wm = 0; wm < WM; ++wm)
 #pragma unroll
-                for (int wn = 0; wn < 4; ++wn)
+                for (int wn = 0; wn < NR * NH; ++wn)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) slot[((wm * 4 + wn) * 16 + i) * kThreads + tid] = acc[wm][wn][i];
         }
@@ -373,6 +384,40 @@ gemm_conv_kernel(GcParams p)
         } else {
             ub += ce - cb;
             first_piece = false;
+        }
+    }
+}
+
+// HALF: the launch may hold rectangles with tiles of half the height or width (instances for them exist only
+// where the host uses them: one tile per workgroup, ordinary halos).
+template <typename TI, typename TO, int WM, int XI, int WI, bool SPLIT, bool HALF>
+__global__ void __launch_bounds__(kThreads, 2)
+gemm_conv_kernel(GcParams p)
+{
+    extern __shared__ __align__(16) float smem[];
+    // consecutive physical workgroups go to different XCDs; give each XCD one contiguous
+    // run of logical workgroups so that neighbours (shared halo, same input tile) share an L2
+    if constexpr (SPLIT) {
+        const long wg = (long)(blockIdx.x % kXcds) * p.per_xcd + blockIdx.x / kXcds;
+        if (wg >= p.n_wg) return;
+        gc_body<TI, TO, WM, XI, WI, true, 2, 2>(p, p.reg[0], wg, smem);
+    } else {
+        // the rectangles follow each other in the grid, each with its own XCD-aware order
+        int r = 0;
+        if constexpr (HALF) {
+            while (r + 1 < p.n_reg && (long)blockIdx.x >= p.reg[r + 1].first_block) ++r;
+        }
+        const GcRegion &g = p.reg[r];
+        const long local = (long)blockIdx.x - g.first_block;
+        const long wg = (local % kXcds) * g.per_xcd + local / kXcds;
+        if (wg >= g.tiles) return;
+        if constexpr (HALF) {
+            if (g.nr == 2 && g.nh == 2) gc_body<TI, TO, WM, XI, WI, false, 2, 2>(p, g, wg, smem);
+            else if (g.nr == 2) gc_body<TI, TO, WM, XI, WI, false, 2, 1>(p, g, wg, smem);
+            else if (g.nh == 2) gc_body<TI, TO, WM, XI, WI, false, 1, 2>(p, g, wg, smem);
+            else gc_body<TI, TO, WM, XI, WI, false, 1, 1>(p, g, wg, smem);
+        } else {
+            gc_body<TI, TO, WM, XI, WI, false, 2, 2>(p, g, wg, smem);
         }
     }
 }
@@ -409,7 +454,7 @@ gc_fixup_kernel(GcParams p)
         for (int r = 0; r < kFixRows; ++r) acc[r] += piece[r * kThreads];
     }
     int fg, n, u0, v0;
-    gc_decode_tile(p, (long)p.rounds * P + lt, fg, n, u0, v0);
+    gc_decode_tile(p, p.reg[0], (long)p.rounds * P + lt, fg, n, u0, v0);
     // register r0 + r of the lane is acc[wm][wn][i] of the convolution kernel
     const int wm = r0 / 64, wn = (r0 / 16) % 4, i0 = r0 % 16;
     const int row = u0 + (2 * wave + (wn >> 1)) * p.d;
@@ -442,12 +487,41 @@ static constexpr int kWI = 8;    // weight float4s per thread per chunk, at most
 
 struct GcPlan {
     bool ok, split;      // split: persistent workgroups with split tiles
+    bool half;           // some rectangle has tiles of half the height or width
     int TF, WM, Cc, Cpad, NC, rows, cols, chan_stride, xs_floats, n_xi, n_wi, n_fgrp, n_rowtile, n_coltile, nrb, full_cls;
     int XI;              // kXI or kXIBig: which set of kernels
+    GcRegion reg[4];
+    int n_reg;
+    long grid;           // physical workgroups when every workgroup takes one tile
     long tiles, n_wg;
     int rounds, rem_units;
     size_t lds_bytes, wt_bytes, partial_bytes;
 };
+
+// rectangle [u_base, u_base + Hr) x [v_base, v_base + Wr) of the output map in tiles of 4*nr rows by 32*nh columns
+static GcRegion gc_region(int nr, int nh, int u_base, int v_base, int Hr, int Wr, int N, int n_fgrp, int kh, int kw,
+                          int d, int Cc)
+{
+    GcRegion g{};
+    const int th = 4 * nr, tw = 32 * nh;
+    g.nr = nr; g.nh = nh; g.u_base = u_base; g.v_base = v_base;
+    g.rows = th + kh - 1;
+    g.cols = tw + (kw - 1) * d;
+    g.chan_stride = g.rows * g.cols;
+    g.m_cs = (unsigned)((1ull << 32) / (unsigned)g.chan_stride + 1);
+    g.m_cols = (unsigned)((1ull << 32) / (unsigned)g.cols + 1);
+    g.n_xi = (Cc * g.chan_stride + kThreads - 1) / kThreads;
+    // residue classes of the last row block that start beyond the rectangle hold no output: not enumerated
+    const int nrb = (Hr + d * th - 1) / (d * th);
+    const int last = Hr - (nrb - 1) * d * th;
+    g.n_rowtile = (nrb - 1) * d + (last < d ? last : d);
+    g.nrb = nrb;
+    g.full_cls = last < d ? last : d;
+    g.n_coltile = (Wr + tw - 1) / tw;
+    g.tiles = (long)N * g.n_rowtile * g.n_coltile * n_fgrp;
+    g.per_xcd = (g.tiles + kXcds - 1) / kXcds;
+    return g;
+}
 
 // Cin / Fout: channel and output counts of the GEMM (swapped for backward-data); N images of
 // Hout x Wout outputs
@@ -521,6 +595,55 @@ static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
         g.rem_units = 0;
         g.partial_bytes = 0;
     }
+    // Rectangles.  One tile per workgroup and ordinary halos: where the last strip of rows (columns) would fill
+    // its tiles at most half -- at most 4 rows per residue class, at most 32 columns -- it becomes a rectangle of
+    // its own with tiles of half the height (width).  The rows before it are whole row blocks of 8*d rows, so every
+    // residue class keeps its tiles.
+    g.reg[0] = gc_region(2, 2, 0, 0, Hout, Wout, N, g.n_fgrp, kh, kw, d, g.Cc);
+    g.n_reg = 1;
+    g.half = false;
+    if (g.XI == kXI) {
+        const int hrem = Hout % (TH * d), wrem = Wout % TW;
+        const int h_main = hrem > 0 && hrem <= 4 * d ? Hout - hrem : Hout;
+        const int w_main = wrem > 0 && wrem <= 32 ? Wout - wrem : Wout;
+        if (h_main < Hout || w_main < Wout) {
+            GcRegion reg[4];
+            int n_reg = 0;
+            double work = 0.;      // in whole tiles
+            for (int ri = 0; ri < 2; ++ri) {
+                const int u_base = ri ? h_main : 0, hr = ri ? Hout - h_main : h_main;
+                for (int ci = 0; ci < 2; ++ci) {
+                    const int v_base = ci ? w_main : 0, wr = ci ? Wout - w_main : w_main;
+                    if (hr <= 0 || wr <= 0) continue;
+                    reg[n_reg] = gc_region(ri ? 1 : 2, ci ? 1 : 2, u_base, v_base, hr, wr, N, g.n_fgrp, kh, kw, d, g.Cc);
+                    work += (double)reg[n_reg].tiles * reg[n_reg].nr * reg[n_reg].nh / 4.;
+                    ++n_reg;
+                }
+            }
+            // Persistent workgroups balance the tail of the grid exactly; one tile per workgroup with small tiles
+            // last balances it nearly as well (the small tiles fill the last round) and does less work.  Take
+            // the rectangles when that saves more than the quarter of a round the uneven end may cost.
+            const bool tail_split = g.split && g.tiles > kSlots;
+            const bool few_split = g.split && !tail_split;
+            if (!few_split && (!g.split || work / kSlots + 0.25 < (double)g.tiles / kSlots)) {
+                for (int r = 0; r < n_reg; ++r) g.reg[r] = reg[r];
+                g.n_reg = n_reg;
+                g.half = true;
+                if (g.split) {
+                    g.split = false;
+                    g.n_wg = g.tiles;
+                    g.rounds = 0;
+                    g.rem_units = 0;
+                    g.partial_bytes = 0;
+                }
+            }
+        }
+    }
+    g.grid = 0;
+    for (int r = 0; r < g.n_reg; ++r) {
+        g.reg[r].first_block = g.grid;
+        g.grid += g.reg[r].per_xcd * kXcds;
+    }
     g.ok = true;
     return g;
 }
@@ -528,23 +651,27 @@ static GcPlan gc_plan(int N, int Cin, int Fout, int Hout, int Wout, int kh, int 
 template <typename TI, typename TO>
 static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
 {
-    const unsigned grid = (unsigned)(p.per_xcd * kXcds);
+    const unsigned grid = (unsigned)(g.split ? p.per_xcd * kXcds : g.grid);
     if (g.XI == kXIBig && g.WM == 2 && g.split)
-        gemm_conv_kernel<TI, TO, 2, kXIBig, kWI, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 2, kXIBig, kWI, true, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.XI == kXIBig && g.WM == 2)
-        gemm_conv_kernel<TI, TO, 2, kXIBig, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 2, kXIBig, kWI, false, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.XI == kXIBig && g.split)
-        gemm_conv_kernel<TI, TO, 1, kXIBig, kWI, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 1, kXIBig, kWI, true, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.XI == kXIBig)
-        gemm_conv_kernel<TI, TO, 1, kXIBig, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 1, kXIBig, kWI, false, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.WM == 2 && g.split)
-        gemm_conv_kernel<TI, TO, 2, kXI, kWI, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 2, kXI, kWI, true, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    else if (g.WM == 2 && g.half)
+        gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.WM == 2)
-        gemm_conv_kernel<TI, TO, 2, kXI, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.split)
-        gemm_conv_kernel<TI, TO, 1, kXI, kWI, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 1, kXI, kWI, true, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    else if (g.half)
+        gemm_conv_kernel<TI, TO, 1, kXI, kWI, false, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else
-        gemm_conv_kernel<TI, TO, 1, kXI, kWI, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+        gemm_conv_kernel<TI, TO, 1, kXI, kWI, false, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     if (g.split) {
         const unsigned left = (unsigned)(g.rem_units / g.NC);
         if (g.WM == 2)
@@ -560,7 +687,7 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
 {
     const GcPlan g = gc_plan(N, Cin, Fout, Hout, Wout, kh, kw, d);
     if (!g.ok) return DSK_ESHAPE;
-    if ((g.n_wg + kXcds - 1) / kXcds * kXcds > 0x7fffffffL) return DSK_ESHAPE;      // before anything is launched
+    if ((g.n_wg + kXcds - 1) / kXcds * kXcds > 0x7fffffffL || g.grid > 0x7fffffffL) return DSK_ESHAPE;      // before anything is launched
     const int taps = kh * kw;
     float *wt = (float *)ws;
     {
@@ -574,11 +701,10 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     p.N = N; p.Cin = Cin; p.Hin = Hin; p.Win = Win; p.Fout = Fout; p.Hout = Hout; p.Wout = Wout;
     p.kh = kh; p.kw = kw; p.d = d; p.off_h = off ? (kh - 1) * d : 0; p.off_w = off ? (kw - 1) * d : 0;
     p.act = act;
-    p.Cpad = g.Cpad; p.Cc = g.Cc; p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.chan_stride = g.chan_stride;
-    p.xs_floats = g.xs_floats; p.n_xi = g.n_xi; p.n_wi = g.n_wi;
-    p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp; p.nrb = g.nrb; p.full_cls = g.full_cls;
-    p.m_cs = (unsigned)((1ull << 32) / (unsigned)g.chan_stride + 1);
-    p.m_cols = (unsigned)((1ull << 32) / (unsigned)g.cols + 1);
+    p.Cpad = g.Cpad; p.Cc = g.Cc; p.NC = g.NC;
+    p.xs_floats = g.xs_floats; p.n_wi = g.n_wi; p.n_fgrp = g.n_fgrp;
+    for (int r = 0; r < g.n_reg; ++r) p.reg[r] = g.reg[r];
+    p.n_reg = g.n_reg;
     p.tiles = g.tiles; p.rounds = g.rounds; p.rem_units = g.rem_units; p.n_wg = g.n_wg;
     p.per_xcd = (p.n_wg + kXcds - 1) / kXcds;
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;

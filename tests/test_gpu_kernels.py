@@ -42,6 +42,10 @@ CONV_CASES = [
     (3, 70, 9, 13, 3, 1, 2, 0),        # 1x1, planes smaller than one wave's 128 pixels
     (1, 300, 20, 33, 2, 1, 1, 0),      # 1x1, more than 256 channels, two filters
     (1, 40, 50, 70, 72, 3, 4, 1),      # 3x3 with three 32-filter blocks: two blocks per workgroup, one group half empty
+    (1, 8, 40, 88, 40, 3, 2, 1),       # last rows and columns at most half a tile, forward and backward-data: half-size tiles
+    (2, 6, 30, 80, 33, 3, 1, 2),       # the same with two images and two filter groups
+    (1, 16, 20, 30, 16, 2, 4, 0),      # a map smaller than half a tile both ways: one rectangle of 4 x 32 tiles
+    (1, 8, 36, 150, 16, 5, 2, 1),      # only the column strip is narrow forward, only the row strip low backward
 ]
 
 

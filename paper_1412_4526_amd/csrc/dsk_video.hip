@@ -245,10 +245,13 @@ __device__ inline void st4(BufRsrc r, bf16 *, unsigned off, const float (&v)[4])
     __builtin_amdgcn_raw_buffer_store_b64(t, r, (int)(off * 2u), 0, 0);
 }
 
-template <typename T, bool IS_MAX>
+// KT, K: window sizes known at compile time (0: taken from s); then all taps of a thread are loaded before the
+// first is used, instead of one memory round trip per tap.
+template <typename T, bool IS_MAX, int KT, int K>
 __global__ void __launch_bounds__(kThreads)
 pool3d_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restrict__ am, Pool3 s)
 {
+    const int kt = KT ? KT : s.kt, k = K ? K : s.k;
     const int op = (int)(blockIdx.x / (unsigned)s.bpp);      // output plane (n*To + t)*C + c
     const int tt = (int)(blockIdx.x % (unsigned)s.bpp) * kThreads + (int)threadIdx.x;
     const int row = tt / s.groups, col = (tt - row * s.groups) * 4;
@@ -262,28 +265,44 @@ pool3d_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restric
     const int nv = s.Wo - col < 4 ? s.Wo - col : 4;
     float best[4] = {0.f, 0.f, 0.f, 0.f};
     int bi[4] = {0, 0, 0, 0};
-    int tap = 0;
-    for (int e = 0; e < s.kt; ++e)
-        for (int a = 0; a < s.k; ++a)
-            for (int b = 0; b < s.k; ++b, ++tap) {
-                const unsigned off = (unsigned)e * fstride + (unsigned)((row + a * s.d) * s.W + col + b * s.d);
-                float v[4] = {0.f, 0.f, 0.f, 0.f};
-                if (nv == 4) {
-                    ld4(rx, xp, off, v);
-                } else {
-                    for (int j = 0; j < nv; ++j) v[j] = buf_ld(rx, xp, off + (unsigned)j, 0u);
-                }
+    auto visit = [&](int tap, const float (&v)[4]) __attribute__((always_inline)) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (IS_MAX) {
-                        if (tap == 0 || v[j] > best[j]) { best[j] = v[j]; bi[j] = tap; }
-                    } else {
-                        best[j] += v[j];
-                    }
-                }
+        for (int j = 0; j < 4; ++j) {
+            if (IS_MAX) {
+                if (tap == 0 || v[j] > best[j]) { best[j] = v[j]; bi[j] = tap; }
+            } else {
+                best[j] += v[j];
             }
+        }
+    };
+    if (KT != 0 && nv == 4) {
+        float v[(KT ? KT * K * K : 1)][4];
+#pragma unroll
+        for (int e = 0; e < KT; ++e)
+#pragma unroll
+            for (int a = 0; a < K; ++a)
+#pragma unroll
+                for (int b = 0; b < K; ++b)
+                    ld4(rx, xp, (unsigned)e * fstride + (unsigned)((row + a * s.d) * s.W + col + b * s.d), v[(e * K + a) * K + b]);
+#pragma unroll
+        for (int t = 0; t < KT * K * K; ++t) visit(t, v[t]);
+    } else {
+        int tap = 0;
+        for (int e = 0; e < kt; ++e)
+            for (int a = 0; a < k; ++a)
+                for (int b = 0; b < k; ++b, ++tap) {
+                    const unsigned off = (unsigned)e * fstride + (unsigned)((row + a * s.d) * s.W + col + b * s.d);
+                    float v[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (nv == 4) {
+                        ld4(rx, xp, off, v);
+                    } else {
+                        for (int j = 0; j < nv; ++j) v[j] = buf_ld(rx, xp, off + (unsigned)j, 0u);
+                    }
+                    visit(tap, v);
+                }
+    }
     if (!IS_MAX) {
-        const float inv = 1.f / (float)(s.kt * s.k * s.k);
+        const float inv = 1.f / (float)(kt * k * k);
 #pragma unroll
         for (int j = 0; j < 4; ++j) best[j] *= inv;
     }
@@ -307,7 +326,9 @@ pool3d_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, uint8_t *__restric
 
 // Gather form: every input element adds up the outputs whose window holds it (and, for max pooling, whose
 // recorded winner it is); fixed order, no atomics.
-template <typename T, bool IS_MAX>
+// KT, K as in the forward kernel: with compile-time sizes the candidate outputs of all taps are loaded together
+// (from a harmless address where a tap does not apply), then added in a fixed order.
+template <typename T, bool IS_MAX, int KT, int K>
 __global__ void __launch_bounds__(kThreads)
 pool3d_bwd_kernel(const T *__restrict__ dy, const uint8_t *__restrict__ am, T *__restrict__ dx, Pool3 s)
 {
@@ -332,6 +353,52 @@ pool3d_bwd_kernel(const T *__restrict__ dy, const uint8_t *__restrict__ am, T *_
         const BufRsrc rdy = buf_rsrc(dyp, dy + s.out_elems);
         const BufRsrc ra = buf_rsrc(ap, IS_MAX ? am + s.out_elems : ap);
         const unsigned fstride = (unsigned)(s.dt * s.C) * HoWo;
+        // one tap, element by element (groups cut by the ends of a row)
+        auto tap_by_element = [&](int e, int a, int b) __attribute__((always_inline)) {
+            const int u = row - a * s.d, v0 = col - b * s.d;
+            const int tap = (e * s.k + a) * s.k + b;
+            const unsigned fo = (unsigned)(e_hi - e) * fstride;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int v = v0 + j;
+                if (v < 0 || v >= s.Wo) continue;
+                const unsigned o = fo + (unsigned)(u * s.Wo + v);
+                const float g = buf_ld(rdy, dyp, o, 0u);
+                if (IS_MAX) acc[j] += buf_ld(ra, ap, o, 0u) == tap ? g : 0.f;
+                else acc[j] += g;
+            }
+        };
+        if (KT != 0) {
+            constexpr int NT = KT ? KT * K * K : 1;
+            float g[NT][4];
+            unsigned w[NT];
+            unsigned full = 0, part = 0;      // bit t: all four / some of the four candidate outputs of tap t exist
+#pragma unroll
+            for (int e = 0; e < KT; ++e)
+#pragma unroll
+                for (int a = 0; a < K; ++a)
+#pragma unroll
+                    for (int b = 0; b < K; ++b) {
+                        const int t = (e * K + a) * K + b;
+                        const int u = row - a * s.d, v0 = col - b * s.d;
+                        const bool here = e >= e_lo && e <= e_hi && u >= 0 && u < s.Ho;
+                        const bool all4 = here && v0 >= 0 && v0 + 3 < s.Wo;
+                        full |= all4 ? 1u << t : 0u;
+                        part |= here && !all4 && v0 + 3 >= 0 && v0 < s.Wo ? 1u << t : 0u;
+                        const unsigned off = all4 ? (unsigned)(e_hi - e) * fstride + (unsigned)(u * s.Wo + v0) : 0u;
+                        ld4(rdy, dyp, off, g[t]);
+                        w[t] = IS_MAX ? (unsigned)__builtin_amdgcn_raw_buffer_load_b32(ra, (int)off, 0, 0) : 0u;
+                    }
+#pragma unroll
+            for (int t = NT - 1; t >= 0; --t) {
+                if ((full >> t) & 1u) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[j] += !IS_MAX || (int)((w[t] >> (8 * j)) & 0xffu) == t ? g[t][j] : 0.f;
+                } else if ((part >> t) & 1u) {
+                    tap_by_element(t / (K * K), (t / K) % K, t % K);
+                }
+            }
+        } else
         for (int e = e_hi; e >= e_lo; --e) {
             const unsigned fo = (unsigned)(e_hi - e) * fstride;
             for (int a = 0; a < s.k; ++a) {
@@ -404,10 +471,14 @@ int pool3_fwd(const void *x, void *y, uint8_t *am, Pool3 p, dsk_dtype t, hipStre
     const long blocks = (long)p.N * p.To * p.C * p.bpp;
     if (blocks > 0x7fffffffL) return DSK_ESHAPE;
     clear_errors();
-    if (t == DSK_F32)
-        pool3d_fwd_kernel<float, IS_MAX><<<dim3((unsigned)blocks), dim3(kThreads), 0, st>>>((const float *)x, (float *)y, am, p);
-    else
-        pool3d_fwd_kernel<bf16, IS_MAX><<<dim3((unsigned)blocks), dim3(kThreads), 0, st>>>((const bf16 *)x, (bf16 *)y, am, p);
+    const dim3 grid((unsigned)blocks), block(kThreads);
+    if (p.kt == 2 && p.k == 2) {
+        if (t == DSK_F32) pool3d_fwd_kernel<float, IS_MAX, 2, 2><<<grid, block, 0, st>>>((const float *)x, (float *)y, am, p);
+        else pool3d_fwd_kernel<bf16, IS_MAX, 2, 2><<<grid, block, 0, st>>>((const bf16 *)x, (bf16 *)y, am, p);
+    } else {
+        if (t == DSK_F32) pool3d_fwd_kernel<float, IS_MAX, 0, 0><<<grid, block, 0, st>>>((const float *)x, (float *)y, am, p);
+        else pool3d_fwd_kernel<bf16, IS_MAX, 0, 0><<<grid, block, 0, st>>>((const bf16 *)x, (bf16 *)y, am, p);
+    }
     return check_launch();
 }
 
@@ -419,10 +490,14 @@ int pool3_bwd(const void *dy, const uint8_t *am, void *dx, Pool3 p, dsk_dtype t,
     const long blocks = (long)p.N * p.T * p.C * p.bpp;
     if (blocks > 0x7fffffffL) return DSK_ESHAPE;
     clear_errors();
-    if (t == DSK_F32)
-        pool3d_bwd_kernel<float, IS_MAX><<<dim3((unsigned)blocks), dim3(kThreads), 0, st>>>((const float *)dy, am, (float *)dx, p);
-    else
-        pool3d_bwd_kernel<bf16, IS_MAX><<<dim3((unsigned)blocks), dim3(kThreads), 0, st>>>((const bf16 *)dy, am, (bf16 *)dx, p);
+    const dim3 grid((unsigned)blocks), block(kThreads);
+    if (p.kt == 2 && p.k == 2) {
+        if (t == DSK_F32) pool3d_bwd_kernel<float, IS_MAX, 2, 2><<<grid, block, 0, st>>>((const float *)dy, am, (float *)dx, p);
+        else pool3d_bwd_kernel<bf16, IS_MAX, 2, 2><<<grid, block, 0, st>>>((const bf16 *)dy, am, (bf16 *)dx, p);
+    } else {
+        if (t == DSK_F32) pool3d_bwd_kernel<float, IS_MAX, 0, 0><<<grid, block, 0, st>>>((const float *)dy, am, (float *)dx, p);
+        else pool3d_bwd_kernel<bf16, IS_MAX, 0, 0><<<grid, block, 0, st>>>((const bf16 *)dy, am, (bf16 *)dx, p);
+    }
     return check_launch();
 }
 

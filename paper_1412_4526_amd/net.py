@@ -8,7 +8,43 @@ import torch
 from . import binding as B
 
 
-class WholeImageNet:
+class GraphReplay:
+    """Capture of one step (forward, and loss + backward when labels and a mask are given) into a HIP graph,
+    for runners whose step is `forward(x)` then `loss_backward(labels, mask)` on preallocated buffers."""
+
+    def capture(self, image, labels=None, mask=None):
+        """Record one step (forward, and loss + backward when labels and mask are given) into a
+        HIP graph.  Every call of a step is a kernel launch of libdsk on preallocated buffers, so
+        the step replays as a whole; small networks are launch-bound otherwise.  `replay` copies
+        new inputs into the captured input tensors."""
+        assert self.timeline is None, "events of a timeline cannot be recorded into a graph"
+        self._in = [image.clone(), None if labels is None else labels.clone(), None if mask is None else mask.clone()]
+        side = torch.cuda.Stream(device=self.device)
+        side.wait_stream(torch.cuda.current_stream(self.device))
+        with torch.cuda.stream(side):          # warm-up off the capture, as torch asks for
+            self._step_eager()
+        torch.cuda.current_stream(self.device).wait_stream(side)
+        torch.cuda.synchronize(self.device)
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self._step_eager()
+        return self
+
+    def _step_eager(self):
+        self.forward(self._in[0])
+        if self._in[1] is not None:
+            self.loss_backward(self._in[1], self._in[2])
+
+    def replay(self, image=None, labels=None, mask=None):
+        """Run the captured step; results are in scores / loss / dw / db as after the eager calls."""
+        for dst, src in zip(self._in, (image, labels, mask)):
+            if src is not None and dst is not None and src.data_ptr() != dst.data_ptr():
+                dst.copy_(src)
+        self.graph.replay()
+        return self.scores
+
+
+class WholeImageNet(GraphReplay):
     """The stride-1, d-regularly-sparse version of an original strided patch CNN,
     bound to one image batch shape.
 
@@ -152,38 +188,6 @@ class WholeImageNet:
                 g = gin
                 cur = 1 - cur
         return self.loss, self.dw, self.db
-
-    # ------------------------------------------------------------------ HIP graph
-    def capture(self, image, labels=None, mask=None):
-        """Record one step (forward, and loss + backward when labels and mask are given) into a
-        HIP graph.  Every call of a step is a kernel launch of libdsk on preallocated buffers, so
-        the step replays as a whole; small networks are launch-bound otherwise.  `replay` copies
-        new inputs into the captured input tensors."""
-        assert self.timeline is None, "events of a timeline cannot be recorded into a graph"
-        self._in = [image.clone(), None if labels is None else labels.clone(), None if mask is None else mask.clone()]
-        side = torch.cuda.Stream(device=self.device)
-        side.wait_stream(torch.cuda.current_stream(self.device))
-        with torch.cuda.stream(side):          # warm-up off the capture, as torch asks for
-            self._step_eager()
-        torch.cuda.current_stream(self.device).wait_stream(side)
-        torch.cuda.synchronize(self.device)
-        self.graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(self.graph):
-            self._step_eager()
-        return self
-
-    def _step_eager(self):
-        self.forward(self._in[0])
-        if self._in[1] is not None:
-            self.loss_backward(self._in[1], self._in[2])
-
-    def replay(self, image=None, labels=None, mask=None):
-        """Run the captured step; results are in scores / loss / dw / db as after the eager calls."""
-        for dst, src in zip(self._in, (image, labels, mask)):
-            if src is not None and dst is not None and src.data_ptr() != dst.data_ptr():
-                dst.copy_(src)
-        self.graph.replay()
-        return self.scores
 
     # ------------------------------------------------------------------ bookkeeping for benchmarks
     def conv_flops(self):

@@ -8,9 +8,10 @@ from types import SimpleNamespace
 import torch
 
 from . import binding as B
+from .net import GraphReplay
 
 
-class WholeVideoNet:
+class WholeVideoNet(GraphReplay):
     """net: object with C0, patch_t, patch, layers (each: kind, K, k, s, kt, st, act) -- the ORIGINAL strided
     cube CNN.  Maps are [N, T, C, H, W] (frame-major); weights [kt, K, C, k, k]."""
 

@@ -72,10 +72,17 @@ __device__ inline void wld(BufRsrc r, const float *, unsigned off, float (&o)[V]
 template <int V>
 __device__ inline void wld(BufRsrc r, const bf16 *, unsigned off, float (&o)[V])
 {
-    static_assert(V == 4, "four bf16 pixels per access");
-    const wu2 t = __builtin_amdgcn_raw_buffer_load_b64(r, (int)(off * 2u), 0, kAuxLd);
+    static_assert(V == 4 || V == 8, "four or eight bf16 pixels per access");
+    unsigned t[V / 2];
+    if constexpr (V == 4) {
+        const wu2 q = __builtin_amdgcn_raw_buffer_load_b64(r, (int)(off * 2u), 0, kAuxLd);
+        t[0] = q[0]; t[1] = q[1];
+    } else {
+        const wu4 q = __builtin_amdgcn_raw_buffer_load_b128(r, (int)(off * 2u), 0, kAuxLd);
+        t[0] = q[0]; t[1] = q[1]; t[2] = q[2]; t[3] = q[3];
+    }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < V / 2; ++i) {
         o[2 * i] = __builtin_bit_cast(float, t[i] << 16);
         o[2 * i + 1] = __builtin_bit_cast(float, t[i] & 0xffff0000u);
     }
@@ -90,14 +97,19 @@ __device__ inline void wst(BufRsrc r, float *, unsigned off, float (&v)[V])
 template <int V>
 __device__ inline void wst(BufRsrc r, bf16 *, unsigned off, float (&v)[V])
 {
-    unsigned h[4];
+    unsigned h[V];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < V; ++j) {
         h[j] = f32_to_bf16(v[j]).v;
         v[j] = __builtin_bit_cast(float, h[j] << 16);
     }
-    const wu2 t = {h[0] | h[1] << 16, h[2] | h[3] << 16};
-    __builtin_amdgcn_raw_buffer_store_b64(t, r, (int)(off * 2u), 0, kAuxSt);
+    if constexpr (V == 4) {
+        const wu2 t = {h[0] | h[1] << 16, h[2] | h[3] << 16};
+        __builtin_amdgcn_raw_buffer_store_b64(t, r, (int)(off * 2u), 0, kAuxSt);
+    } else {
+        const wu4 t = {h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16};
+        __builtin_amdgcn_raw_buffer_store_b128(t, r, (int)(off * 2u), 0, kAuxSt);
+    }
 }
 __device__ inline float round_as(const float *, float v) { return v; }
 __device__ inline float round_as(const bf16 *, float v) { return bf16_to_f32(f32_to_bf16(v)); }
@@ -520,13 +532,14 @@ static WalkShape make_walk(int N, int C, int H, int W, int k, int d, int rows, i
 // rows per batch of loads: what the registers hold
 static constexpr int walk_rows(int k, bool) { return k == 2 ? 8 : 4; }
 // the gradient kernels hold two or three times as much per row (values and tap indices of k tap columns, and y)
-static constexpr int walk_rows_bwd(int k) { return k == 2 ? 4 : 2; }
+static constexpr int walk_rows_bwd(int k, int v) { return (k == 2 ? 16 : 8) / v; }
+// pixels per access in the gradient kernels: 16 bytes in both types
+static constexpr int walk_v_bwd(dsk_dtype t) { return t == DSK_F32 ? 4 : 8; }
 
 bool pool_walk_ok(int N, int C, int H, int W, int k, int d, dsk_dtype t)
 {
     if (k != 2 && k != 3) return false;
-    const int V = 4, R = walk_rows_bwd(k);
-    (void)t;
+    const int V = walk_v_bwd(t), R = walk_rows_bwd(k, V);
     return make_walk(N, C, H, W, k, d, H, W, V, R).n_blocks < 0x7fffffffL;      // the gradient's grid is the larger one
 }
 
@@ -553,7 +566,7 @@ int launch_pool_walk_fwd(const void *x, void *y, uint8_t *am, int N, int C, int 
 
 size_t pool_bwd_act_bias_ws_bytes(int N, int C, int H, int W, int k, int d, dsk_dtype t)
 {
-    const WalkShape s = make_walk(N, C, H, W, k, d, H, W, 4, walk_rows_bwd(k));
+    const WalkShape s = make_walk(N, C, H, W, k, d, H, W, walk_v_bwd(t), walk_rows_bwd(k, walk_v_bwd(t)));
     return (size_t)s.n_blocks * sizeof(float);
 }
 
@@ -561,11 +574,11 @@ template <typename T, bool IS_MAX, int V>
 static int walk_bwd(const void *dy, const uint8_t *am, void *dx, const void *yprev, float *db, int act, void *ws,
                     int N, int C, int H, int W, int k, int d, hipStream_t st)
 {
-    const WalkShape s = make_walk(N, C, H, W, k, d, H, W, V, walk_rows_bwd(k));
+    const WalkShape s = make_walk(N, C, H, W, k, d, H, W, V, walk_rows_bwd(k, V));
     const dim3 grid((unsigned)s.n_blocks), block(kWT);
     float *part = (float *)ws;
     const bool fuse = db != nullptr;
-#define DSK_WB(KK, FU) pool_walk_bwd_kernel<T, KK, IS_MAX, V, walk_rows_bwd(KK), FU><<<grid, block, 0, st>>>( \
+#define DSK_WB(KK, FU) pool_walk_bwd_kernel<T, KK, IS_MAX, V, walk_rows_bwd(KK, V), FU><<<grid, block, 0, st>>>( \
         (const T *)dy, am, (T *)dx, (const T *)yprev, part, act, s)
     if (k == 2 && fuse) DSK_WB(2, true);
     else if (k == 2) DSK_WB(2, false);
@@ -584,8 +597,8 @@ int launch_pool_walk_bwd(const void *dy, const uint8_t *am, void *dx, const void
     if (t == DSK_F32)
         return is_max ? walk_bwd<float, true, 4>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st)
                       : walk_bwd<float, false, 4>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st);
-    return is_max ? walk_bwd<bf16, true, 4>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st)
-                  : walk_bwd<bf16, false, 4>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st);
+    return is_max ? walk_bwd<bf16, true, 8>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st)
+                  : walk_bwd<bf16, false, 8>(dy, am, dx, yprev, db, act, ws, N, C, H, W, k, d, st);
 }
 
 } // namespace dsk

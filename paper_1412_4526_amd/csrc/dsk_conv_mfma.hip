@@ -206,7 +206,9 @@ __device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][NR
 //
 // NR, NH: shape of the tiles of rectangle g (4*NR rows by 32*NH columns); a wave owns rows NR*wave .. NR*wave+NR-1
 // of the tile and all its columns.  wg: the logical workgroup (persistent ones: of the launch; else: of g).
-template <typename TI, typename TO, int WM, int XI, int WI, bool SPLIT, int NR, int NH>
+// KW: taps per kernel row when known at compile time (0: p.kw), so that the row of taps is unrolled and the LDS
+// reads of the next tap are issued under the matrix instructions of the current one.
+template <typename TI, typename TO, int WM, int XI, int WI, bool SPLIT, int NR, int NH, int KW = 0>
 __device__ __forceinline__ void gc_body(const GcParams &p, const GcRegion &g, const long wg, float *smem)
 {
     constexpr int TF = WM * 32;
@@ -348,19 +350,25 @@ __device__ __forceinline__ void gc_body(const GcParams &p, const GcRegion &g, co
             for (int cp = 0; cp < p.Cc; cp += 2) {
                 const float *xb = xlane + cp * g.chan_stride;
                 const float *wb = wlane + cp * taps * TF;
+                auto tap = [&](int ta, int tb, int kw) __attribute__((always_inline)) {
+                    const int xo = ta * g.cols + tb * p.d, wo = (ta * kw + tb) * TF;
+                    float A[WM], B[NR * NH];
+#pragma unroll
+                    for (int wm = 0; wm < WM; ++wm) A[wm] = wb[wo + wm * 32];
+#pragma unroll
+                    for (int wn = 0; wn < NR * NH; ++wn) B[wn] = xb[xo + (wn / NH) * g.cols + (wn % NH) * 32];
+#pragma unroll
+                    for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                        for (int wn = 0; wn < NR * NH; ++wn)
+                            acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
+                };
                 for (int ta = 0; ta < p.kh; ++ta) {
-                    for (int tb = 0; tb < p.kw; ++tb) {
-                        const int xo = ta * g.cols + tb * p.d, wo = (ta * p.kw + tb) * TF;
-                        float A[WM], B[NR * NH];
+                    if constexpr (KW > 0) {
 #pragma unroll
-                        for (int wm = 0; wm < WM; ++wm) A[wm] = wb[wo + wm * 32];
-#pragma unroll
-                        for (int wn = 0; wn < NR * NH; ++wn) B[wn] = xb[xo + (wn / NH) * g.cols + (wn % NH) * 32];
-#pragma unroll
-                        for (int wm = 0; wm < WM; ++wm)
-#pragma unroll
-                            for (int wn = 0; wn < NR * NH; ++wn)
-                                acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
+                        for (int tb = 0; tb < KW; ++tb) tap(ta, tb, KW);
+                    } else {
+                        for (int tb = 0; tb < p.kw; ++tb) tap(ta, tb, p.kw);
                     }
                 }
             }
@@ -390,7 +398,7 @@ __device__ __forceinline__ void gc_body(const GcParams &p, const GcRegion &g, co
 
 // HALF: the launch may hold rectangles with tiles of half the height or width (instances for them exist only
 // where the host uses them: one tile per workgroup, ordinary halos).
-template <typename TI, typename TO, int WM, int XI, int WI, bool SPLIT, bool HALF>
+template <typename TI, typename TO, int WM, int XI, int WI, bool SPLIT, bool HALF, int KW = 0>
 __global__ void __launch_bounds__(kThreads, 2)
 gemm_conv_kernel(GcParams p)
 {
@@ -400,7 +408,7 @@ gemm_conv_kernel(GcParams p)
     if constexpr (SPLIT) {
         const long wg = (long)(blockIdx.x % kXcds) * p.per_xcd + blockIdx.x / kXcds;
         if (wg >= p.n_wg) return;
-        gc_body<TI, TO, WM, XI, WI, true, 2, 2>(p, p.reg[0], wg, smem);
+        gc_body<TI, TO, WM, XI, WI, true, 2, 2, KW>(p, p.reg[0], wg, smem);
     } else {
         // the rectangles follow each other in the grid, each with its own XCD-aware order
         int r = 0;
@@ -412,12 +420,12 @@ gemm_conv_kernel(GcParams p)
         const long wg = (local % kXcds) * g.per_xcd + local / kXcds;
         if (wg >= g.tiles) return;
         if constexpr (HALF) {
-            if (g.nr == 2 && g.nh == 2) gc_body<TI, TO, WM, XI, WI, false, 2, 2>(p, g, wg, smem);
+            if (g.nr == 2 && g.nh == 2) gc_body<TI, TO, WM, XI, WI, false, 2, 2, KW>(p, g, wg, smem);
             else if (g.nr == 2) gc_body<TI, TO, WM, XI, WI, false, 2, 1>(p, g, wg, smem);
             else if (g.nh == 2) gc_body<TI, TO, WM, XI, WI, false, 1, 2>(p, g, wg, smem);
             else gc_body<TI, TO, WM, XI, WI, false, 1, 1>(p, g, wg, smem);
         } else {
-            gc_body<TI, TO, WM, XI, WI, false, 2, 2>(p, g, wg, smem);
+            gc_body<TI, TO, WM, XI, WI, false, 2, 2, KW>(p, g, wg, smem);
         }
     }
 }
@@ -662,6 +670,16 @@ static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
         gemm_conv_kernel<TI, TO, 1, kXIBig, kWI, false, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.WM == 2 && g.split)
         gemm_conv_kernel<TI, TO, 2, kXI, kWI, true, false><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    // the 64-filter kernels for 4 and 5 taps per row have the row unrolled at compile time (1-2 % faster; every
+    // further width costs half a minute of compile time)
+#define DSK_GC_KW(KW_)                                                                                                   \
+    else if (g.WM == 2 && g.half && p.kw == KW_)                                                                         \
+        gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, true, KW_><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);   \
+    else if (g.WM == 2 && p.kw == KW_)                                                                                   \
+        gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, false, KW_><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    DSK_GC_KW(4)
+    DSK_GC_KW(5)
+#undef DSK_GC_KW
     else if (g.WM == 2 && g.half)
         gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.WM == 2)

@@ -258,11 +258,34 @@ __device__ __forceinline__ void gc_body(const GcParams &p, const GcRegion &g, co
         // is read at voff[i] floats beyond the first channel of the chunk.  Elements outside
         // the map, or in the padding, are read from offset 0 instead, which is always a valid
         // address, and bit i of `zero` says that the tile gets 0 there.
+        // Where no zeroing is needed when the tile is written to LDS (uniform).  Forward: a tile entry outside the
+        // map only feeds outputs outside the output map, which are not stored.  Backward-data: tiles that lie wholly
+        // inside the error map.  (Channels beyond Cin meet zero weights, and the padding at the end of the LDS tile
+        // is never read.)
+        const bool no_zeroing = (p.off_h == 0 && p.off_w == 0) ||
+                                (u0 - p.off_h >= 0 && u0 - p.off_h + (g.rows - 1) * p.d < p.Hin &&
+                                 v0 - p.off_w >= 0 && v0 - p.off_w + g.cols <= p.Win);
+        // QUAD (fp32 maps, tiles a multiple of four columns wide, whole chunks, no zeroing): a thread stages FOUR
+        // neighbouring columns per load (16 bytes, any alignment) and LDS write instead of one -- the vector memory
+        // path spends as long on a wave's 4-byte loads as on its 16-byte ones.  Item tid + 256*i holds elements
+        // 4*item .. 4*item+3 of the tile; columns beyond the map read what follows in memory (finite values of the
+        // map, or zero beyond the tensor), which only feed outputs that are not stored.
+        constexpr bool QUADX = sizeof(TI) == 4 && XI % 4 == 0;
+        const bool quad = QUADX && no_zeroing && g.cols % 4 == 0 && p.Cpad == p.Cin && (!p.gsize || p.gsize % p.Cc == 0);
         unsigned voff[XI];
         unsigned zero = 0;
         {
             const int n_x = p.Cc * g.chan_stride;
             const int row0 = u0 - p.off_h, col0 = v0 - p.off_w;
+            if (quad) {
+#pragma unroll
+                for (int i = 0; i < XI / 4; ++i) {
+                    const int e = 4 * (tid + i * kThreads);
+                    const int c = (int)__umulhi((unsigned)e, g.m_cs), rem = e - c * g.chan_stride;
+                    const int r = (int)__umulhi((unsigned)rem, g.m_cols), col = rem - r * g.cols;
+                    voff[i] = e < n_x ? (unsigned)c * HW + (unsigned)((row0 + r * p.d) * p.Win + col0 + col) : 0u;
+                }
+            } else {
 #pragma unroll
             for (int i = 0; i < XI; ++i) {
                 const int e = tid + i * kThreads;
@@ -274,15 +297,8 @@ __device__ __forceinline__ void gc_body(const GcParams &p, const GcRegion &g, co
                 voff[i] = ok ? (unsigned)c * HW + (unsigned)(irow * p.Win + icol) : 0u;
                 zero |= ok ? 0u : 1u << i;
             }
+            }
         }
-
-        // Where no zeroing is needed when the tile is written to LDS (uniform).  Forward: a tile entry outside the
-        // map (read from offset 0 instead: a finite value of the map) only feeds outputs outside the output map,
-        // which are not stored.  Backward-data: tiles that lie wholly inside the error map.  (Channels beyond Cin
-        // meet zero weights, and the padding at the end of the LDS tile is never read.)
-        const bool no_zeroing = (p.off_h == 0 && p.off_w == 0) ||
-                                (u0 - p.off_h >= 0 && u0 - p.off_h + (g.rows - 1) * p.d < p.Hin &&
-                                 v0 - p.off_w >= 0 && v0 - p.off_w + g.cols <= p.Win);
 
         f32x16 acc[WM][NR * NH];
 #pragma unroll
@@ -300,7 +316,14 @@ __device__ __forceinline__ void gc_body(const GcParams &p, const GcRegion &g, co
             const int g0 = p.gsize ? c0 / p.gsize : 0;      // the channel group the chunk begins in
             const TI *src = in_n + (long)c0 * (long)HW + g0 * p.gjump;
             const BufRsrc rx = buf_rsrc(src, in_end);
-            if (c0 + p.Cc <= p.Cin && (!p.gsize || c0 - g0 * p.gsize + p.Cc <= p.gsize)) {
+            if (QUADX && quad) {
+#pragma unroll
+                for (int i = 0; i < XI / 4; ++i) {
+                    const f32x4 q = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(voff[i] * 4u), 0, 0));
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) xv[4 * i + j] = q[j];
+                }
+            } else if (c0 + p.Cc <= p.Cin && (!p.gsize || c0 - g0 * p.gsize + p.Cc <= p.gsize)) {
 #pragma unroll
                 for (int i = 0; i < XI; ++i) xv[i] = buf_ld(rx, src, voff[i], 0u);
             } else {
@@ -331,7 +354,14 @@ __device__ __forceinline__ void gc_body(const GcParams &p, const GcRegion &g, co
         fetch(cb * p.Cc);
         for (int ch = cb; ch < ce; ++ch) {
             __syncthreads();      // every wave is done reading the previous chunk
-            if (no_zeroing) {
+            if (QUADX && quad) {
+#pragma unroll
+                for (int i = 0; i < XI / 4; ++i)
+                    if (4 * (tid + i * kThreads) < p.xs_floats) {      // (the LDS part of the tile ends there)
+                        const f32x4 q = {xv[4 * i], xv[4 * i + 1], xv[4 * i + 2], xv[4 * i + 3]};
+                        ((f32x4 *)xs)[tid + i * kThreads] = q;
+                    }
+            } else if (no_zeroing) {
 #pragma unroll
                 for (int i = 0; i < XI; ++i)
                     if (i < g.n_xi) xs[tid + i * kThreads] = xv[i];

@@ -5,12 +5,17 @@
 // Same decomposition as the fp32 kernel: a workgroup owns TH=8 output rows of one residue
 // class modulo d, TW=64 columns and 32 or 64 filters; the LDS tile has TH+kh-1 rows whatever d
 // is.  What differs is the k index.  One matrix instruction contracts 16 values, here the 16
-// channels of a chunk at one tap, and a lane supplies 8 consecutive ones.  The LDS tile is
-// therefore pixel-major, [row][column][16 channels] (32 bytes per pixel), so that a lane's 8
-// channels are one 16-byte read, and the weights are [tap][filter][16 channels].  The maps stay
-// NCHW in HBM: the tile is transposed while it is staged.  A thread stages "items" = (pixel,
-// half of the 16 channels): eight 2-byte loads, one from each channel plane, which for the
-// lanes of a wave are consecutive pixels of a row (coalesced), packed into one 16-byte LDS write.
+// channels of a chunk at one tap, and a lane supplies 8 consecutive ones (16 bytes).  The LDS
+// tile is therefore [channel half][row][column][8 channels] and the weights are
+// [tap][channel half][filter][8 channels]: the 32 lanes of a half-wave read 32 consecutive
+// 16-byte pieces (no bank conflicts).  The maps stay NCHW in HBM: the tile is transposed while
+// it is staged.  A thread stages "items" = (four neighbouring pixels, half of the 16 channels):
+// eight 8-byte loads, one from each channel plane, turned into four 16-byte LDS writes (one per
+// pixel) by sixteen byte permutes.
+//
+// A wave owns FOUR rows of the tile and one 32-column block.  Tap row ta of tile row j reads LDS
+// row j+ta, so the operands of LDS row r serve every (j, ta) with j+ta = r: kh+3 operand reads
+// per tap column feed 4*kh matrix instructions per 32 filters.
 #include "dsk_internal.h"
 
 namespace dsk {
@@ -19,24 +24,27 @@ static constexpr int kThreads = 256;
 static constexpr int kXcds = 8;
 static constexpr int TH = 8, TW = 64, CK = 16;
 static constexpr int kItems = 8;        // (pixel, channel half) items per thread per chunk, at most
-static constexpr int kItemsPair = 4;    // (pixel pair, channel half) items per thread per chunk, at most
 static constexpr int kWq = 8;           // 16-byte pieces of the chunk's weights per thread, at most
 static constexpr size_t kMaxLds = 64 * 1024;
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 struct GbParams {
     const bf16 *in;
     void *out;
-    const bf16 *wt;      // [n_fgrp][NC][taps][TF][16], zero padded
+    const bf16 *wt;      // [n_fgrp][NC][taps][2][TF][8], zero padded
     const float *bias;   // may be null
     int N, Cin, Hin, Win, Fout, Hout, Wout;
     int kh, kw, d, off_h, off_w, act;
+    int zero_fill;       // pixels outside the map count as zeros (backward-data); else they only feed outputs that are not stored
     int NC;              // chunks of 16 channels
-    int rows, cols, n_pix;   // LDS tile: TH+kh-1 by TW+(kw-1)*d pixels; n_pix: pixels (or pixel pairs) staged per channel half
-    int pp_row;          // pixel pairs per tile row (pair form)
+    int rows, cols;      // tile: TH+kh-1 rows by TW+(kw-1)*d columns
+    int cols_p;          // LDS row pitch in pixels
+    int gpr;             // groups of four pixels per tile row (quad form)
+    int n_pix;           // items per channel half: pixels, or groups of four
     int n_items, n_wq;   // per thread and chunk: items, 16-byte weight pieces (LDS parts padded accordingly)
     int xs_bytes;
     int n_rowtile, n_coltile, n_fgrp;
@@ -44,8 +52,8 @@ struct GbParams {
     long tiles, per_xcd;
 };
 
-// wt[g][ch][t][fl][cc] = w[g*TF+fl][ch*16+cc][t]                (forward)
-//                      = w[ch*16+cc][g*TF+fl][taps-1-t]         (backward-data: roles swapped, taps reversed)
+// wt[g][ch][t][h][fl][cc] = w[g*TF+fl][ch*16+8*h+cc][t]                (forward)
+//                         = w[ch*16+8*h+cc][g*TF+fl][taps-1-t]         (backward-data: roles swapped, taps reversed)
 __global__ void __launch_bounds__(kThreads)
 gb_weight_prep_kernel(const float *__restrict__ w, bf16 *__restrict__ wt, int K, int C, int taps, int NC, int TF,
                       int n_fgrp, int flip)
@@ -53,12 +61,13 @@ gb_weight_prep_kernel(const float *__restrict__ w, bf16 *__restrict__ wt, int K,
     const long total = (long)n_fgrp * NC * taps * TF * CK;
     const long idx = (long)blockIdx.x * kThreads + threadIdx.x;
     if (idx >= total) return;
-    const int cc = (int)(idx % CK);
-    const int fl = (int)((idx / CK) % TF);
+    const int cc = (int)(idx % 8);
+    const int fl = (int)((idx / 8) % TF);
+    const int h = (int)((idx / (8L * TF)) % 2);
     const int t = (int)((idx / ((long)CK * TF)) % taps);
     const int ch = (int)((idx / ((long)CK * TF * taps)) % NC);
     const int g = (int)(idx / ((long)CK * TF * taps * NC));
-    const int f = g * TF + fl, c = ch * CK + cc;
+    const int f = g * TF + fl, c = ch * CK + 8 * h + cc;
     float v = 0.f;
     if (!flip) {
         if (f < K && c < C) v = w[((long)f * C + c) * taps + t];
@@ -68,18 +77,21 @@ gb_weight_prep_kernel(const float *__restrict__ w, bf16 *__restrict__ wt, int K,
     wt[idx] = f32_to_bf16(v);
 }
 
-// PAIR (maps with an even number of columns): an item is (pixel PAIR, channel half).  Every row of
-// a plane then starts at an even element, so two neighbouring pixels starting at an even column
-// are one aligned 4-byte load: half as many loads and staging registers, and the two pixels are
-// separated when they are packed for LDS.
-template <typename TO, int WM, bool PAIR>
+// QN > 0 (maps with an even number of columns): an item is four neighbouring pixels whose first
+// lies at a map column that is a multiple of four, for one channel half; QN such items per thread
+// at most.  Every row of a plane starts at an even element, so the 8-byte load is 4-byte aligned.
+// Tile column c lies at LDS column c + par, where par = (first map column of the tile) mod 4.
+// QN = 0: single pixels, 2-byte loads.
+// KH > 0: the kernel has KH tap rows (compile time, operands shared between tap rows as described
+// at the top); KH = 0: any number, four operand reads per tap.
+template <typename TO, int WM, int QN, int KH>
 __global__ void __launch_bounds__(kThreads, 2)
 gemm_conv_bf16_kernel(GbParams p)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int TF = WM * 32, NI = PAIR ? kItemsPair : kItems;
-    unsigned char *xs = smem;                  // [rows*cols pixels][16 channels] bf16
-    unsigned char *wsm = smem + p.xs_bytes;    // [taps][TF][16 channels] bf16
+    constexpr int TF = WM * 32, NI = QN ? QN : kItems;
+    unsigned char *xs = smem;                  // [2][rows][cols_p] pieces of 8 channels
+    unsigned char *wsm = smem + p.xs_bytes;    // [taps][2][TF] pieces of 8 channels
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -110,72 +122,69 @@ gemm_conv_bf16_kernel(GbParams p)
     const bf16 *in_n = p.in + (long)n * p.Cin * (long)HW;
     const BufRsrc rx = buf_rsrc(in_n, p.in + (long)p.N * p.Cin * (long)HW);
 
-    // Item it = tid + 256*i: channel half g = it / n_pix, pixel it % n_pix of the tile.  voff[i] is
-    // where channel 8*g of the chunk is read for that pixel, relative to the chunk's first
-    // channel; pixels outside the map (and the padding of the item list) read offset 0, which
-    // is a valid address, and bit i of `zero` turns them into zeros at the LDS write.
-    // PAIR: n_pix counts pixel pairs (pp_row per tile row); pair jp of a row is tile columns
-    // 2*jp - par and 2*jp + 1 - par, where par makes the first one an even map column; lpix[i] is
-    // the LDS pixel index of the first (the second follows it) and bits 8+i / 16+i of `zero`
-    // say that the first / second column lies outside the tile and is not written.
+    // Item it = tid + 256*i: channel half g = it / n_pix, item it % n_pix of the tile.  voff[i] is where
+    // channel 8*g of the chunk is read for the item's (first) pixel, relative to the chunk's first channel;
+    // items outside the map (and the padding of the item list) read offset 0, which is a valid address.
+    // lds[i]: byte offset of the item's (first) pixel in the tile.  `zero`: bit 4*i + m says that pixel m of
+    // item i lies outside the map (its value is replaced by zero where the call needs that; quad form), bit 16 + i that
+    // the whole item does, bit 24 + i that the item is padding of the list (not written).
+    const int par = QN ? (v0 - p.off_w) & 3 : 0;
+    const int mc0 = v0 - p.off_w - par;        // map column of LDS column 0
     unsigned voff[NI];
-    int lpix[PAIR ? NI : 1];
+    int lds[NI];
     unsigned zero = 0;
-    const int par = PAIR ? (v0 - p.off_w) & 1 : 0;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int it = tid + i * kThreads;
         const int g = it >= p.n_pix ? 1 : 0, pi = it - g * p.n_pix;
-        if (PAIR) {
-            const int r = pi / p.pp_row, c = 2 * (pi - r * p.pp_row) - par;
-            const int irow = u0 + r * p.d - p.off_h, icol = v0 + c - p.off_w;      // icol is even
-            const bool ok = it < 2 * p.n_pix && irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win;
-            voff[i] = ok ? (unsigned)(8 * g) * HW + (unsigned)(irow * p.Win + icol) : 0u;
-            lpix[i] = r * p.cols + c;
-            zero |= ok ? 0u : 1u << i;
-            zero |= it < 2 * p.n_pix && c >= 0 && c < p.cols ? 0u : 1u << (8 + i);
-            zero |= it < 2 * p.n_pix && c + 1 >= 0 && c + 1 < p.cols ? 0u : 1u << (16 + i);
-        } else {
-            const int r = pi / p.cols, c = pi - r * p.cols;
-            const int irow = u0 + r * p.d - p.off_h, icol = v0 + c - p.off_w;
-            const bool ok = it < 2 * p.n_pix && irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win;
-            voff[i] = ok ? (unsigned)(8 * g) * HW + (unsigned)(irow * p.Win + icol) : 0u;
-            zero |= ok ? 0u : 1u << i;
+        const bool listed = it < 2 * p.n_pix;
+        const int per_row = QN ? p.gpr : p.cols;
+        const int r = pi / per_row, c = (QN ? 4 : 1) * (pi - r * per_row);
+        const int irow = u0 + r * p.d - p.off_h, icol = mc0 + c;
+        const bool ok = listed && irow >= 0 && irow < p.Hin && icol >= 0 && icol < p.Win;
+        voff[i] = ok ? (unsigned)(8 * g) * HW + (unsigned)(irow * p.Win + icol) : 0u;
+        lds[i] = ((g * p.rows + r) * p.cols_p + c) * 16;
+        if (QN) {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) zero |= ok && icol + m < p.Win ? 0u : 1u << (4 * i + m);
         }
+        zero |= ok ? 0u : 1u << (16 + i);
+        zero |= listed ? 0u : 1u << (24 + i);
     }
+    // does any pixel of this tile have to be replaced by zero?  (the same for all threads)
+    const bool masks = p.zero_fill && !(u0 - p.off_h >= 0 && u0 + (p.rows - 1) * p.d - p.off_h < p.Hin && mc0 >= 0 &&
+                                       mc0 + p.cols_p <= p.Win);
 
     f32x16 acc[WM][4];
 #pragma unroll
     for (int wm = 0; wm < WM; ++wm)
 #pragma unroll
-        for (int wn = 0; wn < 4; ++wn)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
+            for (int i = 0; i < 16; ++i) acc[wm][j][i] = 0.f;
 
-    unsigned xr[NI][8];      // one 2-byte value each (PAIR: two, of neighbouring pixels)
+    constexpr int XW = QN ? 2 : 1;
+    unsigned xr[NI][8][XW];      // channel j of the item: four pixels (two words), or one 2-byte value
     u32x4 wv[kWq];
     // Every load is issued unconditionally: a load under a condition would be waited for on the spot.
     auto fetch = [&](int ch) __attribute__((always_inline)) {
         const int c0 = ch * CK;
-        if (c0 + CK <= p.Cin) {
+        const bool whole = c0 + CK <= p.Cin;
 #pragma unroll
-            for (int i = 0; i < NI; ++i)
+        for (int i = 0; i < NI; ++i) {
+            // last chunk of a padded channel count: channels at or beyond Cin meet zero weights; the chunk's
+            // first channel is read instead so that the value is a finite one from inside the tensor
+            const int g8 = tid + i * kThreads >= p.n_pix ? 8 : 0;
+            const unsigned pix = voff[i] - (unsigned)g8 * HW * ((zero >> (16 + i)) & 1u ? 0u : 1u);
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    xr[i][j] = PAIR ? __builtin_amdgcn_raw_buffer_load_b32(rx, (int)(voff[i] * 2u), (int)((unsigned)(c0 + j) * HW * 2u), 0)
-                                    : __builtin_amdgcn_raw_buffer_load_b16(rx, (int)(voff[i] * 2u), (int)((unsigned)(c0 + j) * HW * 2u), 0);
-        } else {
-            // last chunk of a padded channel count: channels at or beyond Cin meet zero weights;
-            // the chunk's first channel is read instead so that the address stays inside the tensor
-#pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                const int g8 = tid + i * kThreads >= p.n_pix ? 8 : 0;
-                const unsigned pix = voff[i] - (unsigned)g8 * HW * ((zero >> i) & 1u ? 0u : 1u);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const unsigned off = c0 + g8 + j < p.Cin ? voff[i] + (unsigned)j * HW : pix;
-                    xr[i][j] = PAIR ? __builtin_amdgcn_raw_buffer_load_b32(rx, (int)(off * 2u), (int)((unsigned)c0 * HW * 2u), 0)
-                                    : __builtin_amdgcn_raw_buffer_load_b16(rx, (int)(off * 2u), (int)((unsigned)c0 * HW * 2u), 0);
+            for (int j = 0; j < 8; ++j) {
+                const unsigned off = whole ? voff[i] : c0 + g8 + j < p.Cin ? voff[i] + (unsigned)j * HW : pix;
+                const int so = (int)((unsigned)(whole ? c0 + j : c0) * HW * 2u);
+                if constexpr (QN) {
+                    const u32x2 q = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(off * 2u), so, 0));
+                    xr[i][j][0] = q[0]; xr[i][j][1] = q[1];
+                } else {
+                    xr[i][j][0] = __builtin_amdgcn_raw_buffer_load_b16(rx, (int)(off * 2u), so, 0);
                 }
             }
         }
@@ -186,42 +195,49 @@ gemm_conv_bf16_kernel(GbParams p)
             wv[q] = __builtin_amdgcn_raw_buffer_load_b128(rw, (q * kThreads + tid) * 16, 0, 0);
     };
 
-    // per-lane LDS byte addresses: B = pixel (row 2*wave, column lo) + 16 bytes for lanes 32..63
-    // (channels 8..15), A = filter lo likewise
-    const unsigned char *xlane = xs + ((2 * wave) * p.cols + lo) * 32 + hi * 16;
-    const unsigned char *wlane = wsm + lo * 32 + hi * 16;
+    // per-lane LDS addresses: B = (channel half hi, row R0, column cb*32 + lo), A = (half hi, filter lo)
+    const int R0 = 4 * (wave >> 1), cb = wave & 1;
+    const unsigned char *xlane = xs + ((hi * p.rows + R0) * p.cols_p + cb * 32 + lo + par) * 16;
+    const unsigned char *wlane = wsm + (hi * TF + lo) * 16;
+    const int rowb = p.cols_p * 16;
 
     fetch(0);
     for (int ch = 0; ch < p.NC; ++ch) {
         __syncthreads();      // every wave is done reading the previous chunk
-        // The loaded halves are packed here, not where they were fetched: packed early (which the
-        // compiler would do to halve the registers they occupy) every pair of loads is waited for
-        // on the spot, and a chunk then costs 32 memory round trips instead of one.
+        // The loaded values are combined here, not where they were fetched: combined early (which the
+        // compiler would do where it saves registers) every load is waited for on the spot, and a chunk
+        // then costs many memory round trips instead of one.
 #pragma unroll
         for (int i = 0; i < NI; ++i)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(xr[i][j]));
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int x = 0; x < XW; ++x) asm volatile("" : "+v"(xr[i][j][x]));
 #pragma unroll
         for (int i = 0; i < NI; ++i)
-            if (i < p.n_items) {
-                const int it = tid + i * kThreads;
-                const int g = it >= p.n_pix ? 1 : 0;
-                const bool z = (zero >> i) & 1u;
-                if (PAIR) {
-                    u32x4 va, vb;      // the low halves belong to the first pixel, the high halves to the second
+            if (i < p.n_items && !((zero >> (24 + i)) & 1u)) {
+                if constexpr (QN) {
+                    u32x4 o[4];      // pixel m: the low / high halves of word m/2 of the eight channels
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const unsigned q0 = xr[i][2 * j], q1 = xr[i][2 * j + 1];
-                        va[j] = z ? 0u : (q0 & 0xffffu) | (q1 << 16);
-                        vb[j] = z ? 0u : (q0 >> 16) | (q1 & 0xffff0000u);
+                    for (int k = 0; k < 4; ++k) {
+                        o[0][k] = __builtin_amdgcn_perm(xr[i][2 * k + 1][0], xr[i][2 * k][0], 0x05040100u);
+                        o[1][k] = __builtin_amdgcn_perm(xr[i][2 * k + 1][0], xr[i][2 * k][0], 0x07060302u);
+                        o[2][k] = __builtin_amdgcn_perm(xr[i][2 * k + 1][1], xr[i][2 * k][1], 0x05040100u);
+                        o[3][k] = __builtin_amdgcn_perm(xr[i][2 * k + 1][1], xr[i][2 * k][1], 0x07060302u);
                     }
-                    if (!((zero >> (8 + i)) & 1u)) *(u32x4 *)(xs + lpix[i] * 32 + g * 16) = va;
-                    if (!((zero >> (16 + i)) & 1u)) *(u32x4 *)(xs + (lpix[i] + 1) * 32 + g * 16) = vb;
+                    if (masks) {
+#pragma unroll
+                        for (int m = 0; m < 4; ++m)
+                            if ((zero >> (4 * i + m)) & 1u) o[m] = u32x4{0u, 0u, 0u, 0u};
+                    }
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) *(u32x4 *)(xs + lds[i] + 16 * m) = o[m];
                 } else {
+                    const bool z = masks && ((zero >> (16 + i)) & 1u);
                     u32x4 v;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) v[j] = z ? 0u : xr[i][2 * j] | (xr[i][2 * j + 1] << 16);
-                    if (it < 2 * p.n_pix) *(u32x4 *)(xs + (it - g * p.n_pix) * 32 + g * 16) = v;
+                    for (int k = 0; k < 4; ++k) v[k] = z ? 0u : xr[i][2 * k][0] | (xr[i][2 * k + 1][0] << 16);
+                    *(u32x4 *)(xs + lds[i]) = v;
                 }
             }
 #pragma unroll
@@ -231,20 +247,42 @@ gemm_conv_bf16_kernel(GbParams p)
         fetch(ch + 1 < p.NC ? ch + 1 : ch);      // in flight while the matrix cores run (the last one is not used)
 
         // ---- matrix cores: one instruction per tap and accumulator tile, k = the chunk's 16 channels
-        for (int ta = 0; ta < p.kh; ++ta) {
-            for (int tb = 0; tb < p.kw; ++tb) {
-                const int xo = (ta * p.cols + tb * p.d) * 32, wo = (ta * p.kw + tb) * TF * 32;
-                bf16x8 A[WM], B[4];
+        for (int tb = 0; tb < p.kw; ++tb) {
+            const unsigned char *xb = xlane + tb * p.d * 16;
+            const unsigned char *wb = wlane + tb * 2 * TF * 16;
+            if constexpr (KH > 0) {
+                bf16x8 A[KH][WM];
 #pragma unroll
-                for (int wm = 0; wm < WM; ++wm) A[wm] = *(const bf16x8 *)(wlane + wo + wm * 32 * 32);
+                for (int ta = 0; ta < KH; ++ta)
 #pragma unroll
-                for (int wn = 0; wn < 4; ++wn)
-                    B[wn] = *(const bf16x8 *)(xlane + xo + ((wn >> 1) * p.cols + (wn & 1) * 32) * 32);
+                    for (int wm = 0; wm < WM; ++wm)
+                        A[ta][wm] = *(const bf16x8 *)(wb + ta * p.kw * 2 * TF * 16 + wm * 32 * 16);
 #pragma unroll
-                for (int wm = 0; wm < WM; ++wm)
+                for (int r = 0; r < KH + 3; ++r) {
+                    const bf16x8 B = *(const bf16x8 *)(xb + r * rowb);
 #pragma unroll
-                    for (int wn = 0; wn < 4; ++wn)
-                        acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
+                    for (int j = 0; j < 4; ++j) {
+                        const int ta = r - j;
+                        if (ta >= 0 && ta < KH) {
+#pragma unroll
+                            for (int wm = 0; wm < WM; ++wm)
+                                acc[wm][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ta < 0 || ta >= KH ? 0 : ta][wm], B, acc[wm][j], 0, 0, 0);
+                        }
+                    }
+                }
+            } else {
+                for (int ta = 0; ta < p.kh; ++ta) {
+                    bf16x8 A[WM], B[4];
+#pragma unroll
+                    for (int wm = 0; wm < WM; ++wm) A[wm] = *(const bf16x8 *)(wb + ta * p.kw * 2 * TF * 16 + wm * 32 * 16);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) B[j] = *(const bf16x8 *)(xb + (ta + j) * rowb);
+#pragma unroll
+                    for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[wm][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[wm], B[j], acc[wm][j], 0, 0, 0);
+                }
             }
         }
     }
@@ -270,9 +308,9 @@ gemm_conv_bf16_kernel(GbParams p)
             for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(bv[wm][i]));
     }
 #pragma unroll
-    for (int wn = 0; wn < 4; ++wn) {
-        const int row = u0 + (2 * wave + (wn >> 1)) * p.d;
-        const int col = v0 + (wn & 1) * 32 + lo;
+    for (int j = 0; j < 4; ++j) {
+        const int row = u0 + (R0 + j) * p.d;
+        const int col = v0 + cb * 32 + lo;
         if (row >= p.Hout || col >= p.Wout) continue;
         TO *o = out_n + (long)row * p.Wout + col + (hi ? 4 * plane : 0);
 #pragma unroll
@@ -280,7 +318,7 @@ gemm_conv_bf16_kernel(GbParams p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int fl = wm * 32 + 8 * (i / 4) + (i % 4);
-                if (fl + 4 * hi < f_left) stf(o, (long)fl * plane, act_apply(p.act, acc[wm][wn][i] + bv[wm][i]));
+                if (fl + 4 * hi < f_left) stf(o, (long)fl * plane, act_apply(p.act, acc[wm][j][i] + bv[wm][i]));
             }
         }
     }
@@ -288,8 +326,7 @@ gemm_conv_bf16_kernel(GbParams p)
 
 struct GbPlan {
     bool ok;
-    int WM, TF, NC, rows, cols, n_pix, pp_row, n_items, n_wq, xs_bytes, n_fgrp, n_rowtile, n_coltile, nrb, full_cls;
-    bool pair;
+    int WM, TF, NC, rows, cols, cols_p, gpr, n_pix, n_items, qn, n_wq, xs_bytes, n_fgrp, n_rowtile, n_coltile, nrb, full_cls;
     long tiles;
     size_t lds_bytes, wt_bytes;
 };
@@ -304,17 +341,23 @@ static GbPlan gb_plan(int N, int Cin, int Win, int Fout, int Hout, int Wout, int
     const long taps = (long)kh * kw;
     if (cols > 4096 || taps > 1024) return g;
     g.cols = (int)cols;
-    g.pair = Win % 2 == 0;
-    g.pp_row = g.cols / 2 + 1;
-    g.n_pix = g.pair ? g.rows * g.pp_row : g.rows * g.cols;
-    g.n_items = (2 * g.n_pix + kThreads - 1) / kThreads;
-    if (g.pair && g.n_items > kItemsPair) {      // too many pairs for the registers set aside: single pixels
-        g.pair = false;
-        g.n_pix = g.rows * g.cols;
-        g.n_items = (2 * g.n_pix + kThreads - 1) / kThreads;
+    // groups of four pixels on the map's four-column grid: the tile begins 0-3 columns into its first group
+    g.gpr = (g.cols + 3 + 3) / 4;
+    g.qn = 0;
+    if (Win % 2 == 0) {
+        const int items = (2 * g.rows * g.gpr + kThreads - 1) / kThreads;
+        g.qn = items <= 2 ? 2 : items <= 4 ? 4 : 0;
     }
-    if (g.n_items > kItems) return g;
-    g.xs_bytes = (g.rows * g.cols * 32 + 255) & ~255;
+    if (g.qn) {
+        g.cols_p = 4 * g.gpr;
+        g.n_pix = g.rows * g.gpr;
+    } else {
+        g.cols_p = g.cols;
+        g.n_pix = g.rows * g.cols;
+    }
+    g.n_items = (2 * g.n_pix + kThreads - 1) / kThreads;
+    if (g.n_items > (g.qn ? g.qn : kItems)) return g;
+    g.xs_bytes = (2 * g.rows * g.cols_p * 16 + 255) & ~255;
     for (int wm = 2; wm >= 1; --wm) {
         if (wm == 2 && Fout <= 32) continue;
         const long wbytes = taps * wm * 32 * CK * 2;
@@ -343,6 +386,25 @@ static GbPlan gb_plan(int N, int Cin, int Win, int Fout, int Hout, int Wout, int
     return g;
 }
 
+template <typename TO, int WM, int QN>
+static void gb_launch_kh(const GbParams &p, unsigned grid, size_t lds, hipStream_t st)
+{
+    switch (p.kh) {
+    case 3: gemm_conv_bf16_kernel<TO, WM, QN, 3><<<dim3(grid), dim3(kThreads), lds, st>>>(p); break;
+    case 4: gemm_conv_bf16_kernel<TO, WM, QN, 4><<<dim3(grid), dim3(kThreads), lds, st>>>(p); break;
+    case 5: gemm_conv_bf16_kernel<TO, WM, QN, 5><<<dim3(grid), dim3(kThreads), lds, st>>>(p); break;
+    default: gemm_conv_bf16_kernel<TO, WM, QN, 0><<<dim3(grid), dim3(kThreads), lds, st>>>(p); break;
+    }
+}
+
+template <typename TO, int WM>
+static void gb_launch_qn(const GbParams &p, int qn, unsigned grid, size_t lds, hipStream_t st)
+{
+    if (qn == 2) gb_launch_kh<TO, WM, 2>(p, grid, lds, st);
+    else if (qn == 4) gb_launch_kh<TO, WM, 4>(p, grid, lds, st);
+    else gb_launch_kh<TO, WM, 0>(p, grid, lds, st);
+}
+
 static int gb_run(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Hin, int Win,
                   int Fout, int Hout, int Wout, int kh, int kw, int d, int off, int act, int flip, int K, int C,
                   dsk_dtype tout, void *ws, hipStream_t st)
@@ -361,7 +423,9 @@ static int gb_run(const void *in, void *out, const float *w, const float *bias, 
     p.N = N; p.Cin = Cin; p.Hin = Hin; p.Win = Win; p.Fout = Fout; p.Hout = Hout; p.Wout = Wout;
     p.kh = kh; p.kw = kw; p.d = d; p.off_h = off ? (kh - 1) * d : 0; p.off_w = off ? (kw - 1) * d : 0;
     p.act = act;
-    p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.n_pix = g.n_pix; p.pp_row = g.pp_row; p.n_items = g.n_items;
+    p.zero_fill = off ? 1 : 0;
+    p.NC = g.NC; p.rows = g.rows; p.cols = g.cols; p.cols_p = g.cols_p; p.gpr = g.gpr; p.n_pix = g.n_pix;
+    p.n_items = g.n_items;
     p.n_wq = g.n_wq;
     p.xs_bytes = g.xs_bytes;
     p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp; p.nrb = g.nrb; p.full_cls = g.full_cls;
@@ -369,19 +433,13 @@ static int gb_run(const void *in, void *out, const float *w, const float *bias, 
     p.per_xcd = (g.tiles + kXcds - 1) / kXcds;
     if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;
     const unsigned grid = (unsigned)(p.per_xcd * kXcds);
-#define DSK_GB_LAUNCH(TO, WM, PAIR) gemm_conv_bf16_kernel<TO, WM, PAIR><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p)
     if (tout == DSK_BF16) {
-        if (g.WM == 2 && g.pair) DSK_GB_LAUNCH(bf16, 2, true);
-        else if (g.WM == 2) DSK_GB_LAUNCH(bf16, 2, false);
-        else if (g.pair) DSK_GB_LAUNCH(bf16, 1, true);
-        else DSK_GB_LAUNCH(bf16, 1, false);
+        if (g.WM == 2) gb_launch_qn<bf16, 2>(p, g.qn, grid, g.lds_bytes, st);
+        else gb_launch_qn<bf16, 1>(p, g.qn, grid, g.lds_bytes, st);
     } else {
-        if (g.WM == 2 && g.pair) DSK_GB_LAUNCH(float, 2, true);
-        else if (g.WM == 2) DSK_GB_LAUNCH(float, 2, false);
-        else if (g.pair) DSK_GB_LAUNCH(float, 1, true);
-        else DSK_GB_LAUNCH(float, 1, false);
+        if (g.WM == 2) gb_launch_qn<float, 2>(p, g.qn, grid, g.lds_bytes, st);
+        else gb_launch_qn<float, 1>(p, g.qn, grid, g.lds_bytes, st);
     }
-#undef DSK_GB_LAUNCH
     return check_launch();
 }
 

@@ -169,23 +169,29 @@ gemm_conv_bf16_kernel(GbParams p)
     // Every load is issued unconditionally: a load under a condition would be waited for on the spot.
     auto fetch = [&](int ch) __attribute__((always_inline)) {
         const int c0 = ch * CK;
-        const bool whole = c0 + CK <= p.Cin;
+        auto load = [&](int i, int j, unsigned off, unsigned plane_off) __attribute__((always_inline)) {
+            if constexpr (QN) {
+                const u32x2 q = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(off * 2u), (int)(plane_off * 2u), 0));
+                xr[i][j][0] = q[0]; xr[i][j][1] = q[1];
+            } else {
+                xr[i][j][0] = __builtin_amdgcn_raw_buffer_load_b16(rx, (int)(off * 2u), (int)(plane_off * 2u), 0);
+            }
+        };
+        if (c0 + CK <= p.Cin) {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) load(i, j, voff[i], (unsigned)(c0 + j) * HW);
+        } else {
             // last chunk of a padded channel count: channels at or beyond Cin meet zero weights; the chunk's
             // first channel is read instead so that the value is a finite one from inside the tensor
-            const int g8 = tid + i * kThreads >= p.n_pix ? 8 : 0;
-            const unsigned pix = voff[i] - (unsigned)g8 * HW * ((zero >> (16 + i)) & 1u ? 0u : 1u);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const unsigned off = whole ? voff[i] : c0 + g8 + j < p.Cin ? voff[i] + (unsigned)j * HW : pix;
-                const int so = (int)((unsigned)(whole ? c0 + j : c0) * HW * 2u);
-                if constexpr (QN) {
-                    const u32x2 q = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rx, (int)(off * 2u), so, 0));
-                    xr[i][j][0] = q[0]; xr[i][j][1] = q[1];
-                } else {
-                    xr[i][j][0] = __builtin_amdgcn_raw_buffer_load_b16(rx, (int)(off * 2u), so, 0);
-                }
+            for (int i = 0; i < NI; ++i) {
+                const int g8 = tid + i * kThreads >= p.n_pix ? 8 : 0;
+                const unsigned pix = voff[i] - (unsigned)g8 * HW * ((zero >> (16 + i)) & 1u ? 0u : 1u);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    load(i, j, c0 + g8 + j < p.Cin ? voff[i] + (unsigned)j * HW : pix, (unsigned)c0 * HW);
             }
         }
         const bf16 *wsrc = p.wt + ((long)fg * p.NC + ch) * taps * TF * CK;
@@ -307,18 +313,23 @@ gemm_conv_bf16_kernel(GbParams p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(bv[wm][i]));
     }
+    // stores through a descriptor of this image's filter block: one scalar offset per filter, no 64-bit
+    // address arithmetic per output
+    const BufRsrc ro = buf_rsrc(out_n, out_n + (long)(f_left < TF ? f_left : TF) * plane);
+    const bool all_f = f_left >= TF;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int row = u0 + (R0 + j) * p.d;
         const int col = v0 + cb * 32 + lo;
         if (row >= p.Hout || col >= p.Wout) continue;
-        TO *o = out_n + (long)row * p.Wout + col + (hi ? 4 * plane : 0);
+        const unsigned o = (unsigned)(row * p.Wout + col) + (hi ? 4u * (unsigned)plane : 0u);
 #pragma unroll
         for (int wm = 0; wm < WM; ++wm) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int fl = wm * 32 + 8 * (i / 4) + (i % 4);
-                if (fl + 4 * hi < f_left) stf(o, (long)fl * plane, act_apply(p.act, acc[wm][j][i] + bv[wm][i]));
+                if (all_f || fl + 4 * hi < f_left)
+                    buf_st(ro, (TO *)nullptr, o, (unsigned)fl * (unsigned)plane, act_apply(p.act, acc[wm][j][i] + bv[wm][i]));
             }
         }
     }

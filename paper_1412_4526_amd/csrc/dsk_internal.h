@@ -23,6 +23,12 @@ __host__ __device__ inline float bf16_to_f32(bf16 h)
 // round-to-nearest-even; NaN stays NaN (quiet)
 __host__ __device__ inline bf16 f32_to_bf16(float f)
 {
+#ifdef __HIP_DEVICE_COMPILE__
+    // the conversion instruction of the matrix-core generation: the same rounding, one instruction
+    bf16 h;
+    h.v = __builtin_bit_cast(uint16_t, (__bf16)f);
+    return h;
+#else
     union { uint32_t u; float f; } c;
     c.f = f;
     bf16 h;
@@ -33,6 +39,7 @@ __host__ __device__ inline bf16 f32_to_bf16(float f)
         h.v = (uint16_t)(c.u >> 16);
     }
     return h;
+#endif
 }
 
 __device__ inline float ldf(const float *p, long i) { return p[i]; }

@@ -1635,6 +1635,7 @@ struct BwPlan {
     bool rowsplit, packb;
     bool fb2;            // two filter blocks per workgroup
     int bfm;             // 8, 4, 2: bf16 tiles in LDS, bf16 matrix cores, tap columns aligned to that many pixels; 0: off
+    bool bf16_cores;     // the kernel of dsk_bww_bf16.hip writes the partial blocks
     int col_passes;      // > 1: one launch per tap column b (a kh x 1 kernel on x shifted by b*d columns)
     int n_part;          // partial blocks the reduce kernel adds up
     long n_ptile;
@@ -1649,6 +1650,15 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     if (taps > 52) return b;
     // few input channels: pack (channel, tap column) pairs into the 32 B-operand columns
     b.packb = allow_packb && s.C <= 4 && s.C * s.kw <= 32 && s.kh >= 2 && s.kh <= 7;
+    if (in == DSK_BF16 && !b.packb && bww_bf16_shape(s, &b.Kp, &b.Cp, &b.S)) {
+        b.bf16_cores = true;
+        b.n_fblk = b.Kp / 32;
+        b.n_cblk = b.Cp / 32;
+        b.n_part = b.S;
+        b.part_bytes = 4 * ((size_t)b.n_part * b.Kp * b.Cp * taps + (size_t)s.K * kBiasSplit);
+        b.ok = true;
+        return b;
+    }
     // bf16 matrix cores: a lane's 8 pixels are read from LDS in pieces as large as the spacing of the
     // tap columns allows (odd spacings and maps of odd width, whose pixel pairs are not aligned
     // 4-byte words, are left to the fp32 path); kernels exist for 3, 4 and 7 accumulator tiles per wave
@@ -1865,7 +1875,11 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
         conv_bwd_weight_mfma_kernel<bf16, TPW, XR, false, PF, false, AL, 2>                              \
             <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                      \
     } while (0)
-        if (b.bfm == 8 && b.fb2 && b.tpw == 5) DSK_BFM2_LAUNCH(5, 6, 8, true);
+        if (b.bf16_cores) {
+            rc = launch_bww_bf16(x, dy, (float *)ws, s, st);
+            if (rc != DSK_OK) return rc;
+        }
+        else if (b.bfm == 8 && b.fb2 && b.tpw == 5) DSK_BFM2_LAUNCH(5, 6, 8, true);
         else if (b.bfm == 4 && b.fb2 && b.tpw == 5) DSK_BFM2_LAUNCH(5, 6, 4, true);
         else if (b.bfm == 2 && b.fb2 && b.tpw == 5) DSK_BFM2_LAUNCH(5, 6, 2, true);
         else if (b.bfm == 8 && b.fb2) DSK_BFM2_LAUNCH(8, 8, 8, false);

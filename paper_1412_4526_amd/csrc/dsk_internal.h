@@ -155,6 +155,11 @@ int launch_conv_fwd_bf16(const void *x, const float *w, const float *b, void *y,
 int launch_conv_bwd_data_bf16(const void *dy, const float *w, void *dx, const ConvShape &s, dsk_dtype out, void *ws,
                               hipStream_t st);
 
+// ---- bf16 matrix-core kernel for the weight gradient on bf16 maps (dsk_bww_bf16.hip): square kernels of 3-5 taps
+// a side; writes partial blocks part[S][kh*kw][Kp][Cp] for the reduce kernel of dsk_conv_mfma.hip
+bool bww_bf16_shape(const ConvShape &s, int *Kp, int *Cp, int *S);
+int launch_bww_bf16(const void *x, const void *dy, float *part, const ConvShape &s, hipStream_t st);
+
 // ---- pooling, padding, activation, loss (dsk_pool.hip, dsk_misc.hip, dsk_loss.hip) ----
 int launch_maxpool_fwd(const void *x, void *y, uint8_t *am, int N, int C, int H, int W, int k, int d,
                        dsk_dtype t, hipStream_t st);

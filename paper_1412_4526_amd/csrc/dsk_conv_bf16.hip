@@ -455,10 +455,13 @@ static int gb_run(const void *in, void *out, const float *w, const float *bias, 
 }
 
 // ---- entry points for the dispatcher (bf16 input maps only)
+// a 1 x 1 kernel has no taps to space: its tiles take neighbouring rows
+static int tap_spacing(const ConvShape &s) { return s.kh == 1 && s.kw == 1 ? 1 : s.d; }
+
 size_t conv_bf16_ws_bytes(int which, const ConvShape &s)
 {
-    const GbPlan g = which == DSK_WS_CONV_FWD ? gb_plan(s.N, s.C, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d)
-                                              : gb_plan(s.N, s.K, s.Wo, s.C, s.H, s.W, s.kh, s.kw, s.d);
+    const GbPlan g = which == DSK_WS_CONV_FWD ? gb_plan(s.N, s.C, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, tap_spacing(s))
+                                              : gb_plan(s.N, s.K, s.Wo, s.C, s.H, s.W, s.kh, s.kw, tap_spacing(s));
     return g.ok ? g.wt_bytes : 0;
 }
 
@@ -467,22 +470,21 @@ bool conv_bf16_supported(int which, const ConvShape &s)
     if ((long)s.H * s.W >= (1L << 28) || (long)s.C * s.H * s.W >= (1L << 30) ||
         (long)s.K * s.Ho * s.Wo >= (1L << 30))
         return false;
-    if (s.kh == 1 && s.kw == 1) return false;      // 1x1 layers have their own kernel
-    if (which == DSK_WS_CONV_FWD) return gb_plan(s.N, s.C, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
-    if (which == DSK_WS_CONV_BWD_DATA) return gb_plan(s.N, s.K, s.Wo, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
+    if (which == DSK_WS_CONV_FWD) return gb_plan(s.N, s.C, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, tap_spacing(s)).ok;
+    if (which == DSK_WS_CONV_BWD_DATA) return gb_plan(s.N, s.K, s.Wo, s.C, s.H, s.W, s.kh, s.kw, tap_spacing(s)).ok;
     return false;
 }
 
 int launch_conv_fwd_bf16(const void *x, const float *w, const float *b, void *y, const ConvShape &s,
                          dsk_dtype out, int act, void *ws, hipStream_t st)
 {
-    return gb_run(x, y, w, b, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d, 0, act, 0, s.K, s.C, out, ws, st);
+    return gb_run(x, y, w, b, s.N, s.C, s.H, s.W, s.K, s.Ho, s.Wo, s.kh, s.kw, tap_spacing(s), 0, act, 0, s.K, s.C, out, ws, st);
 }
 
 int launch_conv_bwd_data_bf16(const void *dy, const float *w, void *dx, const ConvShape &s, dsk_dtype out, void *ws,
                               hipStream_t st)
 {
-    return gb_run(dy, dx, w, nullptr, s.N, s.K, s.Ho, s.Wo, s.C, s.H, s.W, s.kh, s.kw, s.d, 1, DSK_ACT_NONE, 1,
+    return gb_run(dy, dx, w, nullptr, s.N, s.K, s.Ho, s.Wo, s.C, s.H, s.W, s.kh, s.kw, tap_spacing(s), 1, DSK_ACT_NONE, 1,
                   s.K, s.C, out, ws, st);
 }
 

@@ -184,6 +184,11 @@ BF16_CASES = [
     (1, 32, 44, 60, 72, 3, 2, 1),      # three filter blocks, two per workgroup; 4-byte LDS reads
     (1, 16, 60, 110, 40, 3, 18, 0),    # tile too large for four-pixel items: pixel pairs
     (1, 16, 30, 66, 33, 3, 1, 1),      # 66-column tiles: the last group of four is half outside
+    (1, 32, 40, 96, 100, 3, 8, 0),     # weight gradient: four filter blocks per workgroup, 16-byte operand reads
+    (1, 32, 44, 60, 130, 3, 4, 1),     # ... 8-byte operand reads, a last group of two blocks
+    (1, 32, 50, 80, 24, 4, 4, 0),      # 4x4 with one filter block: a tap column per wave
+    (1, 32, 40, 64, 20, 3, 2, 0),      # 3x3 with one filter block: tap columns divided between waves
+    (2, 48, 70, 72, 64, 1, 8, 1),      # 1x1 layer on the bf16 matrix cores (tiles of neighbouring rows)
 ]
 
 

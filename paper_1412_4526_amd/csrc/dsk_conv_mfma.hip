@@ -942,28 +942,12 @@ static int pw_run(const void *in, void *out, const float *w, const float *bias, 
 static constexpr int PH = 4;    // pixel-tile rows (one residue class mod d)
 static constexpr int PW = 32;   // pixel-tile columns
 static constexpr int DY_STRIDE = PH * PW + 1;   // odd: lanes = filters read conflict-free
-static constexpr int DYB = PH * PW + 8;         // bf16 tiles: 272 bytes per filter
 
-// Loads for the tiles of the weight gradient.  RAW (bf16 tiles in LDS): the 16 bits are kept as
-// they are, in the low half of the register, instead of being widened to fp32 and rounded back.
-template <bool RAW>
-__device__ inline float bw_ld(BufRsrc r, const float *p, unsigned lane_off, unsigned uniform_off)
-{
-    return buf_ld(r, p, lane_off, uniform_off);
-}
-template <bool RAW>
-__device__ inline float bw_ld(BufRsrc r, const bf16 *p, unsigned lane_off, unsigned uniform_off)
-{
-    if (!RAW) return buf_ld(r, p, lane_off, uniform_off);
-    return __builtin_bit_cast(float, (unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(
-                                         r, (int)(lane_off * 2u), (int)(uniform_off * 2u), 0));
-}
-template <bool RAW> __device__ inline float bw_ld(const float *p, long i) { return p[i]; }
-template <bool RAW> __device__ inline float bw_ld(const bf16 *p, long i)
-{
-    return RAW ? __builtin_bit_cast(float, (unsigned)p[i].v) : bf16_to_f32(p[i]);
-}
-__device__ inline unsigned short bw_raw16(float v) { return (unsigned short)__builtin_bit_cast(unsigned, v); }
+// loads for the tiles of the weight gradient
+__device__ inline float bw_ld(BufRsrc r, const float *p, unsigned lane_off, unsigned uniform_off) { return buf_ld(r, p, lane_off, uniform_off); }
+__device__ inline float bw_ld(BufRsrc r, const bf16 *p, unsigned lane_off, unsigned uniform_off) { return buf_ld(r, p, lane_off, uniform_off); }
+__device__ inline float bw_ld(const float *p, long i) { return p[i]; }
+__device__ inline float bw_ld(const bf16 *p, long i) { return bf16_to_f32(p[i]); }
 
 struct BwParams {
     const void *x, *dy;
@@ -992,26 +976,17 @@ struct BwParams {
 //   operand are (channel, tap column b) pairs instead of 32 channels, so the accumulator
 //   tiles are indexed by the tap ROW only and a 5x5x3 kernel costs 5 MFMA columns of which
 //   15/32 are useful instead of 25 of which 3/32 are.
-// BFM = 8, 4 or 2 (bf16 maps whose tap columns are a multiple of that many pixels apart; 0: off):
-//   the tiles are kept in LDS as bf16 in the same [filter or channel][row][column] order, and one
-//   v_mfma_f32_32x32x16_bf16 contracts 16 consecutive pixels of a row, of which a lane supplies 8:
-//   one 16-byte LDS read when they are aligned to 8 pixels, else two 8-byte or four 4-byte reads.
-//   The matrix cores then have 1/16 of the work and the kernel runs at the speed of its staging.
 // FB = 2 (3x3 kernels): the workgroup owns TWO 32-filter blocks; waves 0/2 take the first
 //   and waves 1/3 the second, and the two waves of a block divide the taps.  The x tile is then
 //   staged once per 64 filters, and a staged tile feeds 2.2 times as many matrix instructions
 //   as when every wave takes all nine taps of one tile row.
-template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false, int BFM = 0, int FB = 1>
+template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false, int FB = 1>
 __global__ void __launch_bounds__(kThreads, (TPW <= 9 ? 2 : 1))
 conv_bwd_weight_mfma_kernel(BwParams p)
 {
     extern __shared__ __align__(16) float smem[];
     float *dys = smem;                       // [32 * FB filters][DY_STRIDE]
     float *xs = smem + FB * 32 * DY_STRIDE;  // [32 channels][xstride]
-    // the same two tiles as bf16: row pitch of the dy tile DYB, of an x channel p.xstride (both
-    // multiples of 8 elements and an odd number of 16-byte units, which spreads lanes over the banks)
-    unsigned short *dyb = (unsigned short *)smem;
-    unsigned short *xb16 = (unsigned short *)smem + FB * 32 * DYB;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1062,13 +1037,8 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
-    float dr[BFM ? 1 : 16 * FB];         // dy tile share: (filter, row) segments wave*2+hi+8i, column lo
-    float xr[BFM ? 1 : NCI][BFM ? 1 : XR];   // x tile share: channels wave+4*ci, rows r, column lane
-    // BFM: the maps have an even number of columns, so two neighbouring pixels are one aligned
-    // 4-byte load and one 4-byte LDS write.  dy: filter wave+4i, row lane/16, pixel pair lane%16;
-    // x: channel wave+4*ci, row 2k + lane/32, pixel pair lane%32.
-    unsigned drp[BFM ? 8 * FB : 1];
-    unsigned xrp[BFM ? NCI : 1][BFM ? XR / 2 : 1];
+    float dr[16 * FB];       // dy tile share: (filter, row) segments wave*2+hi+8i, column lo
+    float xr[NCI][XR];       // x tile share: channels wave+4*ci, rows r, column lane
 
     // Every tile starts inside both maps (the host enumerates only such tiles), so the tile's
     // base is always a valid address: loads that fall outside the maps are redirected there and
@@ -1090,7 +1060,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     // dy: a wave's load covers two filters (lanes 0-31 / 32-63) x 4 rows x 8 column groups; filter wave*8*FB + 2*i +
     // lane/32.  x: channel wave + 4*ci, items (row, column group) lane and lane + 64 of the xrows * xcols/4.
     // (the kernels that do not prefetch -- 5 x 5 layers -- lose 4 % with it)
-    constexpr bool QUAD = PREFETCH && BFM == 0 && !PACKB && XR >= 8 && sizeof(TI) == 4;
+    constexpr bool QUAD = PREFETCH && !PACKB && XR >= 8 && sizeof(TI) == 4;
     const bool quad = QUAD && p.xcols % 4 == 0 && p.xrows * (p.xcols / 4) <= 128;      // (uniform)
     const int qd_f = lane >> 5, qd_r = (lane & 31) >> 3, qd_g = lane & 7;
     const int qG = p.xcols / 4 > 0 ? p.xcols / 4 : 1;
@@ -1106,36 +1076,6 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         const TI *dyt = dy + (((long)n * p.K + f_base) * p.Ho + u0) * p.Wo + v0;
         const long xn = p.bgroup ? n + (long)(n / p.bgroup) * p.bskip : (long)n;
         const TI *xt = x + ((xn * p.C + cb * 32) * p.H + u0) * p.W + v0 + col_shift;
-        if constexpr (BFM != 0) {
-            st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;
-            st_nr_x = (p.H - u0 + p.d - 1) / p.d;
-            st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
-            const int rl = lane >> 4, jl = lane & 15, xl = lane >> 5, pl = lane & 31;
-            st_dcol_ok = v0 + 2 * jl < p.Wo;
-            st_col_ok = 2 * pl < p.xcols && v0 + 2 * pl + col_shift < p.W;
-            // offsets in elements; rows, filters and channels that do not exist are read from the
-            // tile's first element instead (a valid address) and become zeros at the LDS write
-            const unsigned dlo = st_dcol_ok && rl < st_nr_dy ? (unsigned)rl * dWo + 2u * jl : 0u;
-            const BufRsrc rd = buf_rsrc(dyt, dy_end);
-#pragma unroll
-            for (int i = 0; i < 8 * FB; ++i) {
-                const int f = wave + 4 * i;
-                const unsigned so = f < nf_valid ? (unsigned)f * HoWo : 0u;
-                drp[i] = __builtin_amdgcn_raw_buffer_load_b32(rd, (int)(dlo * 2u), (int)(so * 2u), 0);
-            }
-            const BufRsrc rx = buf_rsrc(xt, x_end);
-#pragma unroll
-            for (int ci = 0; ci < NCI; ++ci) {
-                const int c = wave + 4 * ci;
-#pragma unroll
-                for (int k = 0; k < XR / 2; ++k) {
-                    const unsigned so = c < nc_valid && 2 * k < st_nr_x ? (unsigned)c * HW + (unsigned)(2 * k) * dW : 0u;
-                    const unsigned xo = st_col_ok && 2 * k + xl < st_nr_x ? (unsigned)xl * dW + 2u * pl : 0u;
-                    xrp[ci][k] = __builtin_amdgcn_raw_buffer_load_b32(rx, (int)(xo * 2u), (int)(so * 2u), 0);
-                }
-            }
-            return;
-        }
         // dy: segment i of this wave is filter f_i, rows r_i (lanes 0-31) and r_i+1 (lanes 32-63)
         st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;           // dy rows u0 + r*d that exist (>= 1)
         st_dcol_ok = v0 + lo < p.Wo;
@@ -1182,7 +1122,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
             for (int i = 0; i < 16 * FB; ++i) {
                 const int seg = wave * 2 + 8 * i;
-                dr[i] = bw_ld<BFM != 0>(rd, dyt, dlane_off, (unsigned)(seg >> 2) * HoWo + (unsigned)(seg & 3) * dWo);
+                dr[i] = bw_ld(rd, dyt, dlane_off, (unsigned)(seg >> 2) * HoWo + (unsigned)(seg & 3) * dWo);
             }
             const BufRsrc rx = buf_rsrc(xt, x_end);
 #pragma unroll
@@ -1190,7 +1130,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
                 for (int r = 0; r < XR; ++r) {
                     const int rr = r < p.xrows ? r : 0;      // rows beyond the tile are not staged
-                    xr[ci][r] = bw_ld<BFM != 0>(rx, xt, xlane_off, (unsigned)(wave + 4 * ci) * HW + (unsigned)rr * dW);
+                    xr[ci][r] = bw_ld(rx, xt, xlane_off, (unsigned)(wave + 4 * ci) * HW + (unsigned)rr * dW);
                 }
             }
             return;
@@ -1202,7 +1142,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             const bool ok_s = f < nf_valid && r < st_nr_dy;   // uniform
             const TI *base = ok_s ? dyt + ((unsigned)f * HoWo + (unsigned)r * dWo) : dyt;
             const bool ok = ok_s && st_dcol_ok && r + hi < st_nr_dy;
-            dr[i] = bw_ld<BFM != 0>(base, (long)(ok ? (unsigned)hi * dWo + (unsigned)lo : 0u));
+            dr[i] = bw_ld(base, (long)(ok ? (unsigned)hi * dWo + (unsigned)lo : 0u));
         }
 #pragma unroll
         for (int ci = 0; ci < NCI; ++ci) {
@@ -1211,7 +1151,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             for (int r = 0; r < XR; ++r) {
                 const bool ok_s = c < nc_valid && r < st_nr_x;              // uniform
                 const TI *base = ok_s ? xt + ((unsigned)c * HW + (unsigned)r * dW) : xt;
-                xr[ci][r] = bw_ld<BFM != 0>(base, (long)xlane_off);
+                xr[ci][r] = bw_ld(base, (long)xlane_off);
             }
         }
     };
@@ -1221,27 +1161,6 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     while (pt < p.n_ptile) {
         if (!PREFETCH) load_tile(pt);
         __syncthreads();        // every wave is done with the previous tile
-        if constexpr (BFM != 0) {
-            const int rl = lane >> 4, jl = lane & 15, xl = lane >> 5, pl = lane & 31;
-#pragma unroll
-            for (int i = 0; i < 8 * FB; ++i) {
-                const int f = wave + 4 * i;
-                const bool ok = st_dcol_ok && f < nf_valid && rl < st_nr_dy;
-                *(unsigned *)(dyb + f * DYB + rl * PW + 2 * jl) = ok ? drp[i] : 0u;
-            }
-            if (2 * pl < p.xcols) {
-#pragma unroll
-                for (int ci = 0; ci < NCI; ++ci)
-#pragma unroll
-                    for (int k = 0; k < XR / 2; ++k) {
-                        const int r = 2 * k + xl;
-                        if (r < p.xrows) {
-                            const bool ok = st_col_ok && wave + 4 * ci < nc_valid && r < st_nr_x;
-                            *(unsigned *)(xb16 + (wave + 4 * ci) * p.xstride + r * p.xcols + 2 * pl) = ok ? xrp[ci][k] : 0u;
-                        }
-                    }
-            }
-        } else {
         if (QUAD && st_full && quad) {
 #pragma unroll
             for (int i = 0; i < 4 * FB; ++i) {
@@ -1269,8 +1188,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             for (int i = 0; i < 16 * FB; ++i) {
                 const int seg = wave * 2 + hi + 8 * i;
                 const float v = st_dcol_ok ? dr[i] : 0.f;
-                if (BFM) dyb[(seg >> 2) * DYB + (seg & 3) * PW + lo] = bw_raw16(v);
-                else dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
+                dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
             }
         } else {
 #pragma unroll
@@ -1278,8 +1196,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
                 const int seg = wave * 2 + hi + 8 * i;
                 const bool ok = st_dcol_ok && (seg >> 2) < nf_valid && (seg & 3) < st_nr_dy;
                 const float v = ok ? dr[i] : 0.f;
-                if (BFM) dyb[(seg >> 2) * DYB + (seg & 3) * PW + lo] = bw_raw16(v);
-                else dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
+                dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
             }
         }
         if (lane < p.xcols) {
@@ -1292,46 +1209,13 @@ conv_bwd_weight_mfma_kernel(BwParams p)
                         // finite value of the map) only ever meets dy entries outside ITS map, which are zeros,
                         // and the columns of channels beyond C are never written out.
                         const float v = xr[ci][r];
-                        if (BFM) xb16[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = bw_raw16(v);
-                        else xs[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = v;
+                        xs[(wave + 4 * ci) * p.xstride + r * p.xcols + lane] = v;
                     }
-        }
         }
         }
         __syncthreads();
         if (PREFETCH && pt + p.S < p.n_ptile) load_tile(pt + p.S);      // in flight while the matrix cores run
         pt += p.S;
-        if (BFM) {
-            // ---- bf16 matrix cores: k index = 16 consecutive pixels of a row, 8 per lane
-            const unsigned short *ab = dyb + (my_fb * 32 + lo) * DYB + 8 * hi;
-            const unsigned short *bb = xb16 + blane + 8 * hi;
-            for (int r = ROWSPLIT ? wave : 0; r < (ROWSPLIT ? wave + 1 : PH); ++r) {
-#pragma unroll
-                for (int q = 0; q < PW / 16; ++q) {
-                    const bf16x8 A = *(const bf16x8 *)(ab + r * PW + 16 * q);
-                    bf16x8 B[TPW];
-#pragma unroll
-                    for (int t = 0; t < TPW; ++t) {
-                        const unsigned short *src = bb + boff[t] + r * p.xcols + 16 * q;
-                        if (BFM == 8) {
-                            B[t] = *(const bf16x8 *)src;
-                        } else if (BFM == 4) {
-                            const u32x2 b0 = *(const u32x2 *)src, b1 = *(const u32x2 *)(src + 4);
-                            const u32x4 b = {b0[0], b0[1], b1[0], b1[1]};
-                            B[t] = __builtin_bit_cast(bf16x8, b);
-                        } else {
-                            const unsigned *s32 = (const unsigned *)src;
-                            const u32x4 b = {s32[0], s32[1], s32[2], s32[3]};
-                            B[t] = __builtin_bit_cast(bf16x8, b);
-                        }
-                    }
-#pragma unroll
-                    for (int t = 0; t < TPW; ++t)
-                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B[t], acc[t], 0, 0, 0);
-                }
-            }
-            continue;
-        }
         // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
         // Steps of two pixel pairs (one two-address LDS read per operand).  The operands of step s+1 are read into
         // a second set of registers BEFORE the matrix instructions of step s are issued: with one set, a read could
@@ -1634,7 +1518,6 @@ struct BwPlan {
     int Kp, Cp, xrows, xcols, xstride, n_rowtile, n_coltile, S, n_fblk, n_cblk, tpw;
     bool rowsplit, packb;
     bool fb2;            // two filter blocks per workgroup
-    int bfm;             // 8, 4, 2: bf16 tiles in LDS, bf16 matrix cores, tap columns aligned to that many pixels; 0: off
     bool bf16_cores;     // the kernel of dsk_bww_bf16.hip writes the partial blocks
     int col_passes;      // > 1: one launch per tap column b (a kh x 1 kernel on x shifted by b*d columns)
     int n_part;          // partial blocks the reduce kernel adds up
@@ -1659,15 +1542,9 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
         b.ok = true;
         return b;
     }
-    // bf16 matrix cores: a lane's 8 pixels are read from LDS in pieces as large as the spacing of the
-    // tap columns allows (odd spacings and maps of odd width, whose pixel pairs are not aligned
-    // 4-byte words, are left to the fp32 path); kernels exist for 3, 4 and 7 accumulator tiles per wave
-    b.bfm = 0;
-    if (in == DSK_BF16 && !b.packb && s.kw > 1 && s.d % 2 == 0 && s.W % 2 == 0 && taps > 8 && taps <= 28 && s.kh <= 5)
-        b.bfm = s.d % 8 == 0 ? 8 : s.d % 4 == 0 ? 4 : 2;
-    b.fb2 = !b.packb && (taps == 9 || (b.bfm && taps == 16)) && s.K > 32;
-    b.rowsplit = !b.packb && !b.bfm && !b.fb2 && (taps == 1 || taps == 9);
-    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.fb2 ? (taps == 9 ? 5 : 8) : b.bfm ? (taps <= 12 ? 3 : taps <= 16 ? 4 : 7)
+    b.fb2 = !b.packb && taps == 9 && s.K > 32;
+    b.rowsplit = !b.packb && !b.fb2 && (taps == 1 || taps == 9);
+    b.tpw = b.packb ? 2 : b.rowsplit ? (int)taps : b.fb2 ? 5
           : taps <= 4 ? 1 : taps <= 8 ? 2 : taps <= 16 ? 4 : taps <= 28 ? 7 : 13;
     b.Kp = (s.K + 31) / 32 * 32;
     b.Cp = (s.C + 31) / 32 * 32;
@@ -1682,18 +1559,10 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     b.xcols = (int)xcols;
     b.xstride = (b.xrows * b.xcols) | 1;
     b.lds_bytes = 4 * ((size_t)32 * DY_STRIDE + (size_t)32 * b.xstride);
-    if (b.bfm) {
-        b.xstride = 8 * (((b.xrows * b.xcols + 7) / 8) | 1);
-        b.lds_bytes = 2 * ((size_t)32 * DYB + (size_t)32 * b.xstride);
-    }
     if (b.fb2) {
-        const size_t two = b.bfm ? 2 * ((size_t)64 * DYB + (size_t)32 * b.xstride)
-                                 : 4 * ((size_t)64 * DY_STRIDE + (size_t)32 * b.xstride);
+        const size_t two = 4 * ((size_t)64 * DY_STRIDE + (size_t)32 * b.xstride);
         if (two <= kMaxLdsBw) {
             b.lds_bytes = two;
-        } else if (b.bfm) {
-            b.fb2 = false;
-            b.tpw = taps == 9 ? 3 : 4;
         } else {      // wide tap spacing: back to one block per workgroup, every wave all nine taps of a row
             b.fb2 = false;
             b.rowsplit = true;
@@ -1867,43 +1736,18 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     } while (0)
     int rc = DSK_OK;
     {
-#define DSK_BFM_LAUNCH(TPW, AL)                                                                        \
-    conv_bwd_weight_mfma_kernel<bf16, TPW, 8, false, true, false, AL><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p)
-#define DSK_BFM2_LAUNCH(TPW, XR, AL, PF)                                                                  \
-    do {                                                                                               \
-        allow_lds<&conv_bwd_weight_mfma_kernel<bf16, TPW, XR, false, PF, false, AL, 2>>(b.lds_bytes);     \
-        conv_bwd_weight_mfma_kernel<bf16, TPW, XR, false, PF, false, AL, 2>                              \
-            <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                      \
-    } while (0)
         if (b.bf16_cores) {
             rc = launch_bww_bf16(x, dy, (float *)ws, s, st);
             if (rc != DSK_OK) return rc;
         }
-        else if (b.bfm == 8 && b.fb2 && b.tpw == 5) DSK_BFM2_LAUNCH(5, 6, 8, true);
-        else if (b.bfm == 4 && b.fb2 && b.tpw == 5) DSK_BFM2_LAUNCH(5, 6, 4, true);
-        else if (b.bfm == 2 && b.fb2 && b.tpw == 5) DSK_BFM2_LAUNCH(5, 6, 2, true);
-        else if (b.bfm == 8 && b.fb2) DSK_BFM2_LAUNCH(8, 8, 8, false);
-        else if (b.bfm == 4 && b.fb2) DSK_BFM2_LAUNCH(8, 8, 4, false);
-        else if (b.bfm == 2 && b.fb2) DSK_BFM2_LAUNCH(8, 8, 2, false);
-#undef DSK_BFM2_LAUNCH
-        else if (b.bfm == 8 && b.tpw == 3) DSK_BFM_LAUNCH(3, 8);
-        else if (b.bfm == 8 && b.tpw == 4) DSK_BFM_LAUNCH(4, 8);
-        else if (b.bfm == 8) DSK_BFM_LAUNCH(7, 8);
-        else if (b.bfm == 4 && b.tpw == 3) DSK_BFM_LAUNCH(3, 4);
-        else if (b.bfm == 4 && b.tpw == 4) DSK_BFM_LAUNCH(4, 4);
-        else if (b.bfm == 4) DSK_BFM_LAUNCH(7, 4);
-        else if (b.bfm == 2 && b.tpw == 3) DSK_BFM_LAUNCH(3, 2);
-        else if (b.bfm == 2 && b.tpw == 4) DSK_BFM_LAUNCH(4, 2);
-        else if (b.bfm == 2) DSK_BFM_LAUNCH(7, 2);
-#undef DSK_BFM_LAUNCH
         else if (b.fb2) {
             if (in == DSK_F32) {
-                allow_lds<&conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 0, 2>>(b.lds_bytes);
-                conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 0, 2>
+                allow_lds<&conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 2>>(b.lds_bytes);
+                conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 2>
                     <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
             } else {
-                allow_lds<&conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 0, 2>>(b.lds_bytes);
-                conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 0, 2>
+                allow_lds<&conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 2>>(b.lds_bytes);
+                conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 2>
                     <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
             }
         }

@@ -980,7 +980,11 @@ struct BwParams {
 //   and waves 1/3 the second, and the two waves of a block divide the taps.  The x tile is then
 //   staged once per 64 filters, and a staged tile feeds 2.2 times as many matrix instructions
 //   as when every wave takes all nine taps of one tile row.
-template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false, int FB = 1>
+// SHARED (4*(TPW-1) + 1 taps, e.g. 5x5): divided tap by tap, one wave would have TPW taps and the others
+//   TPW-1, and all would wait for the one (25 taps: 28 taps' time).  The last tap is therefore shared:
+//   every wave takes TPW-1 whole taps and tile row `wave` of the last one, and the four partial tiles of
+//   that tap are added through LDS, in wave order, when the workgroup is done.
+template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false, int FB = 1, bool SHARED = false>
 __global__ void __launch_bounds__(kThreads, (TPW <= 9 ? 2 : 1))
 conv_bwd_weight_mfma_kernel(BwParams p)
 {
@@ -1021,6 +1025,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     for (int t = 0; t < TPW; ++t) {
         int tap = ROWSPLIT ? t : tap0 + tap_step * t;
         tap = tap < taps ? tap : 0;
+        if (SHARED && t == TPW - 1) tap = taps - 1;
         const int a = PACKB ? tap : tap / p.kw;
         boff[t] = a * p.xcols + (PACKB ? 0 : (tap - a * p.kw) * p.d);
     }
@@ -1248,8 +1253,13 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
-                    for (int t = 0; t < TPW; ++t)
+                    for (int t = 0; t < (SHARED ? TPW - 1 : TPW); ++t)
                         acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[st & 1][h], B[st & 1][t][h], acc[t], 0, 0, 0);
+                if (SHARED && r == wave) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        acc[TPW - 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[st & 1][h], B[st & 1][TPW - 1][h], acc[TPW - 1], 0, 0, 0);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -1258,8 +1268,23 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     // ---- partial block out: part[split][tap][f][c]; lane = channel, registers = filters
     const long split = ROWSPLIT ? (long)s * 4 + wave : s;
     float *part = p.part + pass * p.pass_stride + split * p.Kp * p.Cp * taps;
+    if constexpr (SHARED) {
+        // the four partial tiles of the shared tap: through LDS, added in wave order; wave w writes registers 4w..4w+3
+        __syncthreads();      // every wave is done with the last tile
+        float *red = smem;    // [wave][register][lane]
 #pragma unroll
-    for (int t = 0; t < TPW; ++t) {
+        for (int i = 0; i < 16; ++i) red[(wave * 16 + i) * 64 + lane] = acc[TPW - 1][i];
+        __syncthreads();
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+            const int i = 4 * wave + ii;
+            const float v = ((red[i * 64 + lane] + red[(16 + i) * 64 + lane]) + red[(32 + i) * 64 + lane]) + red[(48 + i) * 64 + lane];
+            const int f = f_base + 8 * wave + 4 * hi + ii;
+            part[((long)(taps - 1) * p.Kp + f) * p.Cp + cb * 32 + lo] = v;
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < (SHARED ? TPW - 1 : TPW); ++t) {
         const int tap = ROWSPLIT ? t : tap0 + tap_step * t;
         if (tap >= taps || f_base + my_fb * 32 >= p.Kp) continue;
 #pragma unroll
@@ -1734,6 +1759,18 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
                 <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                  \
         }                                                                                              \
     } while (0)
+#define DSK_BW_LAUNCH_SHARED(TPW, XR)                                                                     \
+    do {                                                                                               \
+        if (in == DSK_F32) {                                                                           \
+            allow_lds<&conv_bwd_weight_mfma_kernel<float, TPW, XR, false, false, false, 1, true>>(b.lds_bytes);  \
+            conv_bwd_weight_mfma_kernel<float, TPW, XR, false, false, false, 1, true>                     \
+                <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                  \
+        } else {                                                                                       \
+            allow_lds<&conv_bwd_weight_mfma_kernel<bf16, TPW, XR, false, false, false, 1, true>>(b.lds_bytes);   \
+            conv_bwd_weight_mfma_kernel<bf16, TPW, XR, false, false, false, 1, true>                      \
+                <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);                                  \
+        }                                                                                              \
+    } while (0)
     int rc = DSK_OK;
     {
         if (b.bf16_cores) {
@@ -1760,7 +1797,9 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
         else if (b.tpw == 2 && b.xrows <= 8) DSK_BW_LAUNCH(2, 8, false, true, false);
         else if (b.tpw == 2) DSK_BW_LAUNCH(2, 10, false, true, false);
         else if (b.tpw == 4) DSK_BW_LAUNCH(4, 8, false, true, false);
+        else if (b.tpw == 7 && taps == 25) DSK_BW_LAUNCH_SHARED(7, 8);
         else if (b.tpw == 7) DSK_BW_LAUNCH(7, 8, false, false, false);
+        else if (taps == 49) DSK_BW_LAUNCH_SHARED(13, 10);
         else DSK_BW_LAUNCH(13, 10, false, false, false);
         rc = check_launch();
         if (rc != DSK_OK) return rc;
@@ -1774,6 +1813,7 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
                 b.col_passes > 1 ? s.kw : 1, p.pass_stride);
     }
 #undef DSK_BW_LAUNCH
+#undef DSK_BW_LAUNCH_SHARED
     rc = check_launch();
     if (rc != DSK_OK || !db) return rc;
     float *bpart = (float *)ws + (size_t)b.n_part * b.Kp * b.Cp * (b.packb ? s.kh : taps) * b.col_passes;

@@ -983,7 +983,8 @@ struct BwParams {
 // SHARED (4*(TPW-1) + 1 taps, e.g. 5x5): divided tap by tap, one wave would have TPW taps and the others
 //   TPW-1, and all would wait for the one (25 taps: 28 taps' time).  The last tap is therefore shared:
 //   every wave takes TPW-1 whole taps and tile row `wave` of the last one, and the four partial tiles of
-//   that tap are added through LDS, in wave order, when the workgroup is done.
+//   that tap are added through LDS, in wave order, when the workgroup is done.  With FB = 2 (nine taps for the
+//   two waves of a block): four whole taps each and two tile rows of the ninth.
 template <typename TI, int TPW, int XR, bool ROWSPLIT, bool PREFETCH, bool PACKB = false, int FB = 1, bool SHARED = false>
 __global__ void __launch_bounds__(kThreads, (TPW <= 9 ? 2 : 1))
 conv_bwd_weight_mfma_kernel(BwParams p)
@@ -1255,7 +1256,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
                     for (int t = 0; t < (SHARED ? TPW - 1 : TPW); ++t)
                         acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[st & 1][h], B[st & 1][t][h], acc[t], 0, 0, 0);
-                if (SHARED && r == wave) {
+                if (SHARED && (FB == 2 ? (r >> 1) == (wave >> 1) : r == wave)) {
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
                         acc[TPW - 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[st & 1][h], B[st & 1][TPW - 1][h], acc[TPW - 1], 0, 0, 0);
@@ -1269,18 +1270,31 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     const long split = ROWSPLIT ? (long)s * 4 + wave : s;
     float *part = p.part + pass * p.pass_stride + split * p.Kp * p.Cp * taps;
     if constexpr (SHARED) {
-        // the four partial tiles of the shared tap: through LDS, added in wave order; wave w writes registers 4w..4w+3
+        // the partial tiles of the shared tap (four of one block, or two of each of two blocks): through LDS, added
+        // in wave order; every wave writes a quarter (half) of the registers of its block's tile
         __syncthreads();      // every wave is done with the last tile
         float *red = smem;    // [wave][register][lane]
 #pragma unroll
         for (int i = 0; i < 16; ++i) red[(wave * 16 + i) * 64 + lane] = acc[TPW - 1][i];
         __syncthreads();
+        if (FB == 2) {
+            if (f_base + my_fb * 32 < p.Kp) {
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) {
-            const int i = 4 * wave + ii;
-            const float v = ((red[i * 64 + lane] + red[(16 + i) * 64 + lane]) + red[(32 + i) * 64 + lane]) + red[(48 + i) * 64 + lane];
-            const int f = f_base + 8 * wave + 4 * hi + ii;
-            part[((long)(taps - 1) * p.Kp + f) * p.Cp + cb * 32 + lo] = v;
+                for (int ii = 0; ii < 8; ++ii) {
+                    const int i = 8 * (wave >> 1) + ii;
+                    const float v = red[(my_fb * 16 + i) * 64 + lane] + red[((my_fb + 2) * 16 + i) * 64 + lane];
+                    const int f = f_base + my_fb * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
+                    part[((long)(taps - 1) * p.Kp + f) * p.Cp + cb * 32 + lo] = v;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) {
+                const int i = 4 * wave + ii;
+                const float v = ((red[i * 64 + lane] + red[(16 + i) * 64 + lane]) + red[(32 + i) * 64 + lane]) + red[(48 + i) * 64 + lane];
+                const int f = f_base + 8 * wave + 4 * hi + ii;
+                part[((long)(taps - 1) * p.Kp + f) * p.Cp + cb * 32 + lo] = v;
+            }
         }
     }
 #pragma unroll
@@ -1779,12 +1793,12 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
         }
         else if (b.fb2) {
             if (in == DSK_F32) {
-                allow_lds<&conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 2>>(b.lds_bytes);
-                conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 2>
+                allow_lds<&conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 2, true>>(b.lds_bytes);
+                conv_bwd_weight_mfma_kernel<float, 5, 8, false, true, false, 2, true>
                     <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
             } else {
-                allow_lds<&conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 2>>(b.lds_bytes);
-                conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 2>
+                allow_lds<&conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 2, true>>(b.lds_bytes);
+                conv_bwd_weight_mfma_kernel<bf16, 5, 8, false, true, false, 2, true>
                     <<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
             }
         }

@@ -1,6 +1,6 @@
 // Weight gradient of a stride-1 convolution with a d-regularly sparse kernel (paper Sec. 4.1:
 // dw[f][c][a][b] = sum over n, u, v of dy[n][f][u][v] * x[n][c][u+a*d][v+b*d]) for bf16 maps on the
-// bf16 matrix cores, square kernels of 3, 4 or 5 taps a side, even tap spacing, maps of even width.
+// bf16 matrix cores, square kernels of 1, 3, 4 or 5 taps a side, even tap spacing, maps of even width.
 //
 // A workgroup owns FB blocks of 32 filters x one block of 32 channels of dw for ALL taps and walks
 // over a 1/S share of the pixel tiles (4 rows of one residue class modulo d x 32 columns); its
@@ -163,6 +163,7 @@ bww_bf16_kernel(BbParams p)
     // ---- the matrix instructions of wave W for one staged tile
     auto multiply = [&]() __attribute__((always_inline)) {
         constexpr int T0 = W * NT / 4, T1 = (W + 1) * NT / 4;
+        if constexpr (T1 > T0) {      // (fewer tiles than waves, 1 x 1 kernels: a wave without tiles only stages)
         constexpr int CG0 = T0 / KH, CG1 = (T1 - 1) / KH;      // its tap columns (filter block * KW + b)
         constexpr int FK0 = CG0 / KW, FK1 = CG1 / KW;          // its filter blocks
         const unsigned short *al = dyb + lo * DYB + 8 * hi;
@@ -200,6 +201,7 @@ bww_bf16_kernel(BbParams p)
                     Bc = Bn;
                 }
             }
+        }
         }
     };
 
@@ -258,7 +260,7 @@ bww_bf16_kernel(BbParams p)
 
 struct BbPlan {
     bool ok;
-    int k, FB, AL, Kp, Cp, xstride, n_rowtile, n_coltile, S, n_fgrp, n_cblk;
+    int k, d, FB, AL, Kp, Cp, xstride, n_rowtile, n_coltile, S, n_fgrp, n_cblk;
     long n_ptile;
     size_t lds_bytes;
 };
@@ -266,19 +268,20 @@ struct BbPlan {
 BbPlan bb_plan(const ConvShape &s)
 {
     BbPlan b{};
-    if (s.kh != s.kw || s.kh < 3 || s.kh > 5) return b;
-    if (s.d % 2 != 0 || s.W % 2 != 0 || s.gsize != 0) return b;
+    if (s.kh != s.kw || !(s.kh == 1 || (s.kh >= 3 && s.kh <= 5))) return b;
+    if ((s.d % 2 != 0 && s.kh > 1) || s.W % 2 != 0 || s.gsize != 0) return b;
     if ((long)s.H * s.W >= (1L << 24)) return b;      // 32-channel block offsets stay below 2^29 elements
     b.k = s.kh;
+    b.d = s.kh == 1 ? 1 : s.d;      // a 1 x 1 kernel has no taps to space: tiles of neighbouring rows
     b.Kp = (s.K + 31) / 32 * 32;
     b.Cp = (s.C + 31) / 32 * 32;
     const int n_fblk = b.Kp / 32;
     b.n_cblk = b.Cp / 32;
     if (PW + (s.kw - 1) * s.d > XC) return b;         // the taps reach beyond the x tile
     b.xstride = (PH + s.kh - 1) * XC + 8;
-    b.AL = s.d % 8 == 0 ? 8 : s.d % 4 == 0 ? 4 : 2;
+    b.AL = s.kh == 1 || s.d % 8 == 0 ? 8 : s.d % 4 == 0 ? 4 : 2;
     // filter blocks per workgroup: as many as give every wave whole tap columns
-    b.FB = s.kh == 5 ? 1 : s.kh == 4 ? (n_fblk >= 2 ? 2 : 1) : (n_fblk >= 3 ? 4 : n_fblk == 2 ? 2 : 1);
+    b.FB = s.kh == 5 ? 1 : s.kh == 4 ? (n_fblk >= 2 ? 2 : 1) : (n_fblk >= 3 ? 4 : n_fblk == 2 ? 2 : 1);      // (1 x 1: a block per wave)
     for (;; b.FB /= 2) {
         b.lds_bytes = 2 * ((size_t)b.FB * 32 * DYB + (size_t)32 * b.xstride);
         // (a thread's dy offsets span 32*FB planes and are taken as 32-bit byte offsets)
@@ -288,9 +291,9 @@ BbPlan bb_plan(const ConvShape &s)
     b.n_fgrp = (n_fblk + b.FB - 1) / b.FB;
     // residue classes of the last row block that start beyond the map hold no pixel: skip them
     {
-        const int nrb = (s.Ho + s.d * PH - 1) / (s.d * PH);
-        const int last = s.Ho - (nrb - 1) * s.d * PH;
-        b.n_rowtile = (nrb - 1) * s.d + (last < s.d ? last : s.d);
+        const int nrb = (s.Ho + b.d * PH - 1) / (b.d * PH);
+        const int last = s.Ho - (nrb - 1) * b.d * PH;
+        b.n_rowtile = (nrb - 1) * b.d + (last < b.d ? last : b.d);
     }
     b.n_coltile = (s.Wo + PW - 1) / PW;
     b.n_ptile = (long)s.N * b.n_rowtile * b.n_coltile;
@@ -328,7 +331,7 @@ int launch_bww_bf16(const void *x, const void *dy, float *part, const ConvShape 
     if (!b.ok) return DSK_ESHAPE;
     BbParams p{};
     p.x = (const bf16 *)x; p.dy = (const bf16 *)dy; p.part = part;
-    p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.Ho = s.Ho; p.Wo = s.Wo; p.d = s.d;
+    p.N = s.N; p.C = s.C; p.H = s.H; p.W = s.W; p.K = s.K; p.Ho = s.Ho; p.Wo = s.Wo; p.d = b.d;
     p.Kp = b.Kp; p.Cp = b.Cp; p.xstride = b.xstride;
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
     p.n_fgrp = b.n_fgrp; p.n_cblk = b.n_cblk;
@@ -340,7 +343,10 @@ int launch_bww_bf16(const void *x, const void *dy, float *part, const ConvShape 
     else if (b.k == 3) bb_launch_al<3, 1>(p, b.AL, grid, b.lds_bytes, st);
     else if (b.k == 4 && b.FB == 2) bb_launch_al<4, 2>(p, b.AL, grid, b.lds_bytes, st);
     else if (b.k == 4) bb_launch_al<4, 1>(p, b.AL, grid, b.lds_bytes, st);
-    else bb_launch_al<5, 1>(p, b.AL, grid, b.lds_bytes, st);
+    else if (b.k == 5) bb_launch_al<5, 1>(p, b.AL, grid, b.lds_bytes, st);
+    else if (b.FB == 4) bww_bf16_kernel<1, 1, 4, 8><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+    else if (b.FB == 2) bww_bf16_kernel<1, 1, 2, 8><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
+    else bww_bf16_kernel<1, 1, 1, 8><<<dim3(grid), dim3(kThreads), b.lds_bytes, st>>>(p);
     return check_launch();
 }
 

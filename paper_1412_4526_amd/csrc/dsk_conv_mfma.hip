@@ -1650,6 +1650,12 @@ static BwPlan bw_plan(const ConvShape &s, dsk_dtype in)
 // ============================================================================
 // a 2-D call: the kernels that know nothing of grouped planes or batch slots may take it
 static bool plain_call(const ConvShape &s) { return s.gsize == 0 && s.bgroup == 0; }
+// the 1 x 1 weight gradient kernel below computes on the fp32 matrix cores; bf16 maps of even width go to the bf16 ones
+static bool pw_bwd_weight_call(const ConvShape &s, dsk_dtype in)
+{
+    int kp, cp, sp;
+    return plain_call(s) && pb_plan(s).ok && !(in == DSK_BF16 && bww_bf16_shape(s, &kp, &cp, &sp));
+}
 
 size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
 {
@@ -1672,7 +1678,7 @@ size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
     }
     if (which == DSK_WS_CONV_BWD_WEIGHT) {
         const PbPlan pb = pb_plan(s);
-        if (pb.ok && plain_call(s)) return pb.part_bytes;
+        if (pw_bwd_weight_call(s, in)) return pb.part_bytes;
         const BwPlan b = bw_plan(s, in);
         return b.ok ? b.part_bytes : 0;
     }
@@ -1693,7 +1699,7 @@ bool conv_mfma_supported(int which, const ConvShape &s, dsk_dtype in, dsk_dtype 
         return (plain_call(s) && pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw).ok) || gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d).ok;
     if (which == DSK_WS_CONV_BWD_DATA)
         return (plain_call(s) && pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw).ok) || gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d).ok;
-    if (which == DSK_WS_CONV_BWD_WEIGHT) return (plain_call(s) && pb_plan(s).ok) || bw_plan(s, in).ok;
+    if (which == DSK_WS_CONV_BWD_WEIGHT) return pw_bwd_weight_call(s, in) || bw_plan(s, in).ok;
     return false;
 }
 
@@ -1718,7 +1724,7 @@ int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const Co
 int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
                                 dsk_dtype in, void *ws, hipStream_t st)
 {
-    if (const PbPlan pb = pb_plan(s); pb.ok && plain_call(s)) {
+    if (const PbPlan pb = pb_plan(s); pw_bwd_weight_call(s, in)) {
         PbParams q{};
         q.x = x; q.dy = dy; q.part = (float *)ws;
         q.N = s.N; q.C = s.C; q.K = s.K; q.Kp = pb.Kp; q.Cp = pb.Cp; q.S = pb.S; q.n_cg = pb.n_cg;

@@ -393,6 +393,7 @@ static GbPlan gb_plan(int N, int Cin, int Win, int Fout, int Hout, int Wout, int
     }
     g.n_coltile = (Wout + TW - 1) / TW;
     g.tiles = (long)N * g.n_rowtile * g.n_coltile * g.n_fgrp;
+    if ((g.tiles + kXcds - 1) / kXcds * kXcds > 0x7fffffffL) return g;      // the grid: such calls take the other kernels
     g.ok = true;
     return g;
 }
@@ -442,7 +443,6 @@ static int gb_run(const void *in, void *out, const float *w, const float *bias, 
     p.n_rowtile = g.n_rowtile; p.n_coltile = g.n_coltile; p.n_fgrp = g.n_fgrp; p.nrb = g.nrb; p.full_cls = g.full_cls;
     p.tiles = g.tiles;
     p.per_xcd = (g.tiles + kXcds - 1) / kXcds;
-    if (p.per_xcd * kXcds > 0x7fffffffL) return DSK_ESHAPE;
     const unsigned grid = (unsigned)(p.per_xcd * kXcds);
     if (tout == DSK_BF16) {
         if (g.WM == 2) gb_launch_qn<bf16, 2>(p, g.qn, grid, g.lds_bytes, st);

@@ -75,7 +75,8 @@ struct GcParams {
     const float *wt;     // [n_fgrp][Cpad][taps][TF], zero padded
     const float *bias;   // may be null
     float *partial;      // split tiles: [2 * n_wg][WM * 64][256] raw accumulators
-    int N, Cin, Hin, Win, Fout, Hout, Wout;
+    int N, Cin, Hin, Win, Fout, Hout, Wout;      // Fout: the filters of this launch (`out` and `bias` begin at its first)
+    int Fimg;            // filter planes per image of `out`
     int kh, kw, d, off_h, off_w, act;
     int Cpad, Cc, NC;    // padded channel count, channels per LDS chunk (even), chunks per tile
     int xs_floats;       // Cc*chan_stride of the largest tile shape rounded up to a multiple of 256
@@ -97,7 +98,7 @@ struct GcParams {
 //                           flip = 1: wt[g][k][t][cl] = w[k][g*TF+cl][taps-1-t]     (backward-data)
 __global__ void __launch_bounds__(kThreads)
 gc_weight_prep_kernel(const float *__restrict__ w, float *__restrict__ wt, int K, int C, int taps,
-                      int Cpad, int TF, int n_fgrp, int flip, int round_bf16)
+                      int Cpad, int TF, int n_fgrp, int flip, int round_bf16, int f0, int f_end)
 {
     const long total = (long)n_fgrp * Cpad * taps * TF;
     const long idx = (long)blockIdx.x * kThreads + threadIdx.x;
@@ -106,13 +107,13 @@ gc_weight_prep_kernel(const float *__restrict__ w, float *__restrict__ wt, int K
     const int t = (int)((idx / TF) % taps);
     const int c = (int)((idx / ((long)TF * taps)) % Cpad);
     const int g = (int)(idx / ((long)TF * taps * Cpad));
-    const int f = g * TF + fl;
+    const int f = f0 + g * TF + fl;      // (a launch may cover the outputs f0 .. f_end-1 only)
     float v = 0.f;
     if (!flip) {
-        if (f < K && c < C) v = w[((long)f * C + c) * taps + t];
+        if (f < f_end && c < C) v = w[((long)f * C + c) * taps + t];
     } else {
         // channel index of the GEMM is the filter k of w, output index is the channel c of w
-        if (f < C && c < K) v = w[((long)c * C + f) * taps + (taps - 1 - t)];
+        if (f < f_end && c < K) v = w[((long)c * C + f) * taps + (taps - 1 - t)];
     }
     wt[idx] = round_bf16 ? bf16_to_f32(f32_to_bf16(v)) : v;
 }
@@ -148,7 +149,7 @@ __device__ inline void gc_epilogue(const GcParams &p, const f32x16 (&acc)[WM][NR
 {
     constexpr int TF = WM * 32;
     const long plane = (long)p.Hout * p.Wout;
-    TO *out_n = (TO *)p.out + ((long)n * p.Fout + (long)fg * TF) * plane;
+    TO *out_n = (TO *)p.out + ((long)n * p.Fimg + (long)fg * TF) * plane;
     const int f_left = p.Fout - fg * TF;      // filters of this group that exist
     // The biases of this lane's filters, fetched together BEFORE the first store.  Loaded where
     // they are used, each load has to be waited for on the spot (it may not pass the stores
@@ -515,7 +516,7 @@ gc_fixup_kernel(GcParams p)
     for (int r = 0; r < kFixRows; ++r) {
         const int i = i0 + r;
         const int f = fg * TF + wm * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
-        if (f < p.Fout) stf(out, (((long)n * p.Fout + f) * p.Hout + row) * p.Wout + col, act_apply(p.act, acc[r] + bv[r]));
+        if (f < p.Fout) stf(out, (((long)n * p.Fimg + f) * p.Hout + row) * p.Wout + col, act_apply(p.act, acc[r] + bv[r]));
     }
 }
 
@@ -729,9 +730,11 @@ static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
     }
 }
 
-static int gc_run(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Hin, int Win,
-                  int Fout, int Hout, int Wout, int kh, int kw, int d, int off, int act, int flip,
-                  int K, int C, dsk_dtype tin, dsk_dtype tout, void *ws, hipStream_t st, const ConvShape &s)
+// One launch for the outputs f0 .. f0+Fout-1 of the Fimg the layer has.
+static int gc_run_part(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Hin, int Win,
+                       int Fout, int Hout, int Wout, int kh, int kw, int d, int off, int act, int flip,
+                       int K, int C, dsk_dtype tin, dsk_dtype tout, void *ws, hipStream_t st, const ConvShape &s, int f0,
+                       int Fimg)
 {
     const GcPlan g = gc_plan(N, Cin, Fout, Hout, Wout, kh, kw, d);
     if (!g.ok) return DSK_ESHAPE;
@@ -741,10 +744,13 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     {
         const long total = (long)g.n_fgrp * g.Cpad * taps * g.TF;
         gc_weight_prep_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
-            w, wt, K, C, taps, g.Cpad, g.TF, g.n_fgrp, flip, tin == DSK_BF16 ? 1 : 0);
+            w, wt, K, C, taps, g.Cpad, g.TF, g.n_fgrp, flip, tin == DSK_BF16 ? 1 : 0, f0, f0 + Fout);
     }
     GcParams p{};
-    p.in = in; p.out = out; p.wt = wt; p.bias = bias;
+    p.in = in; p.wt = wt;
+    p.out = (char *)out + (size_t)f0 * Hout * Wout * (tout == DSK_BF16 ? 2 : 4);
+    p.bias = bias ? bias + f0 : nullptr;
+    p.Fimg = Fimg;
     p.partial = g.split ? (float *)((char *)ws + g.wt_bytes) : nullptr;
     p.N = N; p.Cin = Cin; p.Hin = Hin; p.Win = Win; p.Fout = Fout; p.Hout = Hout; p.Wout = Wout;
     p.kh = kh; p.kw = kw; p.d = d; p.off_h = off ? (kh - 1) * d : 0; p.off_w = off ? (kw - 1) * d : 0;
@@ -764,6 +770,40 @@ static int gc_run(const void *in, void *out, const float *w, const float *bias, 
     else if (tin == DSK_BF16 && tout == DSK_BF16) gc_launch<bf16, bf16>(p, g, st);
     else gc_launch<bf16, float>(p, g, st);
     return check_launch();
+}
+
+// A layer whose filter count leaves at most 32 for the last 64-filter group would compute that group at half use:
+// the whole groups and the last 32 filters then run as two launches, the second with 32-filter tiles.
+static int gc_tail(int Fout) { return Fout > 64 && (Fout - 1) % 64 < 32 ? (Fout - 1) % 64 + 1 : 0; }
+
+static size_t gc_ws_bytes(int N, int Cin, int Fout, int Hout, int Wout, int kh, int kw, int d)
+{
+    const int tail = gc_tail(Fout);
+    if (tail) {
+        const GcPlan a = gc_plan(N, Cin, Fout - tail, Hout, Wout, kh, kw, d), b = gc_plan(N, Cin, tail, Hout, Wout, kh, kw, d);
+        if (a.ok && b.ok) {
+            const size_t wa = a.wt_bytes + a.partial_bytes, wb = b.wt_bytes + b.partial_bytes;
+            return wa > wb ? wa : wb;
+        }
+    }
+    const GcPlan g = gc_plan(N, Cin, Fout, Hout, Wout, kh, kw, d);
+    return g.ok ? g.wt_bytes + g.partial_bytes : 0;
+}
+
+static int gc_run(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Hin, int Win,
+                  int Fout, int Hout, int Wout, int kh, int kw, int d, int off, int act, int flip,
+                  int K, int C, dsk_dtype tin, dsk_dtype tout, void *ws, hipStream_t st, const ConvShape &s)
+{
+    const int tail = gc_tail(Fout);
+    if (tail && gc_plan(N, Cin, Fout - tail, Hout, Wout, kh, kw, d).ok && gc_plan(N, Cin, tail, Hout, Wout, kh, kw, d).ok) {
+        const int rc = gc_run_part(in, out, w, bias, N, Cin, Hin, Win, Fout - tail, Hout, Wout, kh, kw, d, off, act, flip, K, C,
+                                   tin, tout, ws, st, s, 0, Fout);
+        if (rc != DSK_OK) return rc;
+        return gc_run_part(in, out, w, bias, N, Cin, Hin, Win, tail, Hout, Wout, kh, kw, d, off, act, flip, K, C, tin, tout,
+                           ws, st, s, Fout - tail, Fout);
+    }
+    return gc_run_part(in, out, w, bias, N, Cin, Hin, Win, Fout, Hout, Wout, kh, kw, d, off, act, flip, K, C, tin, tout, ws, st,
+                       s, 0, Fout);
 }
 
 // ============================================================================
@@ -920,7 +960,7 @@ static int pw_run(const void *in, void *out, const float *w, const float *bias, 
     float *wt = (float *)ws;
     const long total = (long)g.n_fgrp * g.Cpad * g.TF;
     gc_weight_prep_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
-        w, wt, K, C, 1, g.Cpad, g.TF, g.n_fgrp, flip, tin == DSK_BF16 ? 1 : 0);
+        w, wt, K, C, 1, g.Cpad, g.TF, g.n_fgrp, flip, tin == DSK_BF16 ? 1 : 0, 0, Fout);
     PwParams p{};
     p.in = in; p.out = out; p.wt = wt; p.bias = bias;
     p.N = N; p.Cin = Cin; p.Fout = Fout; p.act = act; p.Cpad = g.Cpad; p.n_fgrp = g.n_fgrp;
@@ -1667,14 +1707,12 @@ size_t conv_ws_bytes(int which, const ConvShape &s, dsk_dtype in)
     if (which == DSK_WS_CONV_FWD) {
         const PwPlan pw = pw_plan(s.C, s.K, (long)s.H * s.W, s.kh, s.kw);
         if (pw.ok && plain_call(s)) return pw.wt_bytes;
-        const GcPlan g = gc_plan(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d);
-        return g.ok ? g.wt_bytes + g.partial_bytes : 0;
+        return gc_ws_bytes(s.N, s.C, s.K, s.Ho, s.Wo, s.kh, s.kw, s.d);
     }
     if (which == DSK_WS_CONV_BWD_DATA) {
         const PwPlan pw = pw_plan(s.K, s.C, (long)s.H * s.W, s.kh, s.kw);
         if (pw.ok && plain_call(s)) return pw.wt_bytes;
-        const GcPlan g = gc_plan(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d);
-        return g.ok ? g.wt_bytes + g.partial_bytes : 0;
+        return gc_ws_bytes(s.N, s.K, s.C, s.H, s.W, s.kh, s.kw, s.d);
     }
     if (which == DSK_WS_CONV_BWD_WEIGHT) {
         const PbPlan pb = pb_plan(s);

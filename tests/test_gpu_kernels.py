@@ -46,6 +46,8 @@ CONV_CASES = [
     (2, 6, 30, 80, 33, 3, 1, 2),       # the same with two images and two filter groups
     (1, 16, 20, 30, 16, 2, 4, 0),      # a map smaller than half a tile both ways: one rectangle of 4 x 32 tiles
     (1, 8, 36, 150, 16, 5, 2, 1),      # only the column strip is narrow forward, only the row strip low backward
+    (1, 96, 40, 70, 80, 3, 2, 1),      # 80 filters forward, 96 backward: the last 16 / 32 run as a launch of 32-filter tiles
+    (2, 65, 30, 64, 130, 4, 2, 0),     # ... a tail of 2 filters forward, of one backward
 ]
 
 

@@ -194,6 +194,46 @@ BF16_CASES = [
 ]
 
 
+def _random_bf16_case(seed):
+    """A small layer drawn from the shapes the bf16 matrix-core kernels branch on: kernel size, tap spacing (odd,
+    2, 4, 8 and their multiples), even and odd widths, channel and filter counts around the 16 / 32 / 64 block sizes,
+    maps that end inside a tile."""
+    r = np.random.default_rng(1000 + seed)
+    k = int(r.choice([1, 3, 3, 4, 4, 5, 5]))
+    d = int(r.choice([1, 2, 2, 3, 4, 4, 6, 8, 8, 12, 16]))
+    if (k - 1) * d > 48: d = 48 // (k - 1)
+    C = int(r.choice([16, 17, 24, 32, 33, 48, 64, 70]))
+    K = int(r.choice([1, 5, 16, 31, 32, 33, 64, 65, 96, 100, 130]))
+    H = (k - 1) * d + int(r.integers(1, 40))
+    W = (k - 1) * d + int(r.integers(1, 80))
+    if seed % 3: W += W % 2      # two in three with even width (the four- and eight-pixel staging)
+    return (int(r.integers(1, 3)), C, H, W, K, k, d, int(r.integers(0, 3)))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_conv_bf16_random_shapes(seed):
+    """The three bf16 calls on a seeded random small layer against the oracle on the rounded inputs."""
+    case = _random_bf16_case(seed)
+    N, C, H, W, K, k, d, act = case
+    _say("conv bf16 random", seed, case)
+    rng = np.random.default_rng(seed)
+    x = bf16_round(rng.uniform(-1, 1, (N, C, H, W))).astype(np.float32)
+    w = bf16_round(rng.standard_normal((K, C, k, k)) * np.sqrt(2.0 / (C * k * k))).astype(np.float32)
+    b = (rng.standard_normal(K) * 0.2).astype(np.float32)
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    dy = bf16_round(rng.standard_normal((N, K, Ho, Wo))).astype(np.float32)
+    xb, gb = _t(x, torch.bfloat16), _t(dy, torch.bfloat16)
+    y = dsk.dsk_conv_fwd(xb, _t(w), _t(b), d, act, out_dtype=torch.float32)
+    dw, db = dsk.dsk_conv_bwd_weight(xb, gb, k, k, d)
+    dx = dsk.dsk_conv_bwd_data(gb, _t(w), d, H, W, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert_close(y, oracle_conv_fwd(x, w, b, d, act), "y")
+    rdw, rdb, rdx = oracle_conv_bwd(x, w, b, d, 0, dy)
+    assert_close(dw, rdw, "dw")
+    assert_close(db, rdb, "db")
+    assert_close(dx, rdx, "dx")
+
+
 @pytest.mark.parametrize("case", BF16_CASES, ids=lambda c: "N%dC%dH%dW%dK%dk%dd%da%d" % c)
 def test_conv_bf16_variant(case):
     """bf16 activations/weights, fp32 accumulate: within 2e-2 of the fp32 oracle on the

@@ -194,6 +194,44 @@ BF16_CASES = [
 ]
 
 
+def _random_f32_case(seed):
+    """A small layer drawn from the shapes the fp32 matrix-core kernels branch on: 1-7 taps a side, any tap spacing,
+    channel counts below and around the chunk sizes, filter counts around the 32 / 64 blocks (a last group of at
+    most 32 filters runs as a second launch), maps that end inside a tile or inside half a tile."""
+    r = np.random.default_rng(2000 + seed)
+    k = int(r.choice([1, 2, 3, 3, 4, 5, 5, 6, 7]))
+    d = int(r.choice([1, 1, 2, 3, 4, 5, 8, 16]))
+    if (k - 1) * d > 96: d = 96 // (k - 1)
+    C = int(r.choice([1, 3, 4, 8, 20, 32, 33, 64, 96, 130]))
+    K = int(r.choice([1, 2, 21, 32, 33, 64, 65, 80, 96, 128, 160]))
+    H = (k - 1) * d + int(r.integers(1, 50))
+    W = (k - 1) * d + int(r.integers(1, 140))
+    return (int(r.integers(1, 3)), C, H, W, K, k, d, int(r.integers(0, 3)))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_conv_f32_random_shapes(seed):
+    """Forward, backward-data and weight gradient on a seeded random small layer against the oracle."""
+    case = _random_f32_case(seed)
+    N, C, H, W, K, k, d, act = case
+    _say("conv f32 random", seed, case)
+    rng = np.random.default_rng(seed)
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = (rng.standard_normal((K, C, k, k)) * np.sqrt(2.0 / (C * k * k))).astype(np.float32)
+    b = (rng.standard_normal(K) * 0.2).astype(np.float32)
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    dy = rng.standard_normal((N, K, Ho, Wo)).astype(np.float32)
+    y = dsk.dsk_conv_fwd(_t(x), _t(w), _t(b), d, act)
+    dw, db = dsk.dsk_conv_bwd_weight(_t(x), _t(dy), k, k, d)
+    dx = dsk.dsk_conv_bwd_data(_t(dy), _t(w), d, H, W)
+    torch.cuda.synchronize()
+    assert_close(y, oracle_conv_fwd(x, w, b, d, act), "y")
+    rdw, rdb, rdx = oracle_conv_bwd(x, w, b, d, 0, dy)
+    assert_close(dw, rdw, "dw")
+    assert_close(db, rdb, "db")
+    assert_close(dx, rdx, "dx")
+
+
 def _random_bf16_case(seed):
     """A small layer drawn from the shapes the bf16 matrix-core kernels branch on: kernel size, tap spacing (odd,
     2, 4, 8 and their multiples), even and odd widths, channel and filter counts around the 16 / 32 / 64 block sizes,

@@ -711,6 +711,11 @@ static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
     DSK_GC_KW(4)
     DSK_GC_KW(5)
 #undef DSK_GC_KW
+    // ... and the 32-filter kernel for 5 taps (the first layer, backward-data into 32 channels)
+    else if (g.WM == 1 && !g.split && g.half && p.kw == 5)
+        gemm_conv_kernel<TI, TO, 1, kXI, kWI, false, true, 5><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    else if (g.WM == 1 && !g.split && p.kw == 5)
+        gemm_conv_kernel<TI, TO, 1, kXI, kWI, false, false, 5><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.WM == 2 && g.half)
         gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.WM == 2)

@@ -708,6 +708,7 @@ static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
         gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, true, KW_><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);   \
     else if (g.WM == 2 && p.kw == KW_)                                                                                   \
         gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, false, KW_><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
+    DSK_GC_KW(3)
     DSK_GC_KW(4)
     DSK_GC_KW(5)
 #undef DSK_GC_KW

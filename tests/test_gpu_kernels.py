@@ -426,6 +426,25 @@ def test_pad_image_and_act_bwd():
         assert_close(gt, ref, "act_bwd %d" % act)
 
 
+def test_bf16_rounding_on_the_device():
+    """The kernels round fp32 to bf16 with the hardware's conversion: nearest, ties to even, as torch does on the CPU
+    -- exact ties both ways, values just off a tie, the largest finite values, signed zeros and infinities."""
+    vals = []
+    for base in (1.0, -1.0, 3.0e38, 1.5e-20, 0.3):
+        u = np.float32(base).view(np.uint32)
+        u0 = np.uint32(u & 0xffff0000)
+        for low in (0x0000, 0x0001, 0x7fff, 0x8000, 0x8001, 0xffff):          # bit 16 clear: a tie goes down
+            vals.append(np.uint32(u0 | low))
+        for low in (0x7fff, 0x8000, 0x8001):                                  # bit 16 set: a tie goes up
+            vals.append(np.uint32(u0 | 0x10000 | low))
+    vals += [np.float32(v).view(np.uint32) for v in (0.0, -0.0, np.inf, -np.inf, 3.3895314e38)]
+    img = np.array(vals, np.uint32).view(np.float32)
+    img = np.resize(img, (1, 1, 8, 8)).astype(np.float32)
+    got = to_np(dsk.dsk_pad_image(_t(img), 0, 0, out_dtype=torch.bfloat16)).astype(np.float32)
+    want = bf16_round(img)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
 @pytest.mark.parametrize("shape", [(2, 5, 12, 20), (1, 3, 9, 7), (1, 40, 64, 96), (2, 4, 50, 66)],
                          ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])

@@ -1500,14 +1500,44 @@ pw_bwd_weight_kernel(PbParams p)
             for (int i = 0; i < 16; ++i) acc[a][j][i] = 0.f;
 
     // staging share of a thread: pixel lo of rows 2*wave + hi + 8*i (x: 32 channel rows, dy: 4*FB filter rows)
+    // QUAD (fp32 maps): four neighbouring pixels of row tid/8 + 32*i with one 16-byte load (x: 8 rows, dy: FB rows) --
+    // what the staging costs is the number of load instructions, and this is a quarter of them.
+    constexpr bool QUAD = sizeof(TI) == 4;
+    const int qrow = tid >> 3, qg = tid & 7;
     float xr[32], dr[4 * FB];
     bool st_q_ok = false;
+    unsigned st_qmask = 0;      // QUAD: bit j: pixel 4*qg + j of the staged tile exists
     auto load_tile = [&](long t) __attribute__((always_inline)) {
         const int n = (int)(t / per_img);
         const unsigned q0 = (unsigned)(t - n * per_img) * kPbQ;
         st_q_ok = q0 + lo < HW;
         const TI *xn = x + ((long)n * p.C + c_base) * p.HW, *dn = dy + (long)n * p.K * p.HW;
         const BufRsrc rx = buf_rsrc(xn, x_end), rd = buf_rsrc(dn, dy_end);
+        if constexpr (QUAD) {
+            // rows that do not exist are read from row 0; a quad that reaches past the plane reads what follows in
+            // memory (zero past the tensor); both are zeroed at the LDS write
+            st_qmask = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) st_qmask |= q0 + 4u * qg + j < HW ? 1u << j : 0u;
+            const unsigned pix = st_qmask ? q0 + 4u * qg : 0u;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = qrow + 32 * i;
+                const unsigned off = c_base + c < p.C ? (unsigned)c * HW + pix : 0u;
+                const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(off * 4u), 0, 0));
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xr[4 * i + j] = v[j];
+            }
+#pragma unroll
+            for (int i = 0; i < FB; ++i) {
+                const int f = qrow + 32 * i;
+                const unsigned off = f < p.K ? (unsigned)f * HW + pix : 0u;
+                const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rd, (int)(off * 4u), 0, 0));
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dr[4 * i + j] = v[j];
+            }
+            return;
+        }
         // rows that do not exist are read from row 0 (a valid address) and zeroed at the LDS write
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
@@ -1527,6 +1557,22 @@ pw_bwd_weight_kernel(PbParams p)
     if (t < p.n_tile) load_tile(t);
     while (t < p.n_tile) {
         __syncthreads();        // every wave is done with the previous tile
+        if constexpr (QUAD) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = qrow + 32 * i;
+                const bool row_ok = c_base + c < p.C;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xs[c * kPbPitch + 4 * qg + j] = row_ok && ((st_qmask >> j) & 1u) ? xr[4 * i + j] : 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < FB; ++i) {
+                const int f = qrow + 32 * i;
+                const bool row_ok = f < p.K;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dys[f * kPbPitch + 4 * qg + j] = row_ok && ((st_qmask >> j) & 1u) ? dr[4 * i + j] : 0.f;
+            }
+        } else {
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
             const int c = 2 * wave + hi + 8 * i;
@@ -1536,6 +1582,7 @@ pw_bwd_weight_kernel(PbParams p)
         for (int i = 0; i < 4 * FB; ++i) {
             const int f = 2 * wave + hi + 8 * i;
             dys[f * kPbPitch + lo] = st_q_ok && f < p.K ? dr[i] : 0.f;
+        }
         }
         __syncthreads();
         t += p.S;

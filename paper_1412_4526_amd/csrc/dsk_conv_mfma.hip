@@ -1712,7 +1712,7 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     b.n_ptile = (long)s.N * b.n_rowtile * b.n_coltile;
     const long blocks = (long)(b.fb2 ? (b.n_fblk + 1) / 2 : b.n_fblk) * b.n_cblk;
     long S = 2048 / blocks;
-    if (S > 256) S = 256;
+    if (S > (blocks == 1 ? 512 : 256)) S = blocks == 1 ? 512 : 256;      // (a single block: enough shares to fill every workgroup slot)
     if (S > b.n_ptile / 4) S = b.n_ptile / 4;
     if (S < 1) S = 1;
     b.S = (int)S;

@@ -394,13 +394,14 @@ __device__ __forceinline__ void gc_body(const GcParams &p, const GcRegion &g, co
                         for (int wn = 0; wn < NR * NH; ++wn)
                             acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[wm], B[wn], acc[wm][wn], 0, 0, 0);
                 };
-                for (int ta = 0; ta < p.kh; ++ta) {
-                    if constexpr (KW > 0) {
+                if constexpr (KW > 0) {      // (square kernels: the host launches these instances for kh = kw only)
+#pragma unroll
+                    for (int ta = 0; ta < KW; ++ta)
 #pragma unroll
                         for (int tb = 0; tb < KW; ++tb) tap(ta, tb, KW);
-                    } else {
+                } else {
+                    for (int ta = 0; ta < p.kh; ++ta)
                         for (int tb = 0; tb < p.kw; ++tb) tap(ta, tb, p.kw);
-                    }
                 }
             }
         }
@@ -704,18 +705,18 @@ static void gc_launch(const GcParams &p, const GcPlan &g, hipStream_t st)
     // the 64-filter kernels for 4 and 5 taps per row have the row unrolled at compile time (1-2 % faster; every
     // further width costs half a minute of compile time)
 #define DSK_GC_KW(KW_)                                                                                                   \
-    else if (g.WM == 2 && g.half && p.kw == KW_)                                                                         \
+    else if (g.WM == 2 && g.half && p.kw == KW_ && p.kh == KW_)                                                                       \
         gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, true, KW_><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);   \
-    else if (g.WM == 2 && p.kw == KW_)                                                                                   \
+    else if (g.WM == 2 && p.kw == KW_ && p.kh == KW_)                                                                                \
         gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, false, KW_><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     DSK_GC_KW(3)
     DSK_GC_KW(4)
     DSK_GC_KW(5)
 #undef DSK_GC_KW
     // ... and the 32-filter kernel for 5 taps (the first layer, backward-data into 32 channels)
-    else if (g.WM == 1 && !g.split && g.half && p.kw == 5)
+    else if (g.WM == 1 && !g.split && g.half && p.kw == 5 && p.kh == 5)
         gemm_conv_kernel<TI, TO, 1, kXI, kWI, false, true, 5><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
-    else if (g.WM == 1 && !g.split && p.kw == 5)
+    else if (g.WM == 1 && !g.split && p.kw == 5 && p.kh == 5)
         gemm_conv_kernel<TI, TO, 1, kXI, kWI, false, false, 5><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);
     else if (g.WM == 2 && g.half)
         gemm_conv_kernel<TI, TO, 2, kXI, kWI, false, true><<<dim3(grid), dim3(kThreads), g.lds_bytes, st>>>(p);

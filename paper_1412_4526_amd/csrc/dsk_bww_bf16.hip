@@ -41,7 +41,8 @@ struct BbParams {
     float *part;         // [split][taps][Kp][Cp]
     int N, C, H, W, K, Ho, Wo, d;
     int Kp, Cp;          // padded to 32
-    int xstride;         // elements per channel of the x tile: (PH+k-1) rows of XC columns and 8 more (an odd number of 16-byte units)
+    int xstride;         // elements per channel of the x tile: (PH+k-1) rows of XC columns and 8 more (an odd number of 16-byte
+                         // units: 16-byte operand reads), or 4 more (an odd number of 8-byte units: 8- and 4-byte reads)
     int n_rowtile, n_coltile;
     long n_ptile;        // N * n_rowtile * n_coltile
     int S;               // split count
@@ -226,7 +227,14 @@ bww_bf16_kernel(BbParams p)
             // meets dy entries outside THEIR map, which are zeros, and the columns of channels beyond C are never
             // written out.
 #pragma unroll
-            for (int j = 0; j < XR; ++j) *(u32x4 *)(xb + xq_lds + j * XC) = xrq[j];
+            for (int j = 0; j < XR; ++j) {
+                if constexpr (AL == 8) {
+                    *(u32x4 *)(xb + xq_lds + j * XC) = xrq[j];
+                } else {      // (the channels are 8-byte aligned only)
+                    *(u32x2 *)(xb + xq_lds + j * XC) = u32x2{xrq[j][0], xrq[j][1]};
+                    *(u32x2 *)(xb + xq_lds + j * XC + 4) = u32x2{xrq[j][2], xrq[j][3]};
+                }
+            }
         }
         __syncthreads();
         if (pt + p.S < p.n_ptile) load_tile(pt + p.S);      // in flight while the matrix cores run
@@ -278,8 +286,9 @@ BbPlan bb_plan(const ConvShape &s)
     const int n_fblk = b.Kp / 32;
     b.n_cblk = b.Cp / 32;
     if (PW + (s.kw - 1) * s.d > XC) return b;         // the taps reach beyond the x tile
-    b.xstride = (PH + s.kh - 1) * XC + 8;
     b.AL = s.kh == 1 || s.d % 8 == 0 ? 8 : s.d % 4 == 0 ? 4 : 2;
+    // narrower operand reads: channels an odd number of 8-byte units apart spread the lanes over twice as many banks
+    b.xstride = (PH + s.kh - 1) * XC + (b.AL == 8 ? 8 : 4);
     // filter blocks per workgroup: as many as give every wave whole tap columns
     b.FB = s.kh == 5 ? 1 : s.kh == 4 ? (n_fblk >= 2 ? 2 : 1) : (n_fblk >= 3 ? 4 : n_fblk == 2 ? 2 : 1);      // (1 x 1: a block per wave)
     for (;; b.FB /= 2) {

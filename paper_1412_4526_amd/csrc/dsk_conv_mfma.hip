@@ -22,6 +22,7 @@ namespace dsk {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
@@ -988,7 +989,7 @@ static int pw_run(const void *in, void *out, const float *w, const float *bias, 
 // ============================================================================
 static constexpr int PH = 4;    // pixel-tile rows (one residue class mod d)
 static constexpr int PW = 32;   // pixel-tile columns
-static constexpr int DY_STRIDE = PH * PW + 1;   // odd: lanes = filters read conflict-free
+static constexpr int DY_STRIDE = PH * PW + 2;   // twice an odd number: lanes = filters read conflict-free, rows are 8-byte aligned
 
 // loads for the tiles of the weight gradient
 __device__ inline float bw_ld(BufRsrc r, const float *p, unsigned lane_off, unsigned uniform_off) { return buf_ld(r, p, lane_off, uniform_off); }
@@ -1218,21 +1219,24 @@ conv_bwd_weight_mfma_kernel(BwParams p)
 #pragma unroll
             for (int i = 0; i < 4 * FB; ++i) {
                 float *dst = dys + (wave * 8 * FB + 2 * i + qd_f) * DY_STRIDE + qd_r * PW + 4 * qd_g;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) dst[j] = (st_dmask >> j) & 1u ? dr[4 * i + j] : 0.f;
+                // (rows of both tiles begin at even words: two 8-byte writes per quad)
+                f32x2 v0 = {(st_dmask >> 0) & 1u ? dr[4 * i] : 0.f, (st_dmask >> 1) & 1u ? dr[4 * i + 1] : 0.f};
+                f32x2 v1 = {(st_dmask >> 2) & 1u ? dr[4 * i + 2] : 0.f, (st_dmask >> 3) & 1u ? dr[4 * i + 3] : 0.f};
+                *(f32x2 *)dst = v0;
+                *(f32x2 *)(dst + 2) = v1;
             }
 #pragma unroll
             for (int ci = 0; ci < NCI; ++ci) {
                 // no zeroing (see below): an x entry outside the map only meets dy entries outside their map
                 if (qx_ok0) {
                     float *d0 = xs + (wave + 4 * ci) * p.xstride + qx_r0 * p.xcols + 4 * qx_g0;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) d0[j] = xr[ci][j];
+                    *(f32x2 *)d0 = f32x2{xr[ci][0], xr[ci][1]};
+                    *(f32x2 *)(d0 + 2) = f32x2{xr[ci][2], xr[ci][3]};
                 }
                 if (qx_ok1) {
                     float *d1 = xs + (wave + 4 * ci) * p.xstride + qx_r1 * p.xcols + 4 * qx_g1;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) d1[j] = xr[ci][4 + j];
+                    *(f32x2 *)d1 = f32x2{xr[ci][4], xr[ci][5]};
+                    *(f32x2 *)(d1 + 2) = f32x2{xr[ci][6], xr[ci][7]};
                 }
             }
         } else {
@@ -1690,7 +1694,9 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     if (xcols > 64 || s.kh > (b.tpw == 13 || b.tpw == 2 || b.packb ? 7 : 5)) return b;
     if ((long)s.H * s.W >= (1L << 24)) return b;         // 32-channel block offsets stay below 2^29 elements
     b.xcols = (int)xcols;
-    b.xstride = (b.xrows * b.xcols) | 1;
+    // twice an odd number of words per channel: lanes = channels read conflict-free, and rows of tiles a multiple of
+    // four columns wide are 8-byte aligned
+    b.xstride = b.xrows * b.xcols + (6 - b.xrows * b.xcols % 4) % 4;
     b.lds_bytes = 4 * ((size_t)32 * DY_STRIDE + (size_t)32 * b.xstride);
     if (b.fb2) {
         const size_t two = 4 * ((size_t)64 * DY_STRIDE + (size_t)32 * b.xstride);

@@ -989,7 +989,7 @@ static int pw_run(const void *in, void *out, const float *w, const float *bias, 
 // ============================================================================
 static constexpr int PH = 4;    // pixel-tile rows (one residue class mod d)
 static constexpr int PW = 32;   // pixel-tile columns
-static constexpr int DY_STRIDE = PH * PW + 2;   // twice an odd number: lanes = filters read conflict-free, rows are 8-byte aligned
+static constexpr int DY_STRIDE = PH * PW + 2;   // the larger of the two pitches of the dy tile (see the kernel)
 
 // loads for the tiles of the weight gradient
 __device__ inline float bw_ld(BufRsrc r, const float *p, unsigned lane_off, unsigned uniform_off) { return buf_ld(r, p, lane_off, uniform_off); }
@@ -1038,8 +1038,13 @@ __global__ void __launch_bounds__(kThreads, (TPW <= 9 ? 2 : 1))
 conv_bwd_weight_mfma_kernel(BwParams p)
 {
     extern __shared__ __align__(16) float smem[];
-    float *dys = smem;                       // [32 * FB filters][DY_STRIDE]
-    float *xs = smem + FB * 32 * DY_STRIDE;  // [32 channels][xstride]
+    // Instances that stage quads (see below) keep both tiles at pitches of twice an odd number of words -- conflict-free
+    // reads with lanes = filters or channels, rows 8-byte aligned; the others at odd pitches (measured: half a percent
+    // faster for them).  The host chooses the channel pitch of the x tile by the same rule.
+    constexpr bool QUAD = PREFETCH && !PACKB && XR >= 8 && sizeof(TI) == 4;
+    constexpr int DYS = QUAD ? PH * PW + 2 : PH * PW + 1;
+    float *dys = smem;                       // [32 * FB filters][DYS]
+    float *xs = smem + FB * 32 * DYS;        // [32 channels][xstride]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1114,7 +1119,6 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     // dy: a wave's load covers two filters (lanes 0-31 / 32-63) x 4 rows x 8 column groups; filter wave*8*FB + 2*i +
     // lane/32.  x: channel wave + 4*ci, items (row, column group) lane and lane + 64 of the xrows * xcols/4.
     // (the kernels that do not prefetch -- 5 x 5 layers -- lose 4 % with it)
-    constexpr bool QUAD = PREFETCH && !PACKB && XR >= 8 && sizeof(TI) == 4;
     const bool quad = QUAD && p.xcols % 4 == 0 && p.xrows * (p.xcols / 4) <= 128;      // (uniform)
     const int qd_f = lane >> 5, qd_r = (lane & 31) >> 3, qd_g = lane & 7;
     const int qG = p.xcols / 4 > 0 ? p.xcols / 4 : 1;
@@ -1218,7 +1222,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         if (QUAD && st_full && quad) {
 #pragma unroll
             for (int i = 0; i < 4 * FB; ++i) {
-                float *dst = dys + (wave * 8 * FB + 2 * i + qd_f) * DY_STRIDE + qd_r * PW + 4 * qd_g;
+                float *dst = dys + (wave * 8 * FB + 2 * i + qd_f) * DYS + qd_r * PW + 4 * qd_g;
                 // (rows of both tiles begin at even words: two 8-byte writes per quad)
                 f32x2 v0 = {(st_dmask >> 0) & 1u ? dr[4 * i] : 0.f, (st_dmask >> 1) & 1u ? dr[4 * i + 1] : 0.f};
                 f32x2 v1 = {(st_dmask >> 2) & 1u ? dr[4 * i + 2] : 0.f, (st_dmask >> 3) & 1u ? dr[4 * i + 3] : 0.f};
@@ -1245,7 +1249,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
             for (int i = 0; i < 16 * FB; ++i) {
                 const int seg = wave * 2 + hi + 8 * i;
                 const float v = st_dcol_ok ? dr[i] : 0.f;
-                dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
+                dys[(seg >> 2) * DYS + (seg & 3) * PW + lo] = v;
             }
         } else {
 #pragma unroll
@@ -1253,7 +1257,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
                 const int seg = wave * 2 + hi + 8 * i;
                 const bool ok = st_dcol_ok && (seg >> 2) < nf_valid && (seg & 3) < st_nr_dy;
                 const float v = ok ? dr[i] : 0.f;
-                dys[(seg >> 2) * DY_STRIDE + (seg & 3) * PW + lo] = v;
+                dys[(seg >> 2) * DYS + (seg & 3) * PW + lo] = v;
             }
         }
         if (lane < p.xcols) {
@@ -1278,7 +1282,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         // a second set of registers BEFORE the matrix instructions of step s are issued: with one set, a read could
         // only be issued after the instructions that use its registers, and its latency would be exposed once per
         // step.  The eight steps of a tile row are unrolled, so that every offset is an immediate.
-        const float *ab = dys + (my_fb * 32 + lo) * DY_STRIDE + hi;
+        const float *ab = dys + (my_fb * 32 + lo) * DYS + hi;
         const float *bb = xs + blane + hi;
         constexpr int NS = PW / 4;      // steps per row
         float A[2][2], B[2][TPW][2];
@@ -1696,7 +1700,10 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     b.xcols = (int)xcols;
     // twice an odd number of words per channel: lanes = channels read conflict-free, and rows of tiles a multiple of
     // four columns wide are 8-byte aligned
-    b.xstride = b.xrows * b.xcols + (6 - b.xrows * b.xcols % 4) % 4;
+    {
+        const bool quads = in == DSK_F32 && !b.packb && (b.fb2 || b.tpw == 2 || b.tpw == 4 || (b.tpw == 1 && !(b.rowsplit && b.xrows <= 4)));
+        b.xstride = quads ? b.xrows * b.xcols + (6 - b.xrows * b.xcols % 4) % 4 : (b.xrows * b.xcols) | 1;
+    }
     b.lds_bytes = 4 * ((size_t)32 * DY_STRIDE + (size_t)32 * b.xstride);
     if (b.fb2) {
         const size_t two = 4 * ((size_t)64 * DY_STRIDE + (size_t)32 * b.xstride);

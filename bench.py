@@ -42,6 +42,8 @@ def layer_costs(net, elem):
             out[("conv_fwd", l)] = dict(flops=fl, bytes=nin * elem + nout * oel + wb)
             out[("conv_bwd_data", l)] = dict(flops=fl, bytes=nout * oel + nin * elem + wb)
             out[("conv_bwd_weight", l)] = dict(flops=fl, bytes=nin * elem + nout * oel + wb)
+            # backward-data with the non-linearity backward of the conv layer below: that layer's output is read too
+            out[("conv_bwd_data_act", l)] = dict(flops=fl, bytes=nout * oel + 2 * nin * elem + wb)
             out[("act_bwd", l)] = dict(flops=0.0, bytes=3 * nout * oel)
         elif p.kind == dsk.DSK_MAXPOOL:
             out[("maxpool_fwd", l)] = dict(flops=0.0, bytes=nin * elem + nout * (elem + 1))

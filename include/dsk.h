@@ -192,6 +192,22 @@ int dsk_pool_bwd_act_bias(int kind, const void *dy, const uint8_t *argmax, const
                           int N, int C, int H, int W, int k, int d, dsk_act act, dsk_dtype t,
                           void *ws, size_t ws_bytes, void *stream);
 
+/* A convolution layer's backward-data fused with the backward of the convolution layer directly below it
+ * (no pool in between, e.g. the two fully connected layers at the top of a network), Sec. 4.1:
+ *   dx[n][c][p][q] = act'(.) * (dsk_conv_bwd_data of dy and w at [n][c][p][q])   act' through x
+ *   db[c]          = sum_{n,p,q} dx[n][c][p][q]   of the values as stored (fp32, fixed order)
+ * x[N][C][H][W] is this layer's input, i.e. the stored output of the layer below, whose non-linearity is
+ * `act` and whose bias gradient is db; x and dx have type `out`; x may be NULL for DSK_ACT_NONE.  The result
+ * equals dsk_conv_bwd_data followed by dsk_act_bwd_bias(x, dx, db, N, C, H, W, act, out).  1 x 1 kernels with
+ * in == out write the error map once, from the epilogue of the matrix kernel; every other shape runs the two
+ * passes one after the other. */
+size_t dsk_conv_bwd_data_act_bias_workspace_bytes(int N, int C, int H, int W, int K, int kh, int kw, int d,
+                                                  dsk_dtype in, dsk_dtype out);
+int dsk_conv_bwd_data_act_bias(const void *dy, const float *w, const void *x, void *dx, float *db,
+                               int N, int C, int H, int W, int K, int kh, int kw, int d,
+                               dsk_dtype in, dsk_dtype out, dsk_act act,
+                               void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Last layer: masked softmax cross-entropy (pixel mask of Sec. 4.3)           */
 /* ------------------------------------------------------------------------- */

@@ -25,6 +25,7 @@ SYMBOLS = ("dsk_plan", "dsk_status_string", "dsk_pad_image", "dsk_conv_workspace
            "dsk_maxpool_fwd", "dsk_maxpool_bwd", "dsk_avgpool_fwd", "dsk_avgpool_bwd",
            "dsk_act_bwd", "dsk_act_bwd_bias_workspace_bytes", "dsk_act_bwd_bias",
            "dsk_pool_bwd_act_bias_workspace_bytes", "dsk_pool_bwd_act_bias",
+           "dsk_conv_bwd_data_act_bias_workspace_bytes", "dsk_conv_bwd_data_act_bias",
            "dsk_softmax_xent_workspace_bytes", "dsk_masked_softmax_xent", "dsk_masked_softmax_xent_static",
            "dsk_fs_pool_fwd", "dsk_fs_conv_fwd", "dsk_fs_assemble",
            "dsk_pad_video", "dsk_conv3d_workspace_bytes", "dsk_conv3d_fwd", "dsk_conv3d_bwd_data", "dsk_conv3d_bwd_weight",
@@ -81,6 +82,9 @@ def _load():
     lib.dsk_pool_bwd_act_bias_workspace_bytes.argtypes = [ci] * 8
     lib.dsk_pool_bwd_act_bias_workspace_bytes.restype = sz
     lib.dsk_pool_bwd_act_bias.argtypes = [ci, vp, vp, vp, vp, vp] + [ci] * 6 + [ci, ci, vp, sz, vp]
+    lib.dsk_conv_bwd_data_act_bias_workspace_bytes.argtypes = [ci] * 10
+    lib.dsk_conv_bwd_data_act_bias_workspace_bytes.restype = sz
+    lib.dsk_conv_bwd_data_act_bias.argtypes = [vp] * 5 + [ci] * 8 + [ci, ci, ci, vp, sz, vp]
     lib.dsk_softmax_xent_workspace_bytes.argtypes = [ci] * 4
     lib.dsk_softmax_xent_workspace_bytes.restype = sz
     lib.dsk_masked_softmax_xent.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
@@ -329,6 +333,33 @@ def dsk_pool_bwd_act_bias(kind, dy, argmax, y, k, d, H, W, act, dx=None, db=None
                                      None if act == DSK_ACT_NONE else _dev(y), _dev(dx), _dev(db, torch.float32),
                                      N, C, H, W, k, d, act, _dtype_code(dy), wsp, wsb, _stream()),
            "dsk_pool_bwd_act_bias")
+    return dx, db
+
+
+def dsk_conv_bwd_data_act_bias_workspace_bytes(N, C, H, W, K, kh, kw, d, in_code, out_code):
+    return int(lib.dsk_conv_bwd_data_act_bias_workspace_bytes(N, C, H, W, K, kh, kw, d, in_code, out_code))
+
+
+def dsk_conv_bwd_data_act_bias(dy, w, x, d, act, dx=None, db=None, ws=None):
+    """Backward-data of a conv layer, non-linearity backward of the conv layer below it (whose stored
+    output x is this layer's input) and that layer's bias gradient.  Returns (dx, db)."""
+    N, K, Ho, Wo = dy.shape
+    Kw, C, kh, kw = w.shape
+    _, Cx, H, W = x.shape
+    assert Kw == K and Cx == C and Ho == H - (kh - 1) * d and Wo == W - (kw - 1) * d
+    if dx is None:
+        dx = torch.empty((N, C, H, W), dtype=x.dtype, device=dy.device)
+    assert dx.dtype == x.dtype
+    if db is None:
+        db = torch.empty((C,), dtype=torch.float32, device=dy.device)
+    need = dsk_conv_bwd_data_act_bias_workspace_bytes(N, C, H, W, K, kh, kw, d, _dtype_code(dy), _dtype_code(dx))
+    if ws is None or ws.numel() * ws.element_size() < need:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dy.device)
+    wsp, wsb = _ws(ws)
+    _check(lib.dsk_conv_bwd_data_act_bias(_dev(dy), _dev(w, torch.float32), None if act == DSK_ACT_NONE else _dev(x),
+                                          _dev(dx), _dev(db, torch.float32), N, C, H, W, K, kh, kw, d,
+                                          _dtype_code(dy), _dtype_code(dx), act, wsp, wsb, _stream()),
+           "dsk_conv_bwd_data_act_bias")
     return dx, db
 
 

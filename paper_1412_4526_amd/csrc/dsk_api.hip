@@ -256,6 +256,43 @@ int dsk_conv_bwd_data(const void *dy, const float *w, void *dx,
     return dispatch_conv_bwd_data(dy, w, dx, s, in, out, ws, (hipStream_t)stream);
 }
 
+size_t dsk_conv_bwd_data_act_bias_workspace_bytes(int N, int C, int H, int W, int K, int kh, int kw, int d,
+                                                  dsk_dtype in, dsk_dtype out)
+{
+    ConvShape s;
+    if (conv_shape(N, C, H, W, K, kh, kw, d, &s) != DSK_OK || bad_dtype(in) || bad_dtype(out)) return 0;
+    size_t need = conv_ws_bytes(DSK_WS_CONV_BWD_DATA, s, in);
+    const size_t a = act_bwd_bias_ws_bytes(C);
+    if (a > need) need = a;
+    if (conv_bwd_data_act_fused(s, in, out)) {
+        const size_t f = conv_bwd_data_act_ws_bytes(s);
+        if (f > need) need = f;
+    }
+    return need;
+}
+
+int dsk_conv_bwd_data_act_bias(const void *dy, const float *w, const void *x, void *dx, float *db,
+                               int N, int C, int H, int W, int K, int kh, int kw, int d,
+                               dsk_dtype in, dsk_dtype out, dsk_act act, void *ws, size_t ws_bytes, void *stream)
+{
+    if (bad_ptr(dy) || bad_ptr(w) || bad_ptr(dx) || bad_ptr(db)) return DSK_EINVAL;
+    if (bad_dtype(in) || bad_dtype(out) || act < DSK_ACT_NONE || act > DSK_ACT_TANH) return DSK_EINVAL;
+    if (act != DSK_ACT_NONE && bad_ptr(x)) return DSK_EINVAL;
+    ConvShape s;
+    int rc = conv_shape(N, C, H, W, K, kh, kw, d, &s);
+    if (rc != DSK_OK) return rc;
+    const size_t need = dsk_conv_bwd_data_act_bias_workspace_bytes(N, C, H, W, K, kh, kw, d, in, out);
+    if (ws == nullptr || !aligned16(ws) || ws_bytes < need) return DSK_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    clear_errors();
+    if (g_conv_algo != 1 && conv_bwd_data_act_fused(s, in, out))
+        return launch_conv_bwd_data_act(dy, w, x, dx, db, s, out, act, ws, st);
+    // other shapes: the two passes one after the other
+    rc = dispatch_conv_bwd_data(dy, w, dx, s, in, out, ws, st);
+    if (rc != DSK_OK) return rc;
+    return launch_act_bwd_bias(x, dx, db, N, C, (long)H * W, act, out, ws, st);
+}
+
 int dsk_conv_bwd_weight(const void *x, const void *dy, float *dw, float *db,
                         int N, int C, int H, int W, int K, int kh, int kw, int d,
                         dsk_dtype in, void *ws, size_t ws_bytes, void *stream)

@@ -831,10 +831,26 @@ struct PwParams {
     const float *bias;   // may be null
     int N, Cin, Fout, act, Cpad, n_fgrp;
     long HW;             // pixels per plane, < 2^28
-    long n_wave;         // N * ceil(HW / 128)
+    long n_wave;         // N * ceil(HW / (32 NB))
+    // GATE (backward-data followed by the non-linearity backward of the layer below, Sec. 4.1):
+    const void *gate;    // that layer's stored output, same shape and type as `out` (unused for gact = none)
+    float *part;         // [n_wave][Cst]: per-wave sums of the stored values, for that layer's bias gradient
+    int gact, Cst;       // Cst = n_fgrp * TF
 };
 
-template <typename TI, typename TO, int WM>
+// Sum of 2H values per lane over the lanes that differ in `bit`: the lane with the bit clear keeps the
+// sums of the first H values, the other one those of the last H (each sends the half it gives up).
+template <int H>
+__device__ inline void pw_fold(float *v, bool up, int bit)
+{
+#pragma unroll
+    for (int j = 0; j < H; ++j) {
+        const float send = up ? v[j] : v[j + H], keep = up ? v[j + H] : v[j];
+        v[j] = keep + __shfl_xor(send, bit);
+    }
+}
+
+template <typename TI, typename TO, int WM, bool GATE, int NB>
 __global__ void __launch_bounds__(kThreads, 2)
 pw_conv_kernel(PwParams p)
 {
@@ -842,16 +858,16 @@ pw_conv_kernel(PwParams p)
     const int lane = threadIdx.x & 63, lo = lane & 31, hi = lane >> 5;
     const long wv = (long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (wv >= p.n_wave) return;
-    const long per_img = (p.HW + 127) / 128;
+    const long per_img = (p.HW + 32 * NB - 1) / (32 * NB);
     const int n = (int)(wv / per_img);
-    const unsigned q0 = (unsigned)(wv - n * per_img) * 128u;
+    const unsigned q0 = (unsigned)(wv - n * per_img) * (32u * NB);
     const unsigned HW = (unsigned)p.HW;
     const TI *in_n = (const TI *)p.in + (long)n * p.Cin * p.HW;
     const BufRsrc rin = buf_rsrc(in_n, in_n + (long)p.Cin * p.HW);
     // this lane's pixel of each of the four 32-pixel blocks; pixels beyond the plane read pixel 0
-    unsigned qoff[4];
+    unsigned qoff[NB];
 #pragma unroll
-    for (int wn = 0; wn < 4; ++wn) {
+    for (int wn = 0; wn < NB; ++wn) {
         const unsigned q = q0 + 32u * wn + lo;
         qoff[wn] = q < HW ? q : 0u;
     }
@@ -859,16 +875,16 @@ pw_conv_kernel(PwParams p)
     for (int fg = 0; fg < p.n_fgrp; ++fg) {
         const float *wg = p.wt + (long)fg * p.Cpad * TF;
         const BufRsrc rw = buf_rsrc(wg, wg + (long)p.Cpad * TF);
-        f32x16 acc[WM][4];
+        f32x16 acc[WM][NB];
 #pragma unroll
         for (int wm = 0; wm < WM; ++wm)
 #pragma unroll
-            for (int wn = 0; wn < 4; ++wn)
+            for (int wn = 0; wn < NB; ++wn)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[wm][wn][i] = 0.f;
-        float a_cur[KS][WM], b_cur[KS][4], a_nxt[KS][WM], b_nxt[KS][4];
+        float a_cur[KS][WM], b_cur[KS][NB], a_nxt[KS][WM], b_nxt[KS][NB];
         // channels at or beyond Cin meet zero weights; they are read from the last channel
-        auto fetch = [&](int c0, float (&a)[KS][WM], float (&b)[KS][4]) __attribute__((always_inline)) {
+        auto fetch = [&](int c0, float (&a)[KS][WM], float (&b)[KS][NB]) __attribute__((always_inline)) {
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 const int c = c0 + 2 * s;                      // lanes 32..63 take c + 1
@@ -876,7 +892,7 @@ pw_conv_kernel(PwParams p)
 #pragma unroll
                 for (int wm = 0; wm < WM; ++wm) a[s][wm] = buf_ld(rw, wg, (unsigned)(hi * TF + wm * 32 + lo), (unsigned)c * TF);
 #pragma unroll
-                for (int wn = 0; wn < 4; ++wn) b[s][wn] = buf_ld(rin, in_n, qoff[wn] + (hi ? co : ce) * HW, 0u);
+                for (int wn = 0; wn < NB; ++wn) b[s][wn] = buf_ld(rin, in_n, qoff[wn] + (hi ? co : ce) * HW, 0u);
             }
         };
         fetch(0, a_cur, b_cur);
@@ -888,19 +904,70 @@ pw_conv_kernel(PwParams p)
 #pragma unroll
                 for (int wm = 0; wm < WM; ++wm)
 #pragma unroll
-                    for (int wn = 0; wn < 4; ++wn)
+                    for (int wn = 0; wn < NB; ++wn)
                         acc[wm][wn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[s][wm], b_cur[s][wn], acc[wm][wn], 0, 0, 0);
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
 #pragma unroll
                 for (int wm = 0; wm < WM; ++wm) a_cur[s][wm] = a_nxt[s][wm];
 #pragma unroll
-                for (int wn = 0; wn < 4; ++wn) b_cur[s][wn] = b_nxt[s][wn];
+                for (int wn = 0; wn < NB; ++wn) b_cur[s][wn] = b_nxt[s][wn];
             }
         }
         // bias, non-linearity, store (register i of a lane: filter 8*(i/4) + i%4 + 4*hi of its block)
         TO *out_n = (TO *)p.out + ((long)n * p.Fout + (long)fg * TF) * p.HW;
         const int f_left = p.Fout - fg * TF;
+        if constexpr (GATE) {
+            // out = acc * act'(gate), and the sum of what is stored over this wave's 128 pixels, per filter
+            const TO *y_n = (const TO *)p.gate + ((long)n * p.Fout + (long)fg * TF) * p.HW;
+            const BufRsrc ry = buf_rsrc(y_n, y_n + (p.gact != DSK_ACT_NONE ? (long)f_left * p.HW : 0));   // filters beyond the last read 0
+            float sum[WM * 16];
+#pragma unroll
+            for (int i = 0; i < WM * 16; ++i) sum[i] = 0.f;
+#pragma unroll
+            for (int wn = 0; wn < NB; ++wn) {
+                const unsigned q = q0 + 32u * wn + lo;
+                float yv[WM][16];
+                if (p.gact != DSK_ACT_NONE) {
+#pragma unroll
+                    for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            yv[wm][i] = buf_ld(ry, y_n, qoff[wn] + (hi ? 4u * HW : 0u), (unsigned)(wm * 32 + 8 * (i / 4) + (i % 4)) * HW);
+                }
+                TO *o = out_n + q + (hi ? 4 * p.HW : 0);
+#pragma unroll
+                for (int wm = 0; wm < WM; ++wm)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int fl = wm * 32 + 8 * (i / 4) + (i % 4);
+                        float g = acc[wm][wn][i];      // zero for filters beyond the last (zero weights)
+                        if (p.gact == DSK_ACT_RELU) g = yv[wm][i] > 0.f ? g : 0.f;
+                        else if (p.gact == DSK_ACT_TANH) g *= 1.f - yv[wm][i] * yv[wm][i];
+                        g = round_w<TO>(g);            // the sum is over what the weight gradient will read
+                        if (q < HW) {
+                            if (fl + 4 * hi < f_left) stf(o, (long)fl * p.HW, g);
+                            sum[wm * 16 + i] += g;
+                        }
+                    }
+            }
+            // over the 32 pixels of a half wave: lane lo ends with the sum of register lo (WM = 1: lo / 2)
+            int idx;
+            if constexpr (WM == 2) {
+                pw_fold<16>(sum, lo & 16, 16); pw_fold<8>(sum, lo & 8, 8); pw_fold<4>(sum, lo & 4, 4);
+                pw_fold<2>(sum, lo & 2, 2); pw_fold<1>(sum, lo & 1, 1);
+                idx = lo;
+            } else {
+                pw_fold<8>(sum, lo & 16, 16); pw_fold<4>(sum, lo & 8, 8); pw_fold<2>(sum, lo & 4, 4);
+                pw_fold<1>(sum, lo & 2, 2);
+                sum[0] += __shfl_xor(sum[0], 1);
+                idx = lo >> 1;
+            }
+            const int i = idx & 15;
+            if (WM == 2 || (lo & 1) == 0)
+                p.part[wv * p.Cst + fg * TF + (idx >> 4) * 32 + 8 * (i / 4) + (i % 4) + 4 * hi] = sum[0];
+            continue;
+        }
         // this lane's biases, fetched together before the first store (see gc_epilogue)
         float bv[WM][16];
         {
@@ -916,7 +983,7 @@ pw_conv_kernel(PwParams p)
                 for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(bv[wm][i]));
         }
 #pragma unroll
-        for (int wn = 0; wn < 4; ++wn) {
+        for (int wn = 0; wn < NB; ++wn) {
             const unsigned q = q0 + 32u * wn + lo;
             if (q >= HW) continue;
             TO *o = out_n + q + (hi ? 4 * p.HW : 0);
@@ -933,15 +1000,19 @@ pw_conv_kernel(PwParams p)
 
 struct PwPlan {
     bool ok;
-    int WM, TF, n_fgrp, Cpad;
+    int WM, NB, TF, n_fgrp, Cpad;      // NB: 32-pixel blocks per wave
     size_t wt_bytes;
 };
 
-static PwPlan pw_plan(int Cin, int Fout, long HW, int kh, int kw)
+static PwPlan pw_plan(int Cin, int Fout, long HW, int kh, int kw, bool gated = false)
 {
     PwPlan g{};
     if (kh != 1 || kw != 1 || HW >= (1L << 28) || (long)Cin * HW >= (1L << 30)) return g;
-    g.WM = Fout > 32 ? 2 : 1;
+    // the gated form is bound by the latency of its loads: 32-filter tiles need fewer registers, so three waves
+    // per SIMD instead of two (2.86 -> 2.63 ms on a 33 -> 256 layer over 4 x 1024 x 1024 pixels; 64-pixel waves
+    // on top of that lose again on bf16 maps, whose rows of 32 pixels are only 64 bytes)
+    g.WM = Fout > 32 && !gated ? 2 : 1;
+    g.NB = 4;
     g.TF = g.WM * 32;
     g.n_fgrp = (Fout + g.TF - 1) / g.TF;
     g.Cpad = (Cin + kPwCh - 1) / kPwCh * kPwCh;
@@ -950,21 +1021,78 @@ static PwPlan pw_plan(int Cin, int Fout, long HW, int kh, int kw)
     return g;
 }
 
-template <typename TI, typename TO>
+template <typename TI, typename TO, bool GATE = false>
 static void pw_launch(const PwParams &p, int WM, hipStream_t st)
 {
     const unsigned grid = (unsigned)((p.n_wave + 3) / 4);
-    if (WM == 2) pw_conv_kernel<TI, TO, 2><<<dim3(grid), dim3(kThreads), 0, st>>>(p);
-    else pw_conv_kernel<TI, TO, 1><<<dim3(grid), dim3(kThreads), 0, st>>>(p);
+    if constexpr (GATE) pw_conv_kernel<TI, TO, 1, true, 4><<<dim3(grid), dim3(kThreads), 0, st>>>(p);
+    else if (WM == 2) pw_conv_kernel<TI, TO, 2, false, 4><<<dim3(grid), dim3(kThreads), 0, st>>>(p);
+    else pw_conv_kernel<TI, TO, 1, false, 4><<<dim3(grid), dim3(kThreads), 0, st>>>(p);
+}
+
+// The per-wave sums of the gated kernel, added up in a fixed order: 128 waves per workgroup, then the groups.
+static constexpr int kPwSumRows = 128;
+
+__global__ void __launch_bounds__(kThreads)
+pw_gate_sum_kernel(const float *__restrict__ part, float *__restrict__ part2, long n_wave, int Cst)
+{
+    const int f = blockIdx.y * kThreads + threadIdx.x;
+    if (f >= Cst) return;
+    const long r0 = (long)blockIdx.x * kPwSumRows, r1 = r0 + kPwSumRows < n_wave ? r0 + kPwSumRows : n_wave;
+    float acc = 0.f;
+    for (long r = r0; r < r1; ++r) acc += part[r * Cst + f];
+    part2[(long)blockIdx.x * Cst + f] = acc;
+}
+
+__global__ void __launch_bounds__(kThreads)
+pw_gate_sum2_kernel(const float *__restrict__ part2, float *__restrict__ db, int n_grp, int Cst, int Fout)
+{
+    const int f = blockIdx.x * kThreads + threadIdx.x;
+    if (f >= Fout) return;
+    float acc = 0.f;
+    for (int g = 0; g < n_grp; ++g) acc += part2[(long)g * Cst + f];
+    db[f] = acc;
+}
+
+// workspace of the gated call: weights | per-wave sums | per-group sums
+struct PwGatePlan {
+    bool ok;
+    PwPlan g;
+    long n_wave;
+    int n_grp, Cst;
+    size_t part_off, part2_off, bytes;
+};
+
+static PwGatePlan pw_gate_plan(int N, int Cin, int Fout, long HW, int kh, int kw)
+{
+    PwGatePlan q{};
+    q.g = pw_plan(Cin, Fout, HW, kh, kw, true);
+    if (!q.g.ok) return q;
+    q.n_wave = (long)N * ((HW + 32 * q.g.NB - 1) / (32 * q.g.NB));
+    if ((q.n_wave + 3) / 4 > 0x7fffffffL) return q;
+    const long grp = (q.n_wave + kPwSumRows - 1) / kPwSumRows;
+    if (grp > 0x7fffffffL) return q;
+    q.n_grp = (int)grp;
+    q.Cst = q.g.n_fgrp * q.g.TF;
+    q.part_off = q.g.wt_bytes;
+    q.part2_off = q.part_off + ((4 * (size_t)q.n_wave * q.Cst + 255) & ~(size_t)255);
+    q.bytes = q.part2_off + ((4 * (size_t)q.n_grp * q.Cst + 255) & ~(size_t)255);
+    q.ok = true;
+    return q;
 }
 
 // K, C: dimensions of w; flip = 1 for backward-data (GEMM channels = filters of w)
+// db != null: the gated form (tin == tout): out = (W^T in) * gact'(gate), db = sums of out per plane
 static int pw_run(const void *in, void *out, const float *w, const float *bias, int N, int Cin, int Fout, long HW,
-                  int act, int flip, int K, int C, dsk_dtype tin, dsk_dtype tout, void *ws, hipStream_t st)
+                  int act, int flip, int K, int C, dsk_dtype tin, dsk_dtype tout, void *ws, hipStream_t st,
+                  const void *gate = nullptr, float *db = nullptr, int gact = DSK_ACT_NONE)
 {
-    const PwPlan g = pw_plan(Cin, Fout, HW, 1, 1);
+    const PwPlan g = pw_plan(Cin, Fout, HW, 1, 1, db != nullptr);
     if (!g.ok) return DSK_ESHAPE;
-    if (((long)N * ((HW + 127) / 128) + 3) / 4 > 0x7fffffffL) return DSK_ESHAPE;      // before anything is launched
+    const PwGatePlan gp = db ? pw_gate_plan(N, Cin, Fout, HW, 1, 1) : PwGatePlan{};
+    if (db && (!gp.ok || tin != tout)) return DSK_ESHAPE;
+    const long n_wave = (long)N * ((HW + 32 * g.NB - 1) / (32 * g.NB));
+    if ((n_wave + 3) / 4 > 0x7fffffffL) return DSK_ESHAPE;      // before anything is launched
     float *wt = (float *)ws;
     const long total = (long)g.n_fgrp * g.Cpad * g.TF;
     gc_weight_prep_kernel<<<dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
@@ -972,8 +1100,19 @@ static int pw_run(const void *in, void *out, const float *w, const float *bias, 
     PwParams p{};
     p.in = in; p.out = out; p.wt = wt; p.bias = bias;
     p.N = N; p.Cin = Cin; p.Fout = Fout; p.act = act; p.Cpad = g.Cpad; p.n_fgrp = g.n_fgrp;
-    p.HW = HW; p.n_wave = (long)N * ((HW + 127) / 128);
-    if ((p.n_wave + 3) / 4 > 0x7fffffffL) return DSK_ESHAPE;
+    p.HW = HW; p.n_wave = n_wave;
+    if (db) {
+        p.gate = gate; p.gact = gact; p.Cst = gp.Cst;
+        p.part = (float *)((char *)ws + gp.part_off);
+        float *part2 = (float *)((char *)ws + gp.part2_off);
+        if (tin == DSK_F32) pw_launch<float, float, true>(p, g.WM, st);
+        else pw_launch<bf16, bf16, true>(p, g.WM, st);
+        pw_gate_sum_kernel<<<dim3((unsigned)gp.n_grp, (unsigned)((gp.Cst + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+            p.part, part2, gp.n_wave, gp.Cst);
+        pw_gate_sum2_kernel<<<dim3((unsigned)((Fout + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
+            part2, db, gp.n_grp, gp.Cst, Fout);
+        return check_launch();
+    }
     if (tin == DSK_F32 && tout == DSK_F32) pw_launch<float, float>(p, g.WM, st);
     else if (tin == DSK_F32 && tout == DSK_BF16) pw_launch<float, bf16>(p, g.WM, st);
     else if (tin == DSK_BF16 && tout == DSK_BF16) pw_launch<bf16, bf16>(p, g.WM, st);
@@ -1824,6 +1963,25 @@ int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const Co
         return pw_run(dy, dx, w, nullptr, s.N, s.K, s.C, (long)s.H * s.W, DSK_ACT_NONE, 1, s.K, s.C, in, out, ws, st);
     return gc_run(dy, dx, w, nullptr, s.N, s.K, s.Ho, s.Wo, s.C, s.H, s.W, s.kh, s.kw, s.d, 1, DSK_ACT_NONE, 1,
                   s.K, s.C, in, out, ws, st, s);
+}
+
+// Backward-data with the non-linearity backward and the bias gradient of the layer below in its epilogue:
+// 1 x 1 layers on plain 2-D maps of one type (the error map is then written once instead of written, read and rewritten).
+bool conv_bwd_data_act_fused(const ConvShape &s, dsk_dtype in, dsk_dtype out)
+{
+    return in == out && plain_call(s) && conv_mfma_supported(DSK_WS_CONV_BWD_DATA, s, in, out) &&
+           pw_gate_plan(s.N, s.K, s.C, (long)s.H * s.W, s.kh, s.kw).ok;
+}
+
+size_t conv_bwd_data_act_ws_bytes(const ConvShape &s)
+{
+    return pw_gate_plan(s.N, s.K, s.C, (long)s.H * s.W, s.kh, s.kw).bytes;
+}
+
+int launch_conv_bwd_data_act(const void *dy, const float *w, const void *x, void *dx, float *db, const ConvShape &s,
+                             dsk_dtype t, int act, void *ws, hipStream_t st)
+{
+    return pw_run(dy, dx, w, nullptr, s.N, s.K, s.C, (long)s.H * s.W, DSK_ACT_NONE, 1, s.K, s.C, t, t, ws, st, x, db, act);
 }
 
 int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,

@@ -138,6 +138,11 @@ int launch_conv_bwd_data_mfma(const void *dy, const float *w, void *dx, const Co
                               dsk_dtype in, dsk_dtype out, void *ws, hipStream_t st);
 int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float *db, const ConvShape &s,
                                 dsk_dtype in, void *ws, hipStream_t st);
+// backward-data of a 1 x 1 layer with the non-linearity backward and bias gradient of the layer below in its epilogue
+bool conv_bwd_data_act_fused(const ConvShape &s, dsk_dtype in, dsk_dtype out);
+size_t conv_bwd_data_act_ws_bytes(const ConvShape &s);
+int launch_conv_bwd_data_act(const void *dy, const float *w, const void *x, void *dx, float *db, const ConvShape &s,
+                             dsk_dtype t, int act, void *ws, hipStream_t st);
 
 // kernel choice for one 2-D convolution call, as the entry points make it (dsk_api.hip)
 int dispatch_conv_fwd(const void *x, const float *w, const float *b, void *y, const ConvShape &s, dsk_dtype in,

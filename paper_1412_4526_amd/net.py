@@ -95,6 +95,10 @@ class WholeImageNet(GraphReplay):
             ws_bytes = max([ws_bytes] + [B.dsk_act_bwd_bias_workspace_bytes(p.K) for p in self.plan])
             ws_bytes = max([ws_bytes] + [B.dsk_pool_bwd_act_bias_workspace_bytes(p.kind, N, p.C, p.H, p.W, p.k, p.d, self.code)
                                          for p in self.plan if p.kind != B.DSK_CONV])
+            ws_bytes = max([ws_bytes] + [B.dsk_conv_bwd_data_act_bias_workspace_bytes(N, p.C, p.H, p.W, p.K, p.k, p.k, p.d,
+                                                                                      self.code, self.code)
+                                         for l, p in enumerate(self.plan)
+                                         if l > 0 and p.kind == B.DSK_CONV and self.plan[l - 1].kind == B.DSK_CONV])
             self.loss = torch.zeros((1,), dtype=torch.float32, device=dev)
             self.dw = [torch.empty_like(w) for w in self.weights]
             self.db = [torch.empty_like(b) for b in self.biases]
@@ -169,7 +173,13 @@ class WholeImageNet(GraphReplay):
                 act_done = False
                 self._timed("conv_bwd_weight", l, B.dsk_conv_bwd_weight, x, g, p.k, p.k, p.d, dw=self.dw[ci],
                             want_db=False, ws=self.ws)
-                if l > 0:        # nobody needs the error map of the image itself
+                if l > 0 and self.plan[l - 1].kind == B.DSK_CONV and self.fuse:
+                    # the error map of the conv layer below, through that layer's non-linearity, and its bias
+                    # gradient (x is that layer's output)
+                    self._timed("conv_bwd_data_act", l, B.dsk_conv_bwd_data_act_bias, g, self.weights[ci], x, p.d,
+                                self.plan[l - 1].act, dx=gin, db=self.db[ci - 1], ws=self.ws)
+                    act_done = True
+                elif l > 0:      # nobody needs the error map of the image itself
                     self._timed("conv_bwd_data", l, B.dsk_conv_bwd_data, g, self.weights[ci], p.d, p.H, p.W,
                                 dx=gin, ws=self.ws)
                 ci -= 1

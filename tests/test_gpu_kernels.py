@@ -110,6 +110,83 @@ def test_conv_bwd(case, algo):
     assert torch.equal(dw, dw2) and torch.equal(db, db2), "bwd_weight is not run-to-run deterministic"
 
 
+def _oracle_pair_bwd(x0, bA, actA, w, d, dy):
+    """Two conv layers with no pool in between: A = 1x1 with identity weights, bias bA and non-linearity actA
+    (so its stored output is actA(x0 + bA) and the error at its input equals the error behind its non-linearity),
+    B = the layer under test (weights w, spacing d, no non-linearity).  Returns (error map behind A's
+    non-linearity, A's bias gradient) for the error dy at B's output."""
+    from workloads import Net, conv, maxpool
+    N, C, H, W = x0.shape
+    K, _, k, _ = w.shape
+    layers = ((maxpool(1, d),) if d > 1 else ()) + (conv(C, 1, 1, actA), conv(K, k, 1, 0))
+    net = Net("pair", C, 1 + (k - 1) * d, layers)
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    n, i, j = np.meshgrid(np.arange(N), np.arange(Ho), np.arange(Wo), indexing="ij")
+    pix = np.stack([n.ravel(), i.ravel(), j.ravel()], 1).astype(np.int32)
+    eye = np.eye(C, dtype=np.float32).reshape(C, C, 1, 1)
+    params = oracle.pack_params([eye, w], [bA, np.zeros(K, np.float32)])
+    delta = np.asarray(dy, np.float64).transpose(0, 2, 3, 1).reshape(-1, K)
+    g, dx = oracle.scan_backward(net, params, x0, pix, delta, want_dx=True)
+    _, dbs = oracle.unpack_params(net, g)
+    return dx, dbs[0]
+
+
+# (N, C, H, W, K, k, d, act of the layer below)
+PAIR_CASES = [
+    (1, 64, 37, 70, 33, 1, 1, 1),      # one group of 64 channels
+    (2, 150, 50, 61, 20, 1, 1, 1),     # three channel groups, the last one ragged; planes not a multiple of 128 pixels
+    (3, 20, 9, 13, 70, 1, 2, 2),       # at most 32 channels (one 32-block), planes smaller than a wave's 128 pixels, tanh
+    (1, 256, 40, 40, 33, 1, 1, 0),     # no non-linearity below: the bias gradient alone
+    (1, 40, 130, 141, 33, 1, 1, 1),    # more than 128 waves: two groups of per-wave sums
+    (2, 8, 40, 37, 16, 3, 2, 1),       # 3x3: the two passes one after the other
+    (1, 16, 30, 45, 10, 2, 4, 2),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("algo", [0, 1], ids=["auto", "direct"])
+@pytest.mark.parametrize("case", PAIR_CASES, ids=lambda c: "N%dC%dH%dW%dK%dk%dd%da%d" % c)
+def test_conv_bwd_data_act_bias(case, algo, dtype):
+    """Backward-data with the non-linearity backward and bias gradient of the conv layer below (Sec. 4.1)
+    against the oracle's two-layer network, and bit for bit against the two separate calls."""
+    N, C, H, W, K, k, d, act = case
+    _say("conv_bwd_data_act_bias", case, "algo", algo, dtype)
+    bf = dtype == "bf16"
+    td = torch.bfloat16 if bf else torch.float32
+    rnd = (lambda a: bf16_round(a).astype(np.float32)) if bf else (lambda a: np.asarray(a, np.float32))
+    rng = np.random.default_rng(hash(case) % 2**31 + 5)
+    x0 = rnd(rng.uniform(-1, 1, (N, C, H, W)))
+    bA = (rng.standard_normal(C) * 0.2).astype(np.float32)
+    w = rnd(rng.standard_normal((K, C, k, k)) * np.sqrt(2.0 / (C * k * k)))
+    Ho, Wo = H - (k - 1) * d, W - (k - 1) * d
+    dy = rng.standard_normal((N, K, Ho, Wo)).astype(np.float32)
+    dy[rng.random(dy.shape) < 0.5] = 0.0
+    dy = rnd(dy)
+    rdx, rdb = _oracle_pair_bwd(x0, bA, act, w, d, dy)
+    prev = dsk.dsk_set_conv_algo(algo)
+    try:
+        eye = torch.eye(C, device=DEV).reshape(C, C, 1, 1).contiguous()
+        x = dsk.dsk_conv_fwd(_t(x0, td), eye, _t(bA), 1, act)        # the stored output of the layer below
+        g, wt = _t(dy, td), _t(w)
+        dx, db = dsk.dsk_conv_bwd_data_act_bias(g, wt, x, d, act)
+        dx2 = dsk.dsk_conv_bwd_data(g, wt, d, H, W)
+        db2 = dsk.dsk_act_bwd_bias(x, dx2, act)
+        dx3, db3 = dsk.dsk_conv_bwd_data_act_bias(g, wt, x, d, act)
+        torch.cuda.synchronize()
+    finally:
+        dsk.dsk_set_conv_algo(prev)
+    assert dx.dtype == td and db.dtype == torch.float32
+    assert_close(dx, rdx, "dx behind the non-linearity", bf16=bf)
+    assert_close(db, rdb, "db of the layer below", bf16=bf)
+    assert torch.equal(dx, dx3) and torch.equal(db, db3), "not run-to-run deterministic"
+    if k > 1 or algo == 1 or (not bf and act != 2):
+        # the same kernels (fp32: the 1x1 kernel with and without the epilogue), so the same bits in dx
+        assert torch.equal(dx, dx2), "differs from the two separate calls"
+    else:
+        assert_close(dx, to_np(dx2), "dx against the two separate calls", bf16=bf)
+    assert_close(db, to_np(db2), "db against the two separate calls", bf16=bf)
+
+
 # More output tiles than the 512 workgroups the chip holds at once, and not a multiple of it:
 # persistent workgroups take whole tiles first and share the channel chunks of the rest.
 SPLIT_CASES = [

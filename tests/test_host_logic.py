@@ -147,6 +147,19 @@ def test_pool_act_loss_argument_errors():
     assert L.dsk_act_bwd_bias(P, P, P, 1, 7, 8, 8, 1, 0, None, 0, None) == dsk.DSK_EWORKSPACE
     assert L.dsk_act_bwd_bias(None, P, P, 1, 7, 8, 8, 1, 0, P, nb, None) == dsk.DSK_EINVAL   # y needed for ReLU
     assert L.dsk_act_bwd_bias(P, P, None, 1, 7, 8, 8, 0, 0, P, nb, None) == dsk.DSK_EINVAL
+    # backward-data with the backward of the conv layer below: 1 x 1 (one pass) and 3 x 3 (two passes)
+    for dims in ((1, 40, 16, 16, 7, 1, 1, 1), (1, 3, 16, 16, 4, 3, 3, 2)):
+        nw = L.dsk_conv_bwd_data_act_bias_workspace_bytes(*dims, 0, 0)
+        assert nw >= max(L.dsk_conv_workspace_bytes(1, *dims, 0), L.dsk_act_bwd_bias_workspace_bytes(dims[1])) > 0
+        q = lambda *a: L.dsk_conv_bwd_data_act_bias(*a)
+        assert q(P, P, P, P, P, *dims, 0, 0, 1, None, 0, None) == dsk.DSK_EWORKSPACE
+        assert q(P, P, P, P, P, *dims, 0, 0, 1, P, nw - 1, None) == dsk.DSK_EWORKSPACE
+        assert q(P, P, None, P, P, *dims, 0, 0, 1, P, nw, None) == dsk.DSK_EINVAL        # x needed for ReLU
+        assert q(P, P, P, P, None, *dims, 0, 0, 0, P, nw, None) == dsk.DSK_EINVAL        # db required
+        assert q(P, P, P, P, P, *dims, 0, 0, 5, P, nw, None) == dsk.DSK_EINVAL           # bad act
+        assert q(P, P, P, P, P, *dims, 0, 3, 1, P, nw, None) == dsk.DSK_EINVAL           # bad dtype
+    assert L.dsk_conv_bwd_data_act_bias(P, P, P, P, P, 1, 3, 16, 16, 4, 9, 3, 2, 0, 0, 1, P, 1 << 20, None) == dsk.DSK_ESHAPE
+    assert L.dsk_conv_bwd_data_act_bias_workspace_bytes(1, 3, 16, 16, 4, 3, 3, 8, 0, 0) == 0      # invalid -> 0
     need = L.dsk_softmax_xent_workspace_bytes(1, 5, 8, 8)
     assert need > 0
     assert L.dsk_masked_softmax_xent(P, P, P, P, P, 0, 1, 5, 8, 8, None, 0, None) == dsk.DSK_EWORKSPACE

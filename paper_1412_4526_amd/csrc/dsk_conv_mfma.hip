@@ -1030,28 +1030,25 @@ static void pw_launch(const PwParams &p, int WM, hipStream_t st)
     else pw_conv_kernel<TI, TO, 1, false, 4><<<dim3(grid), dim3(kThreads), 0, st>>>(p);
 }
 
-// The per-wave sums of the gated kernel, added up in a fixed order: 128 waves per workgroup, then the groups.
+// The per-wave sums of the gated kernel, added up in a fixed order: 128 rows per workgroup, then the groups.
+// A workgroup takes 64 columns; its four waves take every fourth row of its share (a wave reads 256 contiguous
+// bytes of a row) and their sums meet in LDS.
 static constexpr int kPwSumRows = 128;
 
 __global__ void __launch_bounds__(kThreads)
-pw_gate_sum_kernel(const float *__restrict__ part, float *__restrict__ part2, long n_wave, int Cst)
+pw_gate_sum_kernel(const float *__restrict__ src, float *__restrict__ dst, long n_rows, long rows_per_block, int stride,
+                   int n_cols, long dst_stride)
 {
-    const int f = blockIdx.y * kThreads + threadIdx.x;
-    if (f >= Cst) return;
-    const long r0 = (long)blockIdx.x * kPwSumRows, r1 = r0 + kPwSumRows < n_wave ? r0 + kPwSumRows : n_wave;
+    __shared__ float sm[4][64];
+    const int c = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int f = blockIdx.y * 64 + c;
+    const long r0 = (long)blockIdx.x * rows_per_block, r1 = r0 + rows_per_block < n_rows ? r0 + rows_per_block : n_rows;
     float acc = 0.f;
-    for (long r = r0; r < r1; ++r) acc += part[r * Cst + f];
-    part2[(long)blockIdx.x * Cst + f] = acc;
-}
-
-__global__ void __launch_bounds__(kThreads)
-pw_gate_sum2_kernel(const float *__restrict__ part2, float *__restrict__ db, int n_grp, int Cst, int Fout)
-{
-    const int f = blockIdx.x * kThreads + threadIdx.x;
-    if (f >= Fout) return;
-    float acc = 0.f;
-    for (int g = 0; g < n_grp; ++g) acc += part2[(long)g * Cst + f];
-    db[f] = acc;
+    if (f < n_cols)
+        for (long r = r0 + w; r < r1; r += 4) acc += src[r * stride + f];
+    sm[w][c] = acc;
+    __syncthreads();
+    if (w == 0 && f < n_cols) dst[(long)blockIdx.x * dst_stride + f] = (sm[0][c] + sm[1][c]) + (sm[2][c] + sm[3][c]);
 }
 
 // workspace of the gated call: weights | per-wave sums | per-group sums
@@ -1107,10 +1104,10 @@ static int pw_run(const void *in, void *out, const float *w, const float *bias, 
         float *part2 = (float *)((char *)ws + gp.part2_off);
         if (tin == DSK_F32) pw_launch<float, float, true>(p, g.WM, st);
         else pw_launch<bf16, bf16, true>(p, g.WM, st);
-        pw_gate_sum_kernel<<<dim3((unsigned)gp.n_grp, (unsigned)((gp.Cst + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
-            p.part, part2, gp.n_wave, gp.Cst);
-        pw_gate_sum2_kernel<<<dim3((unsigned)((Fout + kThreads - 1) / kThreads)), dim3(kThreads), 0, st>>>(
-            part2, db, gp.n_grp, gp.Cst, Fout);
+        pw_gate_sum_kernel<<<dim3((unsigned)gp.n_grp, (unsigned)((gp.Cst + 63) / 64)), dim3(kThreads), 0, st>>>(
+            p.part, part2, gp.n_wave, kPwSumRows, gp.Cst, gp.Cst, gp.Cst);
+        pw_gate_sum_kernel<<<dim3(1u, (unsigned)((Fout + 63) / 64)), dim3(kThreads), 0, st>>>(
+            part2, db, gp.n_grp, gp.n_grp, gp.Cst, Fout, 0);
         return check_launch();
     }
     if (tin == DSK_F32 && tout == DSK_F32) pw_launch<float, float>(p, g.WM, st);

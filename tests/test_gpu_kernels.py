@@ -249,6 +249,13 @@ def test_conv_workspace_is_enough_and_respected(case):
             dsk.dsk_conv_bwd_weight(x, dy, k, k, d, ws=ws)
         torch.cuda.synchronize()
         assert bool((buf[need16:] == 0xA5).all()), "write beyond the workspace (call %d)" % which
+    # backward-data with the backward of a conv layer below (per-wave bias sums behind the weights for 1x1 kernels)
+    need = dsk.dsk_conv_bwd_data_act_bias_workspace_bytes(N, C, H, W, K, k, k, d, dsk.DSK_F32, dsk.DSK_F32)
+    need16 = (need + 15) // 16 * 16
+    buf = torch.full((need16 + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    dsk.dsk_conv_bwd_data_act_bias(dy, w, x, d, dsk.DSK_ACT_RELU, ws=buf[:max(need16, 16)])
+    torch.cuda.synchronize()
+    assert bool((buf[need16:] == 0xA5).all()), "write beyond the workspace (backward-data with the layer below)"
 
 
 BF16_CASES = [

@@ -187,6 +187,31 @@ def test_conv_bwd_data_act_bias(case, algo, dtype):
     assert_close(db, to_np(db2), "db against the two separate calls", bf16=bf)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_conv_bwd_data_act_bias_random_1x1(seed):
+    """The one-pass form on seeded random 1x1 layers: channel counts around the 32-channel groups, planes that end
+    inside a wave's 128 pixels, one to three images, every non-linearity, both storage types."""
+    r = np.random.default_rng(4000 + seed)
+    C = int(r.choice([1, 7, 31, 32, 33, 64, 65, 100, 129, 200]))
+    K = int(r.choice([1, 2, 5, 21, 33, 40, 64]))
+    N, H, W = int(r.integers(1, 4)), int(r.integers(1, 40)), int(r.integers(1, 90))
+    act, bf = int(r.integers(0, 3)), bool(seed % 2)
+    _say("conv_bwd_data_act_bias random", seed, (N, C, H, W, K, act), "bf16" if bf else "f32")
+    td = torch.bfloat16 if bf else torch.float32
+    rnd = (lambda a: bf16_round(a).astype(np.float32)) if bf else (lambda a: np.asarray(a, np.float32))
+    x0 = rnd(r.uniform(-1, 1, (N, C, H, W)))
+    bA = (r.standard_normal(C) * 0.2).astype(np.float32)
+    w = rnd(r.standard_normal((K, C, 1, 1)) * np.sqrt(2.0 / C))
+    dy = rnd(r.standard_normal((N, K, H, W)))
+    rdx, rdb = _oracle_pair_bwd(x0, bA, act, w, 1, dy)
+    eye = torch.eye(C, device=DEV).reshape(C, C, 1, 1).contiguous()
+    x = dsk.dsk_conv_fwd(_t(x0, td), eye, _t(bA), 1, act)
+    dx, db = dsk.dsk_conv_bwd_data_act_bias(_t(dy, td), _t(w), x, 1, act)
+    torch.cuda.synchronize()
+    assert_close(dx, rdx, "dx behind the non-linearity", bf16=bf)
+    assert_close(db, rdb, "db of the layer below", bf16=bf)
+
+
 # More output tiles than the 512 workgroups the chip holds at once, and not a multiple of it:
 # persistent workgroups take whole tiles first and share the channel chunks of the rest.
 SPLIT_CASES = [

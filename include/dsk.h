@@ -200,7 +200,9 @@ int dsk_pool_bwd_act_bias(int kind, const void *dy, const uint8_t *argmax, const
  * `act` and whose bias gradient is db; x and dx have type `out`; x may be NULL for DSK_ACT_NONE.  The result
  * equals dsk_conv_bwd_data followed by dsk_act_bwd_bias(x, dx, db, N, C, H, W, act, out).  1 x 1 kernels with
  * in == out write the error map once, from the epilogue of the matrix kernel; every other shape runs the two
- * passes one after the other. */
+ * passes one after the other.  db is required; a caller that uses this passes db = NULL to dsk_conv_bwd_weight
+ * of the layer below.  Workspace: dsk_conv_bwd_data_act_bias_workspace_bytes (enough for either form; 0 for an
+ * invalid shape).  Errors as for dsk_conv_bwd_data; the summation order is fixed (bit-identical repeats). */
 size_t dsk_conv_bwd_data_act_bias_workspace_bytes(int N, int C, int H, int W, int K, int kh, int kw, int d,
                                                   dsk_dtype in, dsk_dtype out);
 int dsk_conv_bwd_data_act_bias(const void *dy, const float *w, const void *x, void *dx, float *db,

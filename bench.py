@@ -108,6 +108,7 @@ def video_costs(net, elem):
             for tag in ("conv3d_fwd", "conv3d_bwd_data", "conv3d_bwd_weight"):
                 out[(tag, l)] = dict(flops=fl, bytes=nin * elem + nout * oel + wb)
             out[("act_bwd", l)] = dict(flops=0.0, bytes=3 * nout * oel)
+            out[("conv_bwd_data_act", l)] = dict(flops=fl, bytes=nout * oel + 2 * nin * elem + wb)
         elif p.kind == dsk.DSK_MAXPOOL:
             out[("maxpool3d_fwd", l)] = dict(flops=0.0, bytes=nin * elem + nout * (elem + 1))
             out[("maxpool3d_bwd", l)] = dict(flops=0.0, bytes=nout * (elem + 1) + nin * elem)

@@ -54,6 +54,9 @@ class WholeVideoNet(GraphReplay):
         if train:
             ws_bytes = max(ws_bytes, B.dsk_softmax_xent_workspace_bytes(N * T, self.plan[-1].K, H, W))
             ws_bytes = max([ws_bytes] + [B.dsk_act_bwd_bias_workspace_bytes(p.K) for p in self.plan])
+            ws_bytes = max([ws_bytes] + [B.dsk_conv_bwd_data_act_bias_workspace_bytes(N * q.H, p.C, p.H, p.W, p.K, 1, 1, p.d,
+                                                                                      self.code, self.code)
+                                         for l, (p, q) in enumerate(zip(self.plan, self.tplan)) if self._pointwise_pair(l)])
             self.loss = torch.zeros((1,), dtype=torch.float32, device=dev)
             self.dw = [torch.empty_like(w) for w in self.weights]
             self.db = [torch.empty_like(b) for b in self.biases]
@@ -61,6 +64,11 @@ class WholeVideoNet(GraphReplay):
             self._g = [torch.empty(biggest, dtype=self.act_dtype, device=dev) for _ in range(2)]
         self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
         self.timeline = None
+
+    def _pointwise_pair(self, l):
+        """Layer l is a 1x1x1 convolution directly on top of another convolution."""
+        p, q = self.plan[l], self.tplan[l]
+        return (l > 0 and p.kind == B.DSK_CONV and self.plan[l - 1].kind == B.DSK_CONV and p.k == 1 and q.k == 1)
 
     def _timed(self, tag, layer, fn, *a, **kw):
         if self.timeline is None:
@@ -109,16 +117,26 @@ class WholeVideoNet(GraphReplay):
                     mask.view(NT, self.H, self.W), loss=self.loss, dscores=g, ws=self.ws)
         g = g.view(self.scores.shape)
         ci = len(self.weights) - 1
+        act_done = False      # the error map in g already went through the non-linearity of the layer it belongs to
         for l in range(L - 1, -1, -1):
             p, q = self.plan[l], self.tplan[l]
             x, y = self.maps[l], self.maps[l + 1]
             gin = self._g[1 - cur][:x.numel()].view(x.shape) if l > 0 else None
             if p.kind == B.DSK_CONV:
                 flat = (y.shape[0] * y.shape[1],) + tuple(y.shape[2:])      # frames as a batch of images
-                self._timed("act_bwd", l, B.dsk_act_bwd_bias, y.view(flat), g.view(flat), p.act, db=self.db[ci], ws=self.ws)
+                if not act_done:
+                    self._timed("act_bwd", l, B.dsk_act_bwd_bias, y.view(flat), g.view(flat), p.act, db=self.db[ci], ws=self.ws)
+                act_done = False
                 self._timed("conv3d_bwd_weight", l, B.dsk_conv3d_bwd_weight, x, g, q.k, p.k, p.k, q.d, p.d,
                             dw=self.dw[ci], want_db=False, ws=self.ws)
-                if l > 0:
+                if self._pointwise_pair(l):
+                    # a 1x1x1 layer on top of a convolution: the frames are a batch of images, and the 2-D call writes
+                    # the error map behind the non-linearity of the layer below, and that layer's bias gradient, in one pass
+                    flatx = (x.shape[0] * x.shape[1],) + tuple(x.shape[2:])
+                    self._timed("conv_bwd_data_act", l, B.dsk_conv_bwd_data_act_bias, g.view(flat), self.weights[ci][0],
+                                x.view(flatx), p.d, self.plan[l - 1].act, dx=gin.view(flatx), db=self.db[ci - 1], ws=self.ws)
+                    act_done = True
+                elif l > 0:
                     self._timed("conv3d_bwd_data", l, B.dsk_conv3d_bwd_data, g, self.weights[ci], q.d, p.d,
                                 q.H, p.H, p.W, dx=gin, ws=self.ws)
                 ci -= 1

@@ -169,8 +169,15 @@ def _oracle_full(net, wl, vox=None):
     return xpad, params, scores
 
 
+# a 1x1x1 classifier on top of a fully connected layer (3 frames of 5 x 5 pixels): backward-data of the classifier
+# takes the 2-D call that also does the non-linearity backward and bias gradient of the layer below
+FC_VIDEO = VideoNet("fccube", 2, 3, 5, (
+    conv3(6, 3, 2, act=ACT_RELU),               # -> 2 x 3 x 3
+    conv3(40, 3, 2, act=ACT_TANH),              # -> 1 x 1 x 1
+    conv3(4, 1, 1)), init="n0.05")
+
 NET_CASES = [(TINY_VIDEO, 1, 5, 12, 14, 0.10), (TINY_VIDEO, 2, 3, 9, 70, 0.05), (STRIDED_VIDEO, 1, 4, 10, 9, 0.2),
-             (STRIDED_VIDEO, 2, 7, 6, 11, 0.1)]
+             (STRIDED_VIDEO, 2, 7, 6, 11, 0.1), (FC_VIDEO, 2, 4, 9, 13, 0.2)]
 
 
 @pytest.mark.parametrize("algo", [0, 1])

@@ -1147,6 +1147,11 @@ struct BwParams {
     int n_fblk, n_cblk;
     int bgroup, bskip;   // image n of x sits at slot n + n / bgroup * bskip (video layers; see ConvShape)
     long x_extent;       // readable elements of x
+    // A workgroup's next pixel tile is S tiles further on: S = (step_n * n_rowtile + step_rt) * n_coltile + step_ct,
+    // so that the tile's (image, row tile, column tile) follow by additions with carry instead of three divisions
+    // per tile, and d_magic = floor(2^32 / d) + 1 turns rt / d into one multiplication (rt, d < 2^16; unused for d = 1).
+    int step_ct, step_rt, step_n;
+    unsigned d_magic;
 };
 
 // TPW: accumulator tiles (taps) per wave; XR: rows of the x tile, at most.
@@ -1261,21 +1266,54 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     const int qx_r0 = lane / qG, qx_g0 = lane - qx_r0 * qG, qx_r1 = (lane + 64) / qG, qx_g1 = lane + 64 - qx_r1 * qG;
     const bool qx_ok0 = lane < p.xrows * qG, qx_ok1 = lane + 64 < p.xrows * qG;
     unsigned st_dmask = 0;                      // QUAD: bit j: column 4*qd_g + j of the staged dy tile lies inside the map
+    // STEP (the instances that prefetch, where this arithmetic sits between the barrier and the matrix instructions;
+    // the others measured slower with it, the scalar registers it holds being spilled): the coordinates of the next
+    // tile to load are kept and stepped instead of being divided out of the tile index.
+    constexpr bool STEP = PREFETCH && FB == 1;
+    int t_ct = 0, t_rt = 0, t_n = 0;
+    if (STEP) { t_ct = s % p.n_coltile; t_rt = (s / p.n_coltile) % p.n_rowtile; t_n = s / p.n_coltile / p.n_rowtile; }
+    auto advance = [&]() {
+        if (!STEP) return;
+        t_ct += p.step_ct;
+        const int carry = t_ct >= p.n_coltile ? 1 : 0;
+        t_ct -= carry ? p.n_coltile : 0;
+        t_rt += p.step_rt + carry;
+        const int carry2 = t_rt >= p.n_rowtile ? 1 : 0;
+        t_rt -= carry2 ? p.n_rowtile : 0;
+        t_n += p.step_n + carry2;
+    };
     auto load_tile = [&](long pt) {
-        const int ct = (int)(pt % p.n_coltile);
-        const int rt = (int)((pt / p.n_coltile) % p.n_rowtile);
-        const int n = (int)(pt / ((long)p.n_coltile * p.n_rowtile));
-        const int u0 = (rt / p.d) * p.d * PH + (rt % p.d);
+        int ct = t_ct, rt = t_rt, n = t_n, rq;
+        if constexpr (STEP) {
+            rq = p.d == 1 ? rt : (int)__umulhi((unsigned)rt, p.d_magic);      // rt / d
+        } else {
+            ct = (int)(pt % p.n_coltile);
+            rt = (int)((pt / p.n_coltile) % p.n_rowtile);
+            n = (int)(pt / ((long)p.n_coltile * p.n_rowtile));
+            rq = rt / p.d;
+        }
+        const int u0 = STEP ? rq * p.d * PH + (rt - rq * p.d) : (rt / p.d) * p.d * PH + (rt % p.d);
         const int v0 = ct * PW;
         const TI *dyt = dy + (((long)n * p.K + f_base) * p.Ho + u0) * p.Wo + v0;
         const long xn = p.bgroup ? n + (long)(n / p.bgroup) * p.bskip : (long)n;
         const TI *xt = x + ((xn * p.C + cb * 32) * p.H + u0) * p.W + v0 + col_shift;
         // dy: segment i of this wave is filter f_i, rows r_i (lanes 0-31) and r_i+1 (lanes 32-63)
-        st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;           // dy rows u0 + r*d that exist (>= 1)
         st_dcol_ok = v0 + lo < p.Wo;
         st_col_ok = lane < p.xcols && v0 + lane + col_shift < p.W;
         const unsigned xlane_off = st_col_ok ? (unsigned)lane : 0u;
-        st_nr_x = (p.H - u0 + p.d - 1) / p.d;             // x rows u0 + r*d that exist
+        if constexpr (STEP) {
+            // every row of both tiles exists (no division on this path: all but the tiles at the bottom of a map)
+            const bool rows_full = u0 + (PH - 1) * p.d < p.Ho && u0 + (p.xrows - 1) * p.d < p.H;
+            st_nr_dy = PH;
+            st_nr_x = p.xrows;
+            if (!rows_full) {
+                st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;       // dy rows u0 + r*d that exist (>= 1)
+                st_nr_x = (p.H - u0 + p.d - 1) / p.d;         // x rows u0 + r*d that exist
+            }
+        } else {
+            st_nr_dy = (p.Ho - u0 + p.d - 1) / p.d;
+            st_nr_x = (p.H - u0 + p.d - 1) / p.d;
+        }
         st_nr_x = st_nr_x < p.xrows ? st_nr_x : p.xrows;
         st_full = full_blocks && st_nr_dy >= PH && st_nr_x == p.xrows;
         if (st_full) {
@@ -1351,7 +1389,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
     };
 
     long pt = s;
-    if (PREFETCH && pt < p.n_ptile) load_tile(pt);
+    if (PREFETCH && pt < p.n_ptile) { load_tile(pt); advance(); }
     while (pt < p.n_ptile) {
         if (!PREFETCH) load_tile(pt);
         __syncthreads();        // every wave is done with the previous tile
@@ -1411,7 +1449,7 @@ conv_bwd_weight_mfma_kernel(BwParams p)
         }
         }
         __syncthreads();
-        if (PREFETCH && pt + p.S < p.n_ptile) load_tile(pt + p.S);      // in flight while the matrix cores run
+        if (PREFETCH && pt + p.S < p.n_ptile) { load_tile(pt + p.S); advance(); }      // in flight while the matrix cores run
         pt += p.S;
         // ---- matrix cores: k index = pixel pair (columns 2q, 2q+1); A = dy (filters), B = x (channels)
         // Steps of two pixel pairs (one two-address LDS read per operand).  The operands of step s+1 are read into
@@ -1860,6 +1898,7 @@ static BwPlan bw_plan_one(const ConvShape &s, bool allow_packb, dsk_dtype in)
     }
     b.n_coltile = (s.Wo + PW - 1) / PW;
     b.n_ptile = (long)s.N * b.n_rowtile * b.n_coltile;
+    if (b.n_rowtile >= 65536 || s.d >= 65536) return b;      // the kernel divides row-tile indices by d with a 32-bit multiplication
     const long blocks = (long)(b.fb2 ? (b.n_fblk + 1) / 2 : b.n_fblk) * b.n_cblk;
     long S = 2048 / blocks;
     if (S > (blocks == 1 ? 512 : 256)) S = blocks == 1 ? 512 : 256;      // (a single block: enough shares to fill every workgroup slot)
@@ -2021,6 +2060,10 @@ int launch_conv_bwd_weight_mfma(const void *x, const void *dy, float *dw, float 
     p.kh = s.kh; p.kw = kw_pass; p.d = s.d;
     p.Kp = b.Kp; p.Cp = b.Cp; p.xrows = b.xrows; p.xcols = b.xcols; p.xstride = b.xstride;
     p.n_rowtile = b.n_rowtile; p.n_coltile = b.n_coltile; p.n_ptile = b.n_ptile; p.S = b.S;
+    if (!b.bf16_cores) {      // (that kernel has its own tiles)
+        p.step_ct = b.S % b.n_coltile; p.step_rt = (b.S / b.n_coltile) % b.n_rowtile; p.step_n = b.S / b.n_coltile / b.n_rowtile;
+    }
+    p.d_magic = s.d > 1 ? (unsigned)((1ull << 32) / (unsigned)s.d + 1) : 0u;
     p.n_fblk = b.fb2 ? (b.n_fblk + 1) / 2 : b.n_fblk; p.n_cblk = b.n_cblk;
     p.n_pass = b.col_passes;
     p.bgroup = s.bgroup; p.bskip = s.bskip;
